@@ -1,0 +1,96 @@
+// Host-callable launchers of the stage's HIP kernels.  Internal to the library: the public
+// interface is include/bapipe_stage.h.  All tensors are NHWC in HBM; `dtype` selects the
+// storage type (0 = float, 1 = bf16) of activations, activation gradients and working
+// weights; master weights, weight gradients, statistics and losses are always float.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace bapipe {
+
+enum { DT_F32 = 0, DT_BF16 = 1 };
+inline size_t dt_size(int dt) { return dt == DT_F32 ? 4 : 2; }
+
+// out[n,oh,ow,ko] = sum_{r,s,ki} in[n,ih,iw,ki] * wt[ko][r][s][ki]  (+ bias[ko]),
+// ih = (oh*s_out + r - pad_h) / s_in when divisible and inside [0,Hi), same for iw.
+//   forward conv : in = x,  s_out = stride, s_in = 1,      pad = pad,       wt = w [K][R][S][C]
+//   dgrad        : in = dy, s_out = 1,      s_in = stride, pad = R-1-pad,   wt = flipped,
+//                  channel-transposed copy [C][R][S][K]
+struct GatherConv {
+    int N, Hi, Wi, Ci, Ho, Wo, Co, R, S, s_out, s_in, pad_h, pad_w;
+};
+
+// Forward-convolution geometry (x: N,H,W,C ; y: N,P,Q,K ; filter R x S).
+struct ConvShape {
+    int N, H, W, C, P, Q, K, R, S, stride, pad;
+};
+
+// Epilogue options of kernels that write an activation gradient (see grad_out()).
+struct GradEpi {
+    const void *gate;  // forward values deciding the producer's fused-ReLU mask, or NULL
+    int accum;         // add to what is already stored
+};
+
+// ---- direct (CUDA-core style) convolution: fp32 stages and shapes the MFMA path skips
+hipError_t conv_gather_direct(int dt, const void *in, const void *wt, const float *bias, void *out,
+                              int relu, GradEpi epi, const GatherConv &g, hipStream_t s);
+size_t conv_wgrad_direct_workspace(const ConvShape &c);
+hipError_t conv_wgrad_direct(int dt, const void *x, const void *dy, float *dw, void *workspace,
+                             const ConvShape &c, hipStream_t s);
+
+// ---- bf16 MFMA implicit-GEMM convolution (kernels_conv_mfma.hip)
+bool conv_gather_mfma_supported(const GatherConv &g);
+hipError_t conv_gather_mfma(const void *in, const void *wt, const float *bias, void *out, int relu,
+                            GradEpi epi, const GatherConv &g, hipStream_t s);
+bool conv_wgrad_mfma_supported(const ConvShape &c);
+size_t conv_wgrad_mfma_workspace(const ConvShape &c);
+hipError_t conv_wgrad_mfma(const void *x, const void *dy, float *dw, void *workspace,
+                           const ConvShape &c, hipStream_t s);
+
+// ---- column sums over a [rows][C] matrix: out[c] += sum_r a[r][c]  (bias gradient)
+size_t colsum_workspace(int rows, int C);
+hipError_t colsum_accumulate(int dt, const void *a, int rows, int C, float *out, void *workspace,
+                             hipStream_t s);
+
+// ---- element-wise / pooling / normalisation
+hipError_t relu_fwd(int dt, const void *x, void *y, size_t n, hipStream_t s);
+hipError_t relu_bwd(int dt, const void *y, const void *dy, void *dx, GradEpi epi, size_t n, hipStream_t s);
+hipError_t maxpool2x2_fwd(int dt, const void *x, void *y, uint8_t *idx, int N, int H, int W, int C,
+                          hipStream_t s);
+// gate (if any) is indexed like dy (the pooled tensor), not like dx.
+hipError_t maxpool2x2_bwd(int dt, const void *dy, const uint8_t *idx, void *dx, GradEpi epi_pooled_gate,
+                          int N, int H, int W, int C, hipStream_t s);
+hipError_t add_fwd(int dt, const void *a, const void *b, void *y, int relu, size_t n, hipStream_t s);
+// dx (+)= dy with the epilogue of grad_out
+hipError_t grad_copy(int dt, const void *dy, void *dx, GradEpi epi, size_t n, hipStream_t s);
+
+size_t bn_workspace(int rows, int C);
+// stats: [2][C] floats (mean, invstd)
+hipError_t bn_fwd(int dt, const void *x, const float *gamma, const float *beta, float eps, void *y,
+                  float *stats, int relu, int rows, int C, void *workspace, hipStream_t s);
+hipError_t bn_bwd(int dt, const void *x, const void *dy, const float *gamma, const float *stats,
+                  void *dx, float *dgamma, float *dbeta, GradEpi epi, int rows, int C,
+                  void *workspace, hipStream_t s);
+
+// p = softmax(z) rows of K classes (float out)
+hipError_t softmax_fwd(int dt, const void *z, float *p, int rows, int K, hipStream_t s);
+// dz = scale*(p - onehot), loss[0] = -scale*sum_n log p[n,label]
+hipError_t xent_bwd(int dt, const float *p, const int32_t *labels, float scale, void *dz, float *loss,
+                    int rows, int K, hipStream_t s);
+
+// ---- parameters
+// w <- w - lr*g ; g <- 0 ; work <- storage(w)   (work may be NULL for float vectors)
+hipError_t sgd_step(int dt, float *w, float *g, float lr, void *work, size_t n, hipStream_t s);
+hipError_t recast(int dt, const float *w, void *work, size_t n, hipStream_t s);
+// wt[c][R-1-r][S-1-s][k] = work(w[k][r][s][c])   (dgrad filter)
+hipError_t make_dgrad_filter(int dt, const float *w, void *wt, int K, int R, int S, int C, hipStream_t s);
+hipError_t fill_f32(float *p, float v, size_t n, hipStream_t s);
+
+// ---- boundary layout conversion NCHW <-> NHWC (same storage type); optional ReLU gate
+hipError_t nchw_to_nhwc(int dt, const void *src, void *dst, GradEpi epi, int N, int C, int H, int W,
+                        hipStream_t s);
+hipError_t nhwc_to_nchw(int dt, const void *src, void *dst, int N, int C, int H, int W, hipStream_t s);
+hipError_t nhwc_to_nchw_u8(const uint8_t *src, uint8_t *dst, int N, int C, int H, int W, hipStream_t s);
+
+}  // namespace bapipe

@@ -1,0 +1,793 @@
+// HBM-bound kernels of a stage: ReLU, 2x2 max-pool, residual add, training-mode batch-norm,
+// softmax cross-entropy, SGD update, bias-gradient column sums and boundary layout changes.
+// All activations are NHWC, so the channel index is the fastest one: threads own V = 16/sizeof(T)
+// consecutive channels (one 16-byte access) and neighbouring threads neighbouring channel
+// groups, which keeps every wavefront's HBM access contiguous.
+#include "dev_common.h"
+#include "kernels.h"
+
+namespace bapipe {
+namespace {
+
+constexpr int TPB = 256;
+
+inline unsigned blocks_for(size_t n, int per_block = TPB)
+{
+    size_t b = (n + per_block - 1) / per_block;
+    return (unsigned)(b == 0 ? 1 : b);
+}
+
+template <class T> constexpr int vec_width() { return 16 / (int)sizeof(T); }
+
+inline bool aligned16(const void *p) { return (((uintptr_t)p) & 15u) == 0; }
+
+// ------------------------------------------------------------------ flat element-wise
+template <class T, int V>
+__global__ void k_relu_fwd(const T *__restrict__ x, T *__restrict__ y, size_t nvec)
+{
+    size_t i = (size_t)blockIdx.x * TPB + threadIdx.x;
+    if (i >= nvec) return;
+    vec_t<T, V> a = reinterpret_cast<const vec_t<T, V> *>(x)[i], r;
+#pragma unroll
+    for (int j = 0; j < V; ++j) r.e[j] = from_f32<T>(fmaxf(to_f32(a.e[j]), 0.0f));
+    reinterpret_cast<vec_t<T, V> *>(y)[i] = r;
+}
+
+template <class T, int V>
+__global__ void k_add_fwd(const T *__restrict__ a, const T *__restrict__ b, T *__restrict__ y, int relu,
+                          size_t nvec)
+{
+    size_t i = (size_t)blockIdx.x * TPB + threadIdx.x;
+    if (i >= nvec) return;
+    vec_t<T, V> va = reinterpret_cast<const vec_t<T, V> *>(a)[i];
+    vec_t<T, V> vb = reinterpret_cast<const vec_t<T, V> *>(b)[i], r;
+#pragma unroll
+    for (int j = 0; j < V; ++j) {
+        float v = to_f32(va.e[j]) + to_f32(vb.e[j]);
+        if (relu) v = fmaxf(v, 0.0f);
+        r.e[j] = from_f32<T>(v);
+    }
+    reinterpret_cast<vec_t<T, V> *>(y)[i] = r;
+}
+
+// dx (+)= dy, gated.  With own_gate the kernel is a stand-alone ReLU backward: the value is
+// first zeroed where own_gate <= 0 (own_gate = that ReLU's output).
+template <class T, int V>
+__global__ void k_grad_copy(const T *__restrict__ dy, const T *__restrict__ own_gate, T *dx,
+                            const T *__restrict__ gate, int accum, size_t nvec)
+{
+    size_t i = (size_t)blockIdx.x * TPB + threadIdx.x;
+    if (i >= nvec) return;
+    vec_t<T, V> g = reinterpret_cast<const vec_t<T, V> *>(dy)[i];
+    vec_t<T, V> og, old, gt, r;
+    if (own_gate) og = reinterpret_cast<const vec_t<T, V> *>(own_gate)[i];
+    if (accum) old = reinterpret_cast<const vec_t<T, V> *>(dx)[i];
+    if (gate) gt = reinterpret_cast<const vec_t<T, V> *>(gate)[i];
+#pragma unroll
+    for (int j = 0; j < V; ++j) {
+        float v = to_f32(g.e[j]);
+        if (own_gate && !(to_f32(og.e[j]) > 0.0f)) v = 0.0f;
+        r.e[j] = grad_out<T>(v, accum != 0, old.e[j], gate != nullptr, gt.e[j]);
+    }
+    reinterpret_cast<vec_t<T, V> *>(dx)[i] = r;
+}
+
+// ------------------------------------------------------------------ 2x2 stride-2 max-pool
+template <class T, int V>
+__global__ void k_pool_fwd(const T *__restrict__ x, T *__restrict__ y, uint8_t *__restrict__ idx, int N,
+                           int H, int W, int CV)
+{
+    const int Ho = H / 2, Wo = W / 2;
+    size_t i = (size_t)blockIdx.x * TPB + threadIdx.x;
+    size_t total = (size_t)N * Ho * Wo * CV;
+    if (i >= total) return;
+    int cv = (int)(i % CV);
+    size_t t = i / CV;
+    int q = (int)(t % Wo);
+    t /= Wo;
+    int p = (int)(t % Ho);
+    int n = (int)(t / Ho);
+    const vec_t<T, V> *xv = reinterpret_cast<const vec_t<T, V> *>(x);
+    size_t base = (((size_t)n * H + 2 * p) * W + 2 * q) * CV + cv;
+    vec_t<T, V> a[4];
+    a[0] = xv[base];
+    a[1] = xv[base + CV];
+    a[2] = xv[base + (size_t)W * CV];
+    a[3] = xv[base + (size_t)W * CV + CV];
+    vec_t<T, V> r;
+    vec_t<uint8_t, V> ri;
+#pragma unroll
+    for (int j = 0; j < V; ++j) {
+        float best = to_f32(a[0].e[j]);
+        int bi = 0;
+#pragma unroll
+        for (int k = 1; k < 4; ++k) {
+            float v = to_f32(a[k].e[j]);
+            if (v > best) {                       // strictly greater: the first maximum wins
+                best = v;
+                bi = k;
+            }
+        }
+        r.e[j] = from_f32<T>(best);
+        ri.e[j] = (uint8_t)bi;
+    }
+    reinterpret_cast<vec_t<T, V> *>(y)[i] = r;
+    reinterpret_cast<vec_t<uint8_t, V> *>(idx)[i] = ri;
+}
+
+template <class T, int V>
+__global__ void k_pool_bwd(const T *__restrict__ dy, const uint8_t *__restrict__ idx, T *dx,
+                           const T *__restrict__ gate, int accum, int N, int H, int W, int CV)
+{
+    const int Ho = H / 2, Wo = W / 2;
+    size_t i = (size_t)blockIdx.x * TPB + threadIdx.x;
+    size_t total = (size_t)N * Ho * Wo * CV;
+    if (i >= total) return;
+    int cv = (int)(i % CV);
+    size_t t = i / CV;
+    int q = (int)(t % Wo);
+    t /= Wo;
+    int p = (int)(t % Ho);
+    int n = (int)(t / Ho);
+    vec_t<T, V> g = reinterpret_cast<const vec_t<T, V> *>(dy)[i];
+    vec_t<uint8_t, V> ix = reinterpret_cast<const vec_t<uint8_t, V> *>(idx)[i];
+    vec_t<T, V> gt;
+    if (gate) gt = reinterpret_cast<const vec_t<T, V> *>(gate)[i];
+    vec_t<T, V> *dxv = reinterpret_cast<vec_t<T, V> *>(dx);
+    size_t base = (((size_t)n * H + 2 * p) * W + 2 * q) * CV + cv;
+    const size_t off[4] = {0, (size_t)CV, (size_t)W * CV, (size_t)W * CV + CV};
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        vec_t<T, V> old, r;
+        if (accum) old = dxv[base + off[k]];
+#pragma unroll
+        for (int j = 0; j < V; ++j) {
+            float v = (ix.e[j] == k) ? to_f32(g.e[j]) : 0.0f;
+            r.e[j] = grad_out<T>(v, accum != 0, old.e[j], gate != nullptr, gt.e[j]);
+        }
+        dxv[base + off[k]] = r;
+    }
+}
+
+// ------------------------------------------------------------------ column reductions
+// A [rows][C] matrix is cut into `chunks` row ranges; block (bx, chunk) owns up to TPB channel
+// groups... each block reduces its rows for CGB channel groups with RY row lanes, the lanes are
+// combined through LDS, and one partial per (chunk, channel, quantity) goes to the workspace.
+// A second tiny kernel adds the partials in double.  Fixed partition => bit-reproducible.
+struct ColPlan {
+    int CV, CGB, RY, chunks, rows_per_chunk, gx;
+};
+
+inline ColPlan col_plan(int rows, int C, int V)
+{
+    ColPlan p;
+    p.CV = C / V;
+    p.CGB = p.CV < TPB ? p.CV : TPB;
+    p.RY = TPB / p.CGB;
+    p.gx = (p.CV + p.CGB - 1) / p.CGB;
+    int want = (rows + p.RY * 8 - 1) / (p.RY * 8);
+    int cap = 2048 / p.gx;
+    if (cap < 1) cap = 1;
+    p.chunks = want < 1 ? 1 : (want > cap ? cap : want);
+    p.rows_per_chunk = (rows + p.chunks - 1) / p.chunks;
+    p.chunks = (rows + p.rows_per_chunk - 1) / p.rows_per_chunk;
+    if (p.chunks < 1) p.chunks = 1;
+    return p;
+}
+
+inline int col_vec(int dt, int C, const void *a, const void *b = nullptr, const void *c = nullptr)
+{
+    int V = dt == DT_F32 ? 4 : 8;
+    bool ok = (C % V == 0) && aligned16(a) && aligned16(b) && aligned16(c);
+    return ok ? V : 1;
+}
+
+// NQ quantities per element computed by functor F(row, channel-vector index, out[NQ][V])
+template <class T, int V, int NQ, class F>
+__device__ __forceinline__ void col_partial_body(F f, int rows, ColPlan p, float *__restrict__ part, int C)
+{
+    __shared__ float red[NQ * V * TPB];
+    const int cx = threadIdx.x % p.CGB, ry = threadIdx.x / p.CGB;
+    const int cg = blockIdx.x * p.CGB + cx;
+    const int chunk = blockIdx.y;
+    float acc[NQ][V];
+#pragma unroll
+    for (int qn = 0; qn < NQ; ++qn)
+#pragma unroll
+        for (int j = 0; j < V; ++j) acc[qn][j] = 0.0f;
+    const bool active = ry < p.RY && cg < p.CV;
+    if (active) {
+        int r0 = chunk * p.rows_per_chunk, r1 = r0 + p.rows_per_chunk;
+        if (r1 > rows) r1 = rows;
+        for (int r = r0 + ry; r < r1; r += p.RY) {
+            float v[NQ][V];
+            f(r, cg, v);
+#pragma unroll
+            for (int qn = 0; qn < NQ; ++qn)
+#pragma unroll
+                for (int j = 0; j < V; ++j) acc[qn][j] += v[qn][j];
+        }
+    }
+#pragma unroll
+    for (int qn = 0; qn < NQ; ++qn)
+#pragma unroll
+        for (int j = 0; j < V; ++j) red[(qn * V + j) * TPB + threadIdx.x] = acc[qn][j];
+    __syncthreads();
+    if (active && ry == 0) {
+#pragma unroll
+        for (int qn = 0; qn < NQ; ++qn)
+#pragma unroll
+            for (int j = 0; j < V; ++j) {
+                float s = 0.0f;
+                for (int k = 0; k < p.RY; ++k) s += red[(qn * V + j) * TPB + k * p.CGB + cx];
+                part[((size_t)qn * p.chunks + chunk) * C + cg * V + j] = s;
+            }
+    }
+}
+
+template <class T, int V>
+__global__ void k_colsum_partial(const T *__restrict__ a, int rows, int C, ColPlan p, float *part)
+{
+    const vec_t<T, V> *av = reinterpret_cast<const vec_t<T, V> *>(a);
+    auto f = [&](int r, int cg, float(&v)[1][V]) {
+        vec_t<T, V> x = av[(size_t)r * p.CV + cg];
+#pragma unroll
+        for (int j = 0; j < V; ++j) v[0][j] = to_f32(x.e[j]);
+    };
+    col_partial_body<T, V, 1>(f, rows, p, part, C);
+}
+
+__global__ void k_colsum_final(const float *__restrict__ part, int chunks, int C, float *out)
+{
+    int c = blockIdx.x * TPB + threadIdx.x;
+    if (c >= C) return;
+    double s = 0.0;
+    for (int k = 0; k < chunks; ++k) s += (double)part[(size_t)k * C + c];
+    out[c] += (float)s;
+}
+
+// ------------------------------------------------------------------ batch-norm
+template <class T, int V>
+__global__ void k_bn_stat_partial(const T *__restrict__ x, int rows, int C, ColPlan p, float *part)
+{
+    const vec_t<T, V> *xv = reinterpret_cast<const vec_t<T, V> *>(x);
+    auto f = [&](int r, int cg, float(&v)[2][V]) {
+        vec_t<T, V> a = xv[(size_t)r * p.CV + cg];
+#pragma unroll
+        for (int j = 0; j < V; ++j) {
+            float t = to_f32(a.e[j]);
+            v[0][j] = t;
+            v[1][j] = t * t;
+        }
+    };
+    col_partial_body<T, V, 2>(f, rows, p, part, C);
+}
+
+__global__ void k_bn_stat_final(const float *__restrict__ part, int chunks, int C, int rows, float eps,
+                                float *stats)
+{
+    int c = blockIdx.x * TPB + threadIdx.x;
+    if (c >= C) return;
+    double s = 0.0, ss = 0.0;
+    for (int k = 0; k < chunks; ++k) {
+        s += (double)part[(size_t)k * C + c];
+        ss += (double)part[((size_t)chunks + k) * C + c];
+    }
+    double m = (double)rows, mu = s / m, var = ss / m - mu * mu;
+    if (var < 0.0) var = 0.0;
+    stats[c] = (float)mu;
+    stats[C + c] = (float)(1.0 / sqrt(var + (double)eps));
+}
+
+template <class T, int V>
+__global__ void k_bn_apply(const T *__restrict__ x, const float *__restrict__ gamma,
+                           const float *__restrict__ beta, const float *__restrict__ stats,
+                           T *__restrict__ y, int relu, size_t nvec, int CV, int C)
+{
+    size_t i = (size_t)blockIdx.x * TPB + threadIdx.x;
+    if (i >= nvec) return;
+    int c0 = (int)(i % CV) * V;
+    vec_t<T, V> a = reinterpret_cast<const vec_t<T, V> *>(x)[i], r;
+#pragma unroll
+    for (int j = 0; j < V; ++j) {
+        float xh = (to_f32(a.e[j]) - stats[c0 + j]) * stats[C + c0 + j];
+        float v = gamma[c0 + j] * xh + beta[c0 + j];
+        if (relu) v = fmaxf(v, 0.0f);
+        r.e[j] = from_f32<T>(v);
+    }
+    reinterpret_cast<vec_t<T, V> *>(y)[i] = r;
+}
+
+template <class T, int V>
+__global__ void k_bn_bwd_partial(const T *__restrict__ x, const T *__restrict__ dy,
+                                 const float *__restrict__ stats, int rows, int C, ColPlan p, float *part)
+{
+    const vec_t<T, V> *xv = reinterpret_cast<const vec_t<T, V> *>(x);
+    const vec_t<T, V> *gv = reinterpret_cast<const vec_t<T, V> *>(dy);
+    auto f = [&](int r, int cg, float(&v)[2][V]) {
+        vec_t<T, V> a = xv[(size_t)r * p.CV + cg];
+        vec_t<T, V> g = gv[(size_t)r * p.CV + cg];
+#pragma unroll
+        for (int j = 0; j < V; ++j) {
+            float gg = to_f32(g.e[j]);
+            float xh = (to_f32(a.e[j]) - stats[cg * V + j]) * stats[C + cg * V + j];
+            v[0][j] = gg;
+            v[1][j] = gg * xh;
+        }
+    };
+    col_partial_body<T, V, 2>(f, rows, p, part, C);
+}
+
+// sums[c] = (sum dy, sum dy*xhat) of this micro-batch; dbeta/dgamma accumulate over micro-batches
+__global__ void k_bn_bwd_final(const float *__restrict__ part, int chunks, int C, float *sums,
+                               float *dgamma, float *dbeta)
+{
+    int c = blockIdx.x * TPB + threadIdx.x;
+    if (c >= C) return;
+    double s1 = 0.0, s2 = 0.0;
+    for (int k = 0; k < chunks; ++k) {
+        s1 += (double)part[(size_t)k * C + c];
+        s2 += (double)part[((size_t)chunks + k) * C + c];
+    }
+    sums[c] = (float)s1;
+    sums[C + c] = (float)s2;
+    dbeta[c] += (float)s1;
+    dgamma[c] += (float)s2;
+}
+
+template <class T, int V>
+__global__ void k_bn_bwd_apply(const T *__restrict__ x, const T *__restrict__ dy,
+                               const float *__restrict__ gamma, const float *__restrict__ stats,
+                               const float *__restrict__ sums, T *dx, const T *__restrict__ gate,
+                               int accum, float inv_m, size_t nvec, int CV, int C)
+{
+    size_t i = (size_t)blockIdx.x * TPB + threadIdx.x;
+    if (i >= nvec) return;
+    int c0 = (int)(i % CV) * V;
+    vec_t<T, V> a = reinterpret_cast<const vec_t<T, V> *>(x)[i];
+    vec_t<T, V> g = reinterpret_cast<const vec_t<T, V> *>(dy)[i];
+    vec_t<T, V> old, gt, r;
+    if (accum) old = reinterpret_cast<const vec_t<T, V> *>(dx)[i];
+    if (gate) gt = reinterpret_cast<const vec_t<T, V> *>(gate)[i];
+#pragma unroll
+    for (int j = 0; j < V; ++j) {
+        int c = c0 + j;
+        float inv = stats[C + c];
+        float xh = (to_f32(a.e[j]) - stats[c]) * inv;
+        float v = gamma[c] * inv * (to_f32(g.e[j]) - sums[c] * inv_m - xh * sums[C + c] * inv_m);
+        r.e[j] = grad_out<T>(v, accum != 0, old.e[j], gate != nullptr, gt.e[j]);
+    }
+    reinterpret_cast<vec_t<T, V> *>(dx)[i] = r;
+}
+
+// ------------------------------------------------------------------ softmax cross-entropy
+template <class T>
+__global__ void k_softmax_fwd(const T *__restrict__ z, float *__restrict__ p, int K)
+{
+    __shared__ float sh[TPB / 64];
+    __shared__ float bc;
+    const T *zr = z + (size_t)blockIdx.x * K;
+    float *pr = p + (size_t)blockIdx.x * K;
+    float mx = -INFINITY;
+    for (int k = threadIdx.x; k < K; k += TPB) mx = fmaxf(mx, to_f32(zr[k]));
+    mx = wave_max(mx);
+    if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = mx;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        float m = sh[0];
+        for (int i = 1; i < TPB / 64; ++i) m = fmaxf(m, sh[i]);
+        bc = m;
+    }
+    __syncthreads();
+    mx = bc;
+    float s = 0.0f;
+    for (int k = threadIdx.x; k < K; k += TPB) s += expf(to_f32(zr[k]) - mx);
+    s = wave_sum(s);
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = s;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        float t = 0.0f;
+        for (int i = 0; i < TPB / 64; ++i) t += sh[i];
+        bc = t;
+    }
+    __syncthreads();
+    float inv = 1.0f / bc;
+    for (int k = threadIdx.x; k < K; k += TPB) pr[k] = expf(to_f32(zr[k]) - mx) * inv;
+}
+
+template <class T>
+__global__ void k_xent_dz(const float *__restrict__ p, const int32_t *__restrict__ labels, float scale,
+                          T *__restrict__ dz, int K)
+{
+    const int n = blockIdx.x;
+    const int lab = labels[n];
+    for (int k = threadIdx.x; k < K; k += TPB) {
+        float v = scale * (p[(size_t)n * K + k] - (k == lab ? 1.0f : 0.0f));
+        dz[(size_t)n * K + k] = from_f32<T>(v);
+    }
+}
+
+// one block: loss = -scale * sum_n log p[n, label_n]   (labels outside [0,K) contribute 0)
+__global__ void k_xent_loss(const float *__restrict__ p, const int32_t *__restrict__ labels, float scale,
+                            float *loss, int rows, int K)
+{
+    __shared__ float sh[TPB / 64];
+    float s = 0.0f;
+    for (int n = threadIdx.x; n < rows; n += TPB) {
+        int lab = labels[n];
+        if (lab >= 0 && lab < K) s -= logf(fmaxf(p[(size_t)n * K + lab], 1e-37f));
+    }
+    s = wave_sum(s);
+    if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = s;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        float t = 0.0f;
+        for (int i = 0; i < TPB / 64; ++i) t += sh[i];
+        loss[0] = scale * t;
+    }
+}
+
+// ------------------------------------------------------------------ parameters
+template <class T, bool HAS_WORK>
+__global__ void k_sgd(float *__restrict__ w, float *__restrict__ g, float lr, T *__restrict__ work, size_t n)
+{
+    size_t i = (size_t)blockIdx.x * TPB + threadIdx.x;
+    if (i >= n) return;
+    float v = w[i] - lr * g[i];
+    w[i] = v;
+    g[i] = 0.0f;
+    if (HAS_WORK) work[i] = from_f32<T>(v);
+}
+
+template <class T> __global__ void k_recast(const float *__restrict__ w, T *__restrict__ work, size_t n)
+{
+    size_t i = (size_t)blockIdx.x * TPB + threadIdx.x;
+    if (i < n) work[i] = from_f32<T>(w[i]);
+}
+
+template <class T>
+__global__ void k_dgrad_filter(const float *__restrict__ w, T *__restrict__ wt, int K, int R, int S, int C)
+{
+    size_t i = (size_t)blockIdx.x * TPB + threadIdx.x;
+    size_t total = (size_t)K * R * S * C;
+    if (i >= total) return;
+    int k = (int)(i % K);
+    size_t t = i / K;
+    int s = (int)(t % S);
+    t /= S;
+    int r = (int)(t % R);
+    int c = (int)(t / R);
+    wt[i] = from_f32<T>(w[(((size_t)k * R + (R - 1 - r)) * S + (S - 1 - s)) * C + c]);
+}
+
+__global__ void k_fill(float *p, float v, size_t n)
+{
+    size_t i = (size_t)blockIdx.x * TPB + threadIdx.x;
+    if (i < n) p[i] = v;
+}
+
+// ------------------------------------------------------------------ layout changes
+template <class T>
+__global__ void k_nchw_to_nhwc(const T *__restrict__ src, T *dst, const T *__restrict__ gate, int accum,
+                               int N, int C, int H, int W)
+{
+    size_t i = (size_t)blockIdx.x * TPB + threadIdx.x;       // index into dst (NHWC)
+    size_t total = (size_t)N * C * H * W;
+    if (i >= total) return;
+    int c = (int)(i % C);
+    size_t t = i / C;
+    int w = (int)(t % W);
+    t /= W;
+    int h = (int)(t % H);
+    int n = (int)(t / H);
+    T v = src[(((size_t)n * C + c) * H + h) * W + w];
+    if (gate || accum) {
+        T old = v, gt = v;
+        if (accum) old = dst[i];
+        if (gate) gt = gate[i];
+        v = grad_out<T>(to_f32(v), accum != 0, old, gate != nullptr, gt);
+    }
+    dst[i] = v;
+}
+
+template <class T>
+__global__ void k_nhwc_to_nchw(const T *__restrict__ src, T *__restrict__ dst, int N, int C, int H, int W)
+{
+    size_t i = (size_t)blockIdx.x * TPB + threadIdx.x;       // index into dst (NCHW)
+    size_t total = (size_t)N * C * H * W;
+    if (i >= total) return;
+    int w = (int)(i % W);
+    size_t t = i / W;
+    int h = (int)(t % H);
+    t /= H;
+    int c = (int)(t % C);
+    int n = (int)(t / C);
+    dst[i] = src[(((size_t)n * H + h) * W + w) * C + c];
+}
+
+#define DISPATCH_T(dt, ...)                        \
+    do {                                           \
+        if ((dt) == DT_F32) {                      \
+            using T = float;                       \
+            __VA_ARGS__                            \
+        } else {                                   \
+            using T = bf16_t;                      \
+            __VA_ARGS__                            \
+        }                                          \
+    } while (0)
+
+#define DISPATCH_TV(dt, vec, ...)                  \
+    do {                                           \
+        if ((dt) == DT_F32) {                      \
+            using T = float;                       \
+            if (vec) {                             \
+                constexpr int V = 4;               \
+                __VA_ARGS__                        \
+            } else {                               \
+                constexpr int V = 1;               \
+                __VA_ARGS__                        \
+            }                                      \
+        } else {                                   \
+            using T = bf16_t;                      \
+            if (vec) {                             \
+                constexpr int V = 8;               \
+                __VA_ARGS__                        \
+            } else {                               \
+                constexpr int V = 1;               \
+                __VA_ARGS__                        \
+            }                                      \
+        }                                          \
+    } while (0)
+
+inline bool flat_vec(int dt, size_t n, const void *a, const void *b = nullptr, const void *c = nullptr,
+                     const void *d = nullptr)
+{
+    size_t V = dt == DT_F32 ? 4 : 8;
+    return n % V == 0 && aligned16(a) && aligned16(b) && aligned16(c) && aligned16(d);
+}
+
+}  // namespace
+
+// ====================================================================== launchers
+hipError_t relu_fwd(int dt, const void *x, void *y, size_t n, hipStream_t s)
+{
+    if (n == 0) return hipSuccess;
+    bool vec = flat_vec(dt, n, x, y);
+    DISPATCH_TV(dt, vec, {
+        size_t nv = n / V;
+        hipLaunchKernelGGL((k_relu_fwd<T, V>), dim3(blocks_for(nv)), dim3(TPB), 0, s, (const T *)x, (T *)y, nv);
+    });
+    return hipGetLastError();
+}
+
+hipError_t relu_bwd(int dt, const void *y, const void *dy, void *dx, GradEpi epi, size_t n, hipStream_t s)
+{
+    if (n == 0) return hipSuccess;
+    bool vec = flat_vec(dt, n, y, dy, dx, epi.gate);
+    DISPATCH_TV(dt, vec, {
+        size_t nv = n / V;
+        hipLaunchKernelGGL((k_grad_copy<T, V>), dim3(blocks_for(nv)), dim3(TPB), 0, s, (const T *)dy,
+                           (const T *)y, (T *)dx, (const T *)epi.gate, epi.accum, nv);
+    });
+    return hipGetLastError();
+}
+
+hipError_t grad_copy(int dt, const void *dy, void *dx, GradEpi epi, size_t n, hipStream_t s)
+{
+    if (n == 0) return hipSuccess;
+    bool vec = flat_vec(dt, n, dy, dx, epi.gate);
+    DISPATCH_TV(dt, vec, {
+        size_t nv = n / V;
+        hipLaunchKernelGGL((k_grad_copy<T, V>), dim3(blocks_for(nv)), dim3(TPB), 0, s, (const T *)dy,
+                           (const T *)nullptr, (T *)dx, (const T *)epi.gate, epi.accum, nv);
+    });
+    return hipGetLastError();
+}
+
+hipError_t add_fwd(int dt, const void *a, const void *b, void *y, int relu, size_t n, hipStream_t s)
+{
+    if (n == 0) return hipSuccess;
+    bool vec = flat_vec(dt, n, a, b, y);
+    DISPATCH_TV(dt, vec, {
+        size_t nv = n / V;
+        hipLaunchKernelGGL((k_add_fwd<T, V>), dim3(blocks_for(nv)), dim3(TPB), 0, s, (const T *)a,
+                           (const T *)b, (T *)y, relu, nv);
+    });
+    return hipGetLastError();
+}
+
+hipError_t maxpool2x2_fwd(int dt, const void *x, void *y, uint8_t *idx, int N, int H, int W, int C,
+                          hipStream_t s)
+{
+    size_t outs = (size_t)N * (H / 2) * (W / 2) * C;
+    if (outs == 0) return hipSuccess;
+    int Vw = dt == DT_F32 ? 4 : 8;
+    bool vec = (C % Vw == 0) && aligned16(x) && aligned16(y) && ((uintptr_t)idx % 8 == 0);
+    DISPATCH_TV(dt, vec, {
+        size_t nv = outs / V;
+        hipLaunchKernelGGL((k_pool_fwd<T, V>), dim3(blocks_for(nv)), dim3(TPB), 0, s, (const T *)x, (T *)y,
+                           idx, N, H, W, C / V);
+    });
+    return hipGetLastError();
+}
+
+hipError_t maxpool2x2_bwd(int dt, const void *dy, const uint8_t *idx, void *dx, GradEpi epi, int N, int H,
+                          int W, int C, hipStream_t s)
+{
+    size_t outs = (size_t)N * (H / 2) * (W / 2) * C;
+    if (((H | W) & 1) && !epi.accum) {   // odd sizes: the last row/column gets no gradient
+        size_t bytes = (size_t)N * H * W * C * dt_size(dt);
+        hipLaunchKernelGGL(k_fill, dim3(blocks_for(bytes / 4)), dim3(TPB), 0, s, (float *)dx, 0.0f, bytes / 4);
+        if (bytes % 4) return hipErrorInvalidValue;
+    }
+    if (outs == 0) return hipGetLastError();
+    int Vw = dt == DT_F32 ? 4 : 8;
+    bool vec = (C % Vw == 0) && aligned16(dy) && aligned16(dx) && aligned16(epi.gate) &&
+               ((uintptr_t)idx % 8 == 0);
+    DISPATCH_TV(dt, vec, {
+        size_t nv = outs / V;
+        hipLaunchKernelGGL((k_pool_bwd<T, V>), dim3(blocks_for(nv)), dim3(TPB), 0, s, (const T *)dy, idx,
+                           (T *)dx, (const T *)epi.gate, epi.accum, N, H, W, C / V);
+    });
+    return hipGetLastError();
+}
+
+size_t colsum_workspace(int rows, int C)
+{
+    ColPlan p = col_plan(rows, C, 1);           // V = 1 gives the largest chunk count bound
+    ColPlan p8 = col_plan(rows, C, (C % 8 == 0) ? 8 : 1);
+    ColPlan p4 = col_plan(rows, C, (C % 4 == 0) ? 4 : 1);
+    int chunks = p.chunks > p8.chunks ? p.chunks : p8.chunks;
+    chunks = chunks > p4.chunks ? chunks : p4.chunks;
+    return (size_t)2 * chunks * C * sizeof(float) + 4 * (size_t)C * sizeof(float);
+}
+
+size_t bn_workspace(int rows, int C) { return colsum_workspace(rows, C); }
+
+hipError_t colsum_accumulate(int dt, const void *a, int rows, int C, float *out, void *workspace,
+                             hipStream_t s)
+{
+    if (rows <= 0 || C <= 0) return hipSuccess;
+    int Vsel = col_vec(dt, C, a);
+    float *part = (float *)workspace;
+    DISPATCH_TV(dt, Vsel > 1, {
+        ColPlan p = col_plan(rows, C, V);
+        hipLaunchKernelGGL((k_colsum_partial<T, V>), dim3(p.gx, p.chunks), dim3(TPB), 0, s, (const T *)a, rows,
+                           C, p, part);
+        hipLaunchKernelGGL(k_colsum_final, dim3(blocks_for(C)), dim3(TPB), 0, s, part, p.chunks, C, out);
+    });
+    return hipGetLastError();
+}
+
+hipError_t bn_fwd(int dt, const void *x, const float *gamma, const float *beta, float eps, void *y,
+                  float *stats, int relu, int rows, int C, void *workspace, hipStream_t s)
+{
+    if (rows <= 0 || C <= 0) return hipSuccess;
+    int Vsel = col_vec(dt, C, x, y);
+    float *part = (float *)workspace;
+    DISPATCH_TV(dt, Vsel > 1, {
+        ColPlan p = col_plan(rows, C, V);
+        hipLaunchKernelGGL((k_bn_stat_partial<T, V>), dim3(p.gx, p.chunks), dim3(TPB), 0, s, (const T *)x,
+                           rows, C, p, part);
+        hipLaunchKernelGGL(k_bn_stat_final, dim3(blocks_for(C)), dim3(TPB), 0, s, part, p.chunks, C, rows,
+                           eps, stats);
+        size_t nv = (size_t)rows * C / V;
+        hipLaunchKernelGGL((k_bn_apply<T, V>), dim3(blocks_for(nv)), dim3(TPB), 0, s, (const T *)x, gamma,
+                           beta, stats, (T *)y, relu, nv, C / V, C);
+    });
+    return hipGetLastError();
+}
+
+hipError_t bn_bwd(int dt, const void *x, const void *dy, const float *gamma, const float *stats, void *dx,
+                  float *dgamma, float *dbeta, GradEpi epi, int rows, int C, void *workspace,
+                  hipStream_t s)
+{
+    if (rows <= 0 || C <= 0) return hipSuccess;
+    int Vsel = col_vec(dt, C, x, dy, dx);
+    if (!aligned16(epi.gate)) Vsel = 1;
+    float *part = (float *)workspace;
+    DISPATCH_TV(dt, Vsel > 1, {
+        ColPlan p = col_plan(rows, C, V);
+        float *sums = part + (size_t)2 * p.chunks * C;
+        hipLaunchKernelGGL((k_bn_bwd_partial<T, V>), dim3(p.gx, p.chunks), dim3(TPB), 0, s, (const T *)x,
+                           (const T *)dy, stats, rows, C, p, part);
+        hipLaunchKernelGGL(k_bn_bwd_final, dim3(blocks_for(C)), dim3(TPB), 0, s, part, p.chunks, C, sums,
+                           dgamma, dbeta);
+        if (dx) {
+            size_t nv = (size_t)rows * C / V;
+            hipLaunchKernelGGL((k_bn_bwd_apply<T, V>), dim3(blocks_for(nv)), dim3(TPB), 0, s, (const T *)x,
+                               (const T *)dy, gamma, stats, sums, (T *)dx, (const T *)epi.gate, epi.accum,
+                               1.0f / (float)rows, nv, C / V, C);
+        }
+    });
+    return hipGetLastError();
+}
+
+hipError_t softmax_fwd(int dt, const void *z, float *p, int rows, int K, hipStream_t s)
+{
+    if (rows <= 0) return hipSuccess;
+    DISPATCH_T(dt, { hipLaunchKernelGGL((k_softmax_fwd<T>), dim3(rows), dim3(TPB), 0, s, (const T *)z, p, K); });
+    return hipGetLastError();
+}
+
+hipError_t xent_bwd(int dt, const float *p, const int32_t *labels, float scale, void *dz, float *loss,
+                    int rows, int K, hipStream_t s)
+{
+    if (rows <= 0) return hipSuccess;
+    DISPATCH_T(dt, {
+        hipLaunchKernelGGL((k_xent_dz<T>), dim3(rows), dim3(TPB), 0, s, p, labels, scale, (T *)dz, K);
+    });
+    hipLaunchKernelGGL(k_xent_loss, dim3(1), dim3(TPB), 0, s, p, labels, scale, loss, rows, K);
+    return hipGetLastError();
+}
+
+hipError_t sgd_step(int dt, float *w, float *g, float lr, void *work, size_t n, hipStream_t s)
+{
+    if (n == 0) return hipSuccess;
+    if (!work) {
+        hipLaunchKernelGGL((k_sgd<float, false>), dim3(blocks_for(n)), dim3(TPB), 0, s, w, g, lr, (float *)nullptr, n);
+    } else {
+        DISPATCH_T(dt, {
+            hipLaunchKernelGGL((k_sgd<T, true>), dim3(blocks_for(n)), dim3(TPB), 0, s, w, g, lr, (T *)work, n);
+        });
+    }
+    return hipGetLastError();
+}
+
+hipError_t recast(int dt, const float *w, void *work, size_t n, hipStream_t s)
+{
+    if (n == 0) return hipSuccess;
+    DISPATCH_T(dt, { hipLaunchKernelGGL((k_recast<T>), dim3(blocks_for(n)), dim3(TPB), 0, s, w, (T *)work, n); });
+    return hipGetLastError();
+}
+
+hipError_t make_dgrad_filter(int dt, const float *w, void *wt, int K, int R, int S, int C, hipStream_t s)
+{
+    size_t n = (size_t)K * R * S * C;
+    if (n == 0) return hipSuccess;
+    DISPATCH_T(dt, {
+        hipLaunchKernelGGL((k_dgrad_filter<T>), dim3(blocks_for(n)), dim3(TPB), 0, s, w, (T *)wt, K, R, S, C);
+    });
+    return hipGetLastError();
+}
+
+hipError_t fill_f32(float *p, float v, size_t n, hipStream_t s)
+{
+    if (n == 0) return hipSuccess;
+    hipLaunchKernelGGL(k_fill, dim3(blocks_for(n)), dim3(TPB), 0, s, p, v, n);
+    return hipGetLastError();
+}
+
+hipError_t nchw_to_nhwc(int dt, const void *src, void *dst, GradEpi epi, int N, int C, int H, int W,
+                        hipStream_t s)
+{
+    size_t n = (size_t)N * C * H * W;
+    if (n == 0) return hipSuccess;
+    DISPATCH_T(dt, {
+        hipLaunchKernelGGL((k_nchw_to_nhwc<T>), dim3(blocks_for(n)), dim3(TPB), 0, s, (const T *)src, (T *)dst,
+                           (const T *)epi.gate, epi.accum, N, C, H, W);
+    });
+    return hipGetLastError();
+}
+
+hipError_t nhwc_to_nchw(int dt, const void *src, void *dst, int N, int C, int H, int W, hipStream_t s)
+{
+    size_t n = (size_t)N * C * H * W;
+    if (n == 0) return hipSuccess;
+    DISPATCH_T(dt, {
+        hipLaunchKernelGGL((k_nhwc_to_nchw<T>), dim3(blocks_for(n)), dim3(TPB), 0, s, (const T *)src, (T *)dst,
+                           N, C, H, W);
+    });
+    return hipGetLastError();
+}
+
+hipError_t nhwc_to_nchw_u8(const uint8_t *src, uint8_t *dst, int N, int C, int H, int W, hipStream_t s)
+{
+    size_t n = (size_t)N * C * H * W;
+    if (n == 0) return hipSuccess;
+    hipLaunchKernelGGL((k_nhwc_to_nchw<uint8_t>), dim3(blocks_for(n)), dim3(TPB), 0, s, src, dst, N, C, H, W);
+    return hipGetLastError();
+}
+
+}  // namespace bapipe

@@ -1,0 +1,966 @@
+// Host side of libbapipe_stage: the C ABI of include/bapipe_stage.h, shape inference over the
+// layer list, the 1F1B micro-batch bookkeeping with its bounded activation-stash ring
+// (paper Sec. III-B-1, Table I/II "Features memory"), the HBM memory plan, the per-layer
+// kernel sequencing for forward / backward / update, and the layer profiler (Sec. III-A).
+//
+// Memory plan (all HBM, one allocation each, obtained through the caller's allocator):
+//   params    fp32 master w,b | fp32 accumulators dw,db | working copies (storage type):
+//             w [K][R][S][C] for forward, flipped channel-transposed [C][R][S][K] for dgrad
+//   stash     depth x slot ; a slot holds, for one in-flight micro-batch, exactly the tensors
+//             backward reads again: layer inputs of conv/linear/BN, ReLU gates, pool indices,
+//             BN statistics, softmax output.  depth = min(M, N-i+1) (x2 for 1F1B-SO).
+//   transient forward tensors nobody reads in backward (reused by every micro-batch)
+//   grads     one buffer per tensor that receives an activation gradient (reused)
+//   workspace split-K / column-reduction partials
+#include <hip/hip_runtime.h>
+
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <string>
+#include <vector>
+
+#include "../../include/bapipe_stage.h"
+#include "kernels.h"
+
+using namespace bapipe;
+
+namespace {
+
+thread_local std::string g_create_error;
+
+size_t align_up(size_t v, size_t a = 256) { return (v + a - 1) / a * a; }
+
+struct Tensor {
+    int C = 0, H = 0, W = 0;
+    size_t elems = 0;      // per micro-batch
+    size_t esize = 0;      // bytes per element
+    int root = -1;         // storage owner (FLATTEN outputs alias their input)
+    int producer = -1;     // layer index, -1 for the stage input
+    bool stashed = false;  // kept per in-flight micro-batch
+    bool need_grad = false;
+    bool gated = false;    // producer applies a fused ReLU (or is a ReLU layer)
+    size_t off = 0;        // byte offset in the stash slot or in the transient arena
+    size_t goff = 0;       // byte offset in the gradient arena
+    std::vector<int> consumers;
+    size_t bytes() const { return elems * esize; }
+};
+
+struct Layer {
+    bapipe_layer_desc_t d;
+    int a = -1, b = -1, o = -1;   // tensor ids (0 = stage input, i+1 = output of layer i)
+    size_t w_elems = 0, b_elems = 0;
+    float *w = nullptr, *bias = nullptr, *dw = nullptr, *db = nullptr;
+    void *w_work = nullptr, *w_t = nullptr;
+    size_t aux_off = 0, aux_bytes = 0;   // pool indices / BN statistics inside the slot
+    bool permute_in = false;             // LINEAR fed by a flattened (C,H,W) tensor
+    int pc = 0, ph = 0, pw = 0;
+};
+
+}  // namespace
+
+struct bapipe_stage {
+    std::vector<Layer> layers;
+    std::vector<Tensor> tensors;
+    bapipe_stage_opts_t opts;
+    int dt = DT_F32;
+    int mb = 0, M = 0, depth = 0;
+    float loss_scale = 0.f;
+    hipStream_t stream = nullptr;
+    // arenas
+    char *params = nullptr, *stash = nullptr, *transient = nullptr, *grads = nullptr, *work = nullptr;
+    float *losses = nullptr;
+    size_t params_bytes = 0, slot_bytes = 0, transient_bytes = 0, grads_bytes = 0, work_bytes = 0;
+    size_t accum_off = 0, accum_bytes = 0;   // the dw/db region inside params (zeroed together)
+    // schedule
+    int n_fwd = 0, n_bwd = 0;
+    std::vector<char> loss_valid;
+    std::string err;
+
+    void *dev_alloc(size_t bytes)
+    {
+        if (bytes == 0) bytes = 256;
+        if (opts.mem.alloc) return opts.mem.alloc(bytes, opts.mem.ctx);
+        void *p = nullptr;
+        if (hipMalloc(&p, bytes) != hipSuccess) {
+            (void)hipGetLastError();
+            return nullptr;
+        }
+        return p;
+    }
+    void dev_free(void *p)
+    {
+        if (!p) return;
+        if (opts.mem.alloc) {
+            if (opts.mem.free) opts.mem.free(p, opts.mem.ctx);
+        } else {
+            (void)hipFree(p);
+        }
+    }
+    int fail(int code, const char *fmt, ...)
+    {
+        char buf[512];
+        va_list ap;
+        va_start(ap, fmt);
+        vsnprintf(buf, sizeof buf, fmt, ap);
+        va_end(ap);
+        err = buf;
+        return code;
+    }
+    char *slot(int mbid) { return stash + (size_t)(mbid % depth) * slot_bytes; }
+    void *tptr(int t, int mbid)
+    {
+        const Tensor &T = tensors[tensors[t].root];
+        return (T.stashed ? slot(mbid) : transient) + T.off;
+    }
+    void *gptr(int t) { return grads + tensors[tensors[t].root].goff; }
+};
+
+namespace {
+
+int create_fail(int code, const char *fmt, ...)
+{
+    char buf[512];
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(buf, sizeof buf, fmt, ap);
+    va_end(ap);
+    g_create_error = buf;
+    return code;
+}
+
+bool has_params(int kind) { return kind == BAPIPE_CONV2D || kind == BAPIPE_LINEAR || kind == BAPIPE_BATCHNORM2D; }
+
+GatherConv fwd_geom(const bapipe_stage *st, const Layer &L)
+{
+    const Tensor &A = st->tensors[L.a], &O = st->tensors[L.o];
+    GatherConv g;
+    g.N = st->mb;
+    if (L.d.kind == BAPIPE_LINEAR) {
+        g.Hi = g.Wi = g.Ho = g.Wo = 1;
+        g.Ci = L.d.cin;
+        g.Co = L.d.cout;
+        g.R = g.S = 1;
+        g.s_out = g.s_in = 1;
+        g.pad_h = g.pad_w = 0;
+        return g;
+    }
+    g.Hi = A.H; g.Wi = A.W; g.Ci = A.C;
+    g.Ho = O.H; g.Wo = O.W; g.Co = O.C;
+    g.R = L.d.kh; g.S = L.d.kw;
+    g.s_out = L.d.stride; g.s_in = 1;
+    g.pad_h = g.pad_w = L.d.pad;
+    return g;
+}
+
+GatherConv dgrad_geom(const bapipe_stage *st, const Layer &L)
+{
+    GatherConv f = fwd_geom(st, L), g;
+    g.N = f.N;
+    g.Hi = f.Ho; g.Wi = f.Wo; g.Ci = f.Co;
+    g.Ho = f.Hi; g.Wo = f.Wi; g.Co = f.Ci;
+    g.R = f.R; g.S = f.S;
+    g.s_out = 1; g.s_in = f.s_out;
+    g.pad_h = f.R - 1 - f.pad_h;
+    g.pad_w = f.S - 1 - f.pad_w;
+    return g;
+}
+
+ConvShape conv_shape(const bapipe_stage *st, const Layer &L)
+{
+    GatherConv f = fwd_geom(st, L);
+    ConvShape c;
+    c.N = f.N; c.H = f.Hi; c.W = f.Wi; c.C = f.Ci;
+    c.P = f.Ho; c.Q = f.Wo; c.K = f.Co;
+    c.R = f.R; c.S = f.S; c.stride = f.s_out; c.pad = f.pad_h;
+    return c;
+}
+
+bool use_mfma_gather(const bapipe_stage *st, const GatherConv &g) { return st->dt == DT_BF16 && conv_gather_mfma_supported(g); }
+bool use_mfma_wgrad(const bapipe_stage *st, const ConvShape &c) { return st->dt == DT_BF16 && conv_wgrad_mfma_supported(c); }
+
+#define HIPCHK(call)                                                                   \
+    do {                                                                               \
+        hipError_t e_ = (call);                                                        \
+        if (e_ != hipSuccess) return st->fail(BAPIPE_E_DEVICE, "%s: %s", #call, hipGetErrorString(e_)); \
+    } while (0)
+
+// OIHW (or [out][in] with NCHW-flattened in) host weights <-> internal [K][R][S][C]
+void to_internal(const Layer &L, const float *src, float *dst)
+{
+    const int K = L.d.cout;
+    if (L.d.kind == BAPIPE_LINEAR) {
+        const int In = L.d.cin;
+        if (!L.permute_in) {
+            memcpy(dst, src, sizeof(float) * (size_t)K * In);
+            return;
+        }
+        for (int k = 0; k < K; ++k)
+            for (int c = 0; c < L.pc; ++c)
+                for (int h = 0; h < L.ph; ++h)
+                    for (int w = 0; w < L.pw; ++w)
+                        dst[(size_t)k * In + ((size_t)h * L.pw + w) * L.pc + c] =
+                            src[(size_t)k * In + ((size_t)c * L.ph + h) * L.pw + w];
+        return;
+    }
+    const int C = L.d.cin, R = L.d.kh, S = L.d.kw;
+    for (int k = 0; k < K; ++k)
+        for (int c = 0; c < C; ++c)
+            for (int r = 0; r < R; ++r)
+                for (int s = 0; s < S; ++s)
+                    dst[(((size_t)k * R + r) * S + s) * C + c] = src[(((size_t)k * C + c) * R + r) * S + s];
+}
+
+void from_internal(const Layer &L, const float *src, float *dst)
+{
+    const int K = L.d.cout;
+    if (L.d.kind == BAPIPE_LINEAR) {
+        const int In = L.d.cin;
+        if (!L.permute_in) {
+            memcpy(dst, src, sizeof(float) * (size_t)K * In);
+            return;
+        }
+        for (int k = 0; k < K; ++k)
+            for (int c = 0; c < L.pc; ++c)
+                for (int h = 0; h < L.ph; ++h)
+                    for (int w = 0; w < L.pw; ++w)
+                        dst[(size_t)k * In + ((size_t)c * L.ph + h) * L.pw + w] =
+                            src[(size_t)k * In + ((size_t)h * L.pw + w) * L.pc + c];
+        return;
+    }
+    const int C = L.d.cin, R = L.d.kh, S = L.d.kw;
+    for (int k = 0; k < K; ++k)
+        for (int c = 0; c < C; ++c)
+            for (int r = 0; r < R; ++r)
+                for (int s = 0; s < S; ++s)
+                    dst[(((size_t)k * C + c) * R + r) * S + s] = src[(((size_t)k * R + r) * S + s) * C + c];
+}
+
+// working copies of one layer's weights from its fp32 master
+hipError_t refresh_work(bapipe_stage *st, Layer &L)
+{
+    if (L.d.kind != BAPIPE_CONV2D && L.d.kind != BAPIPE_LINEAR) return hipSuccess;
+    hipError_t e = recast(st->dt, L.w, L.w_work, L.w_elems, st->stream);
+    if (e != hipSuccess) return e;
+    int R = L.d.kind == BAPIPE_LINEAR ? 1 : L.d.kh, S = L.d.kind == BAPIPE_LINEAR ? 1 : L.d.kw;
+    return make_dgrad_filter(st->dt, L.w, L.w_t, L.d.cout, R, S, L.d.cin, st->stream);
+}
+
+// ---------------------------------------------------------------- per-layer forward
+// xin: pointer used for tensor 0 when it is not stashed (caller's NHWC buffer)
+struct FwdCtx {
+    int mbid;
+    const void *x_direct;
+};
+
+const void *in_ptr(bapipe_stage *st, int t, const FwdCtx &c)
+{
+    int r = st->tensors[t].root;
+    if (r == 0 && c.x_direct) return c.x_direct;
+    return st->tptr(t, c.mbid);
+}
+
+int layer_forward(bapipe_stage *st, int li, const FwdCtx &c)
+{
+    Layer &L = st->layers[li];
+    const Tensor &O = st->tensors[L.o];
+    const void *a = in_ptr(st, L.a, c);
+    void *o = st->tptr(L.o, c.mbid);
+    hipStream_t s = st->stream;
+    const int dt = st->dt;
+    switch (L.d.kind) {
+    case BAPIPE_CONV2D:
+    case BAPIPE_LINEAR: {
+        GatherConv g = fwd_geom(st, L);
+        GradEpi none{nullptr, 0};
+        if (use_mfma_gather(st, g))
+            HIPCHK(conv_gather_mfma(a, L.w_work, L.bias, o, L.d.fuse_relu, none, g, s));
+        else
+            HIPCHK(conv_gather_direct(dt, a, L.w_work, L.bias, o, L.d.fuse_relu, none, g, s));
+        break;
+    }
+    case BAPIPE_RELU:
+        HIPCHK(relu_fwd(dt, a, o, O.elems, s));
+        break;
+    case BAPIPE_MAXPOOL2D: {
+        const Tensor &A = st->tensors[L.a];
+        HIPCHK(maxpool2x2_fwd(dt, a, o, (uint8_t *)(st->slot(c.mbid) + L.aux_off), st->mb, A.H, A.W, A.C, s));
+        break;
+    }
+    case BAPIPE_BATCHNORM2D: {
+        const Tensor &A = st->tensors[L.a];
+        HIPCHK(bn_fwd(dt, a, L.w, L.bias, L.d.eps, o, (float *)(st->slot(c.mbid) + L.aux_off), L.d.fuse_relu,
+                      st->mb * A.H * A.W, A.C, st->work, s));
+        break;
+    }
+    case BAPIPE_ADD:
+        HIPCHK(add_fwd(dt, a, in_ptr(st, L.b, c), o, L.d.fuse_relu, O.elems, s));
+        break;
+    case BAPIPE_FLATTEN:
+        break;   // alias of its input
+    case BAPIPE_SOFTMAX_XENT:
+        HIPCHK(softmax_fwd(dt, a, (float *)o, st->mb, O.C, s));
+        break;
+    default:
+        return st->fail(BAPIPE_E_UNSUPPORTED, "layer %d: kind %d", li, L.d.kind);
+    }
+    return BAPIPE_OK;
+}
+
+// ---------------------------------------------------------------- per-layer backward
+struct BwdCtx {
+    int mbid;
+    const void *x_direct;          // unused in backward (stage input is stashed when needed)
+    const void *dy_direct;         // caller's NHWC gradient used in place of grads[last]
+    void *dx_direct;               // caller's NHWC buffer used in place of grads[0]
+    const int32_t *labels;
+    std::vector<char> written;
+};
+
+void *grad_ptr(bapipe_stage *st, int t, BwdCtx &c)
+{
+    int r = st->tensors[t].root;
+    if (r == 0 && c.dx_direct) return c.dx_direct;
+    if (r == st->tensors[(int)st->tensors.size() - 1].root && c.dy_direct) return const_cast<void *>(c.dy_direct);
+    return st->gptr(t);
+}
+
+// epilogue for a write into the gradient of tensor t; pool_gate_t >= 0: the writer is a max-pool
+// whose own output (tensor pool_gate_t) carries the same sign information per window
+GradEpi epi_for(bapipe_stage *st, int t, BwdCtx &c, int pool_gate_t = -1)
+{
+    int r = st->tensors[t].root;
+    GradEpi e{nullptr, 0};
+    if (st->tensors[r].gated) e.gate = st->tptr(pool_gate_t >= 0 ? pool_gate_t : r, c.mbid);
+    e.accum = c.written[r] ? 1 : 0;
+    c.written[r] = 1;
+    return e;
+}
+
+int layer_backward(bapipe_stage *st, int li, BwdCtx &c)
+{
+    Layer &L = st->layers[li];
+    const Tensor &A = st->tensors[L.a];
+    const Tensor &O = st->tensors[L.o];
+    hipStream_t s = st->stream;
+    const int dt = st->dt;
+    const bool a_grad = st->tensors[A.root].need_grad;
+    switch (L.d.kind) {
+    case BAPIPE_CONV2D:
+    case BAPIPE_LINEAR: {
+        const void *g = grad_ptr(st, L.o, c);
+        const void *x = st->tptr(L.a, c.mbid);
+        ConvShape cs = conv_shape(st, L);
+        if (use_mfma_wgrad(st, cs))
+            HIPCHK(conv_wgrad_mfma(x, g, L.dw, st->work, cs, s));
+        else
+            HIPCHK(conv_wgrad_direct(dt, x, g, L.dw, st->work, cs, s));
+        if (L.db) HIPCHK(colsum_accumulate(dt, g, cs.N * cs.P * cs.Q, cs.K, L.db, st->work, s));
+        if (a_grad) {
+            GatherConv dg = dgrad_geom(st, L);
+            GradEpi e = epi_for(st, L.a, c);
+            void *dx = grad_ptr(st, L.a, c);
+            if (use_mfma_gather(st, dg))
+                HIPCHK(conv_gather_mfma(g, L.w_t, nullptr, dx, 0, e, dg, s));
+            else {
+                // the direct kernel takes the plain-store path unless told it writes a gradient
+                HIPCHK(conv_gather_direct(dt, g, L.w_t, nullptr, dx, 0, e, dg, s));
+            }
+        }
+        break;
+    }
+    case BAPIPE_RELU:
+        if (a_grad) {
+            GradEpi e = epi_for(st, L.a, c);
+            HIPCHK(relu_bwd(dt, st->tptr(L.o, c.mbid), grad_ptr(st, L.o, c), grad_ptr(st, L.a, c), e, O.elems, s));
+        }
+        break;
+    case BAPIPE_MAXPOOL2D:
+        if (a_grad) {
+            GradEpi e = epi_for(st, L.a, c, L.o);
+            HIPCHK(maxpool2x2_bwd(dt, grad_ptr(st, L.o, c), (const uint8_t *)(st->slot(c.mbid) + L.aux_off),
+                                  grad_ptr(st, L.a, c), e, st->mb, A.H, A.W, A.C, s));
+        }
+        break;
+    case BAPIPE_BATCHNORM2D: {
+        GradEpi e{nullptr, 0};
+        void *dx = nullptr;
+        if (a_grad) {
+            e = epi_for(st, L.a, c);
+            dx = grad_ptr(st, L.a, c);
+        }
+        HIPCHK(bn_bwd(dt, st->tptr(L.a, c.mbid), grad_ptr(st, L.o, c), L.w,
+                      (const float *)(st->slot(c.mbid) + L.aux_off), dx, L.dw, L.db, e, st->mb * A.H * A.W, A.C,
+                      st->work, s));
+        break;
+    }
+    case BAPIPE_ADD: {
+        const void *g = grad_ptr(st, L.o, c);
+        if (a_grad) {
+            GradEpi e = epi_for(st, L.a, c);
+            HIPCHK(grad_copy(dt, g, grad_ptr(st, L.a, c), e, O.elems, s));
+        }
+        if (st->tensors[st->tensors[L.b].root].need_grad) {
+            GradEpi e = epi_for(st, L.b, c);
+            HIPCHK(grad_copy(dt, g, grad_ptr(st, L.b, c), e, O.elems, s));
+        }
+        break;
+    }
+    case BAPIPE_FLATTEN:
+        break;
+    case BAPIPE_SOFTMAX_XENT:
+        if (a_grad) {
+            c.written[A.root] = 1;
+            HIPCHK(xent_bwd(dt, (const float *)st->tptr(L.o, c.mbid), c.labels, st->loss_scale,
+                            grad_ptr(st, L.a, c), st->losses + c.mbid, st->mb, O.C, s));
+        }
+        break;
+    default:
+        return st->fail(BAPIPE_E_UNSUPPORTED, "layer %d: kind %d", li, L.d.kind);
+    }
+    return BAPIPE_OK;
+}
+
+}  // namespace
+
+// ======================================================================== C ABI
+extern "C" {
+
+const char *bapipe_last_error(const bapipe_stage_t *st) { return st ? st->err.c_str() : g_create_error.c_str(); }
+
+void bapipe_stage_destroy(bapipe_stage_t *st)
+{
+    if (!st) return;
+    (void)hipStreamSynchronize(st->stream);
+    st->dev_free(st->params);
+    st->dev_free(st->stash);
+    st->dev_free(st->transient);
+    st->dev_free(st->grads);
+    st->dev_free(st->work);
+    st->dev_free(st->losses);
+    delete st;
+}
+
+int bapipe_stage_create(const bapipe_layer_desc_t *layers, int n_layers, int micro_batch, int n_micro,
+                        const bapipe_stage_opts_t *opts, bapipe_stage_t **out)
+{
+    if (!layers || !opts || !out) return create_fail(BAPIPE_E_INVALID, "NULL argument");
+    if (n_layers <= 0 || micro_batch <= 0 || n_micro <= 0)
+        return create_fail(BAPIPE_E_INVALID, "n_layers, micro_batch and n_micro must be positive");
+    if (opts->dtype != BAPIPE_FP32 && opts->dtype != BAPIPE_BF16) return create_fail(BAPIPE_E_INVALID, "bad dtype");
+    if (opts->io_layout != BAPIPE_NCHW && opts->io_layout != BAPIPE_NHWC)
+        return create_fail(BAPIPE_E_INVALID, "bad io_layout");
+    if (opts->schedule != BAPIPE_SCHED_1F1B && opts->schedule != BAPIPE_SCHED_1F1B_SO)
+        return create_fail(BAPIPE_E_INVALID, "bad schedule");
+    if (opts->n_stages < 1 || opts->stage_index < 1 || opts->stage_index > opts->n_stages)
+        return create_fail(BAPIPE_E_INVALID, "need 1 <= stage_index <= n_stages");
+    if (opts->in_c <= 0 || opts->in_h <= 0 || opts->in_w <= 0) return create_fail(BAPIPE_E_INVALID, "bad input shape");
+    if ((opts->mem.alloc == nullptr) != (opts->mem.free == nullptr))
+        return create_fail(BAPIPE_E_INVALID, "allocator needs both alloc and free");
+
+    bapipe_stage *st = new bapipe_stage();
+    struct Guard {
+        bapipe_stage *s;
+        ~Guard() { if (s) bapipe_stage_destroy(s); }
+    } guard{st};
+    st->opts = *opts;
+    st->dt = opts->dtype == BAPIPE_FP32 ? DT_F32 : DT_BF16;
+    st->mb = micro_batch;
+    st->M = n_micro;
+    st->stream = (hipStream_t)opts->hip_stream;
+    int live = opts->n_stages - opts->stage_index + 1;           // Table I/II: (N-i+1) micro-batches
+    if (opts->schedule == BAPIPE_SCHED_1F1B_SO) live *= 2;       // doubled warm-up (Table II)
+    st->depth = live < n_micro ? live : n_micro;
+    st->loss_scale = opts->loss_scale > 0.f ? opts->loss_scale : 1.0f / ((float)micro_batch * (float)n_micro);
+    st->loss_valid.assign(n_micro, 0);
+    const size_t es = dt_size(st->dt);
+
+    // ---- shape inference
+    st->tensors.resize(n_layers + 1);
+    {
+        Tensor &T = st->tensors[0];
+        T.C = opts->in_c; T.H = opts->in_h; T.W = opts->in_w;
+        T.elems = (size_t)micro_batch * T.C * T.H * T.W;
+        T.esize = es; T.root = 0; T.producer = -1;
+    }
+    st->layers.resize(n_layers);
+    for (int i = 0; i < n_layers; ++i) {
+        Layer &L = st->layers[i];
+        L.d = layers[i];
+        const bapipe_layer_desc_t &d = L.d;
+        if (d.src0 < -1 || d.src0 >= i) return create_fail(BAPIPE_E_SHAPE, "layer %d: src0=%d must name an earlier layer or -1", i, d.src0);
+        L.a = d.src0 + 1;
+        L.o = i + 1;
+        const Tensor A = st->tensors[L.a];
+        Tensor &O = st->tensors[L.o];
+        O.esize = es; O.root = L.o; O.producer = i;
+        if (A.esize != es) return create_fail(BAPIPE_E_SHAPE, "layer %d: consumes the softmax output", i);
+        switch (d.kind) {
+        case BAPIPE_CONV2D: {
+            if (d.kh <= 0 || d.kw <= 0 || d.stride <= 0 || d.pad < 0 || d.cin <= 0 || d.cout <= 0)
+                return create_fail(BAPIPE_E_INVALID, "layer %d: bad conv parameters", i);
+            if (d.kh != d.kw) return create_fail(BAPIPE_E_UNSUPPORTED, "layer %d: non-square filter", i);
+            if (d.pad > d.kh - 1) return create_fail(BAPIPE_E_UNSUPPORTED, "layer %d: pad > k-1", i);
+            if (A.C != d.cin) return create_fail(BAPIPE_E_SHAPE, "layer %d: cin=%d but input has %d channels", i, d.cin, A.C);
+            int ho = (A.H + 2 * d.pad - d.kh) / d.stride + 1, wo = (A.W + 2 * d.pad - d.kw) / d.stride + 1;
+            if (A.H + 2 * d.pad < d.kh || A.W + 2 * d.pad < d.kw || ho <= 0 || wo <= 0)
+                return create_fail(BAPIPE_E_SHAPE, "layer %d: filter larger than padded input", i);
+            O.C = d.cout; O.H = ho; O.W = wo;
+            L.w_elems = (size_t)d.cout * d.kh * d.kw * d.cin;
+            L.b_elems = d.has_bias ? d.cout : 0;
+            break;
+        }
+        case BAPIPE_LINEAR: {
+            if (d.cin <= 0 || d.cout <= 0) return create_fail(BAPIPE_E_INVALID, "layer %d: bad linear parameters", i);
+            if ((size_t)A.C * A.H * A.W != (size_t)d.cin)
+                return create_fail(BAPIPE_E_SHAPE, "layer %d: cin=%d but input has %zu features", i, d.cin, (size_t)A.C * A.H * A.W);
+            O.C = d.cout; O.H = O.W = 1;
+            L.w_elems = (size_t)d.cout * d.cin;
+            L.b_elems = d.has_bias ? d.cout : 0;
+            const Tensor &R = st->tensors[A.root];
+            if (R.H * R.W > 1) { L.permute_in = true; L.pc = R.C; L.ph = R.H; L.pw = R.W; }
+            break;
+        }
+        case BAPIPE_RELU:
+            O.C = A.C; O.H = A.H; O.W = A.W;
+            break;
+        case BAPIPE_MAXPOOL2D:
+            if (d.kh != 2 || d.kw != 2 || d.stride != 2 || d.pad != 0)
+                return create_fail(BAPIPE_E_UNSUPPORTED, "layer %d: only 2x2 stride-2 unpadded max-pool", i);
+            if (A.H < 2 || A.W < 2) return create_fail(BAPIPE_E_SHAPE, "layer %d: pool input smaller than window", i);
+            O.C = A.C; O.H = A.H / 2; O.W = A.W / 2;
+            break;
+        case BAPIPE_BATCHNORM2D:
+            if (d.cin != A.C || d.cout != A.C) return create_fail(BAPIPE_E_SHAPE, "layer %d: batch-norm over %d channels, input has %d", i, d.cin, A.C);
+            if (!(d.eps > 0.f)) return create_fail(BAPIPE_E_INVALID, "layer %d: eps must be positive", i);
+            O.C = A.C; O.H = A.H; O.W = A.W;
+            L.w_elems = A.C; L.b_elems = A.C;
+            break;
+        case BAPIPE_ADD: {
+            if (d.src1 < -1 || d.src1 >= i) return create_fail(BAPIPE_E_SHAPE, "layer %d: src1=%d must name an earlier layer or -1", i, d.src1);
+            L.b = d.src1 + 1;
+            const Tensor &B = st->tensors[L.b];
+            if (B.C != A.C || B.H != A.H || B.W != A.W) return create_fail(BAPIPE_E_SHAPE, "layer %d: add of different shapes", i);
+            if (L.a == L.b) return create_fail(BAPIPE_E_UNSUPPORTED, "layer %d: add of a tensor with itself", i);
+            O.C = A.C; O.H = A.H; O.W = A.W;
+            break;
+        }
+        case BAPIPE_FLATTEN:
+            O.C = A.C * A.H * A.W; O.H = O.W = 1;
+            O.root = A.root;
+            break;
+        case BAPIPE_SOFTMAX_XENT:
+            if (i != n_layers - 1) return create_fail(BAPIPE_E_SHAPE, "layer %d: softmax cross-entropy must be last", i);
+            if (A.H * A.W != 1) return create_fail(BAPIPE_E_SHAPE, "layer %d: softmax needs a (K,1,1) input", i);
+            O.C = A.C; O.H = O.W = 1;
+            O.esize = sizeof(float);
+            break;
+        default:
+            return create_fail(BAPIPE_E_INVALID, "layer %d: unknown kind %d", i, d.kind);
+        }
+        O.elems = (size_t)micro_batch * O.C * O.H * O.W;
+        st->tensors[L.a].consumers.push_back(i);
+        if (L.b >= 0) st->tensors[L.b].consumers.push_back(i);
+    }
+    const int nt = n_layers + 1, last_t = n_layers;
+    for (int t = 1; t < nt - 1; ++t)
+        if (st->tensors[t].consumers.empty())
+            return create_fail(BAPIPE_E_SHAPE, "layer %d: output is never used", t - 1);
+
+    // ---- what backward needs
+    for (int t = 1; t < nt; ++t) {
+        const Layer &P = st->layers[t - 1];
+        Tensor &T = st->tensors[t];
+        T.gated = (P.d.kind == BAPIPE_RELU) ||
+                  (P.d.fuse_relu && (P.d.kind == BAPIPE_CONV2D || P.d.kind == BAPIPE_LINEAR ||
+                                     P.d.kind == BAPIPE_BATCHNORM2D || P.d.kind == BAPIPE_ADD));
+        if (P.d.kind == BAPIPE_FLATTEN) T.gated = false;
+    }
+    // gate of an aliased tensor is the gate of its root
+    st->tensors[0].need_grad = opts->need_input_grad != 0;
+    for (int t = 1; t < nt; ++t) {
+        const Layer &P = st->layers[t - 1];
+        bool ng = has_params(P.d.kind) || st->tensors[st->tensors[P.a].root].need_grad;
+        if (P.b >= 0) ng = ng || st->tensors[st->tensors[P.b].root].need_grad;
+        st->tensors[t].need_grad = ng;
+    }
+    auto root_of = [&](int t) { return st->tensors[t].root; };
+    for (int i = 0; i < n_layers; ++i) {
+        const Layer &L = st->layers[i];
+        Tensor &RA = st->tensors[root_of(L.a)];
+        switch (L.d.kind) {
+        case BAPIPE_CONV2D: case BAPIPE_LINEAR: case BAPIPE_BATCHNORM2D:
+            RA.stashed = true;
+            break;
+        case BAPIPE_RELU: case BAPIPE_SOFTMAX_XENT:
+            st->tensors[L.o].stashed = true;
+            break;
+        case BAPIPE_MAXPOOL2D:
+            if (RA.gated && RA.need_grad) st->tensors[L.o].stashed = true;   // pooled values gate the window
+            break;
+        default:
+            break;
+        }
+        // a gated tensor is read again by every non-pool layer that writes its gradient
+        if (L.d.kind != BAPIPE_MAXPOOL2D && L.d.kind != BAPIPE_FLATTEN) {
+            if (RA.gated && RA.need_grad) RA.stashed = true;
+            if (L.b >= 0) {
+                Tensor &RB = st->tensors[root_of(L.b)];
+                if (RB.gated && RB.need_grad) RB.stashed = true;
+            }
+        }
+    }
+    if (st->tensors[root_of(last_t)].gated) st->tensors[root_of(last_t)].stashed = true;   // gates the caller's dy
+    if (st->layers[n_layers - 1].d.kind == BAPIPE_SOFTMAX_XENT) {
+        const Tensor &Z = st->tensors[root_of(st->layers[n_layers - 1].a)];
+        if (Z.gated || Z.consumers.size() > 1)
+            return create_fail(BAPIPE_E_UNSUPPORTED, "softmax input must be an un-gated tensor used only by the loss");
+    }
+
+    // ---- memory plan
+    size_t slot = 0, trans = 0, gr = 0;
+    for (int t = 0; t < nt; ++t) {
+        Tensor &T = st->tensors[t];
+        if (T.root != t) continue;
+        if (T.stashed) { T.off = slot; slot += align_up(T.bytes()); }
+        else { T.off = trans; trans += align_up(T.bytes()); }
+        if (T.need_grad && t != last_t) { T.goff = gr; gr += align_up(T.bytes()); }
+    }
+    {   // gradient of the stage output (ingest target when the caller's dy cannot be used in place)
+        Tensor &T = st->tensors[root_of(last_t)];
+        if (st->layers[n_layers - 1].d.kind != BAPIPE_SOFTMAX_XENT && root_of(last_t) == last_t) { T.goff = gr; gr += align_up(T.bytes()); }
+    }
+    size_t work = 256;
+    for (int i = 0; i < n_layers; ++i) {
+        Layer &L = st->layers[i];
+        const Tensor &A = st->tensors[L.a];
+        if (L.d.kind == BAPIPE_MAXPOOL2D) { L.aux_off = slot; L.aux_bytes = st->tensors[L.o].elems; slot += align_up(L.aux_bytes); }
+        if (L.d.kind == BAPIPE_BATCHNORM2D) {
+            L.aux_off = slot; L.aux_bytes = 2 * sizeof(float) * A.C; slot += align_up(L.aux_bytes);
+            size_t w = bn_workspace(micro_batch * A.H * A.W, A.C);
+            work = w > work ? w : work;
+        }
+        if (L.d.kind == BAPIPE_CONV2D || L.d.kind == BAPIPE_LINEAR) {
+            ConvShape cs = conv_shape(st, L);
+            size_t w = use_mfma_wgrad(st, cs) ? conv_wgrad_mfma_workspace(cs) : conv_wgrad_direct_workspace(cs);
+            work = w > work ? w : work;
+            w = colsum_workspace(cs.N * cs.P * cs.Q, cs.K);
+            work = w > work ? w : work;
+        }
+    }
+    st->slot_bytes = align_up(slot);
+    st->transient_bytes = trans;
+    st->grads_bytes = gr;
+    st->work_bytes = work;
+
+    size_t pb = 0;
+    std::vector<size_t> o_w(n_layers), o_b(n_layers), o_dw(n_layers), o_db(n_layers), o_ww(n_layers), o_wt(n_layers);
+    for (int i = 0; i < n_layers; ++i) { const Layer &L = st->layers[i]; o_w[i] = pb; pb += align_up(L.w_elems * 4); o_b[i] = pb; pb += align_up(L.b_elems * 4); }
+    st->accum_off = pb;
+    for (int i = 0; i < n_layers; ++i) { const Layer &L = st->layers[i]; o_dw[i] = pb; pb += align_up(L.w_elems * 4); o_db[i] = pb; pb += align_up(L.b_elems * 4); }
+    st->accum_bytes = pb - st->accum_off;
+    for (int i = 0; i < n_layers; ++i) {
+        const Layer &L = st->layers[i];
+        bool mat = L.d.kind == BAPIPE_CONV2D || L.d.kind == BAPIPE_LINEAR;
+        o_ww[i] = pb; pb += mat ? align_up(L.w_elems * es) : 0;
+        o_wt[i] = pb; pb += mat ? align_up(L.w_elems * es) : 0;
+    }
+    st->params_bytes = pb;
+
+    if (hipSuccess != hipGetLastError()) { /* clear stale error state */ }
+    st->params = (char *)st->dev_alloc(st->params_bytes);
+    st->stash = (char *)st->dev_alloc(st->slot_bytes * st->depth);
+    st->transient = (char *)st->dev_alloc(st->transient_bytes);
+    st->grads = (char *)st->dev_alloc(st->grads_bytes);
+    st->work = (char *)st->dev_alloc(st->work_bytes);
+    st->losses = (float *)st->dev_alloc(sizeof(float) * n_micro);
+    if (!st->params || !st->stash || !st->transient || !st->grads || !st->work || !st->losses)
+        return create_fail(BAPIPE_E_OOM, "device allocation failed (params %zu, stash %zu x %d, transient %zu, grads %zu, work %zu bytes)",
+                           st->params_bytes, st->slot_bytes, st->depth, st->transient_bytes, st->grads_bytes, st->work_bytes);
+    for (int i = 0; i < n_layers; ++i) {
+        Layer &L = st->layers[i];
+        if (!L.w_elems) continue;
+        L.w = (float *)(st->params + o_w[i]);
+        L.dw = (float *)(st->params + o_dw[i]);
+        if (L.b_elems) { L.bias = (float *)(st->params + o_b[i]); L.db = (float *)(st->params + o_db[i]); }
+        if (L.d.kind != BAPIPE_BATCHNORM2D) { L.w_work = st->params + o_ww[i]; L.w_t = st->params + o_wt[i]; }
+    }
+    // parameters start at zero (gamma at one); all of it through kernels on the stage's stream
+    hipError_t e = fill_f32((float *)st->params, 0.f, st->params_bytes / 4, st->stream);
+    for (int i = 0; i < n_layers && e == hipSuccess; ++i)
+        if (st->layers[i].d.kind == BAPIPE_BATCHNORM2D) e = fill_f32(st->layers[i].w, 1.f, st->layers[i].w_elems, st->stream);
+    if (e == hipSuccess) e = fill_f32(st->losses, 0.f, n_micro, st->stream);
+    if (e == hipSuccess) e = hipStreamSynchronize(st->stream);
+    if (e != hipSuccess) return create_fail(BAPIPE_E_DEVICE, "initialisation: %s", hipGetErrorString(e));
+    guard.s = nullptr;
+    *out = st;
+    return BAPIPE_OK;
+}
+
+int bapipe_stage_forward(bapipe_stage_t *st, int mb_id, const void *x_dev, void *y_dev)
+{
+    if (!st || !x_dev) return st ? st->fail(BAPIPE_E_INVALID, "forward: NULL argument") : BAPIPE_E_INVALID;
+    if (mb_id != st->n_fwd || mb_id >= st->M)
+        return st->fail(BAPIPE_E_ORDER, "forward: expected micro-batch %d of %d, got %d", st->n_fwd, st->M, mb_id);
+    if (st->n_fwd - st->n_bwd >= st->depth)
+        return st->fail(BAPIPE_E_ORDER, "forward: %d micro-batches already in flight (stash depth %d)", st->n_fwd - st->n_bwd, st->depth);
+    const Tensor &In = st->tensors[0];
+    const int dt = st->dt;
+    hipStream_t s = st->stream;
+    FwdCtx c{mb_id, nullptr};
+    GradEpi none{nullptr, 0};
+    if (st->opts.io_layout == BAPIPE_NCHW) {
+        HIPCHK(nchw_to_nhwc(dt, x_dev, st->tptr(0, mb_id), none, st->mb, In.C, In.H, In.W, s));
+    } else if (In.stashed) {
+        HIPCHK(hipMemcpyAsync(st->tptr(0, mb_id), x_dev, In.bytes(), hipMemcpyDeviceToDevice, s));
+    } else {
+        c.x_direct = x_dev;
+    }
+    for (int i = 0; i < (int)st->layers.size(); ++i) {
+        int rc = layer_forward(st, i, c);
+        if (rc != BAPIPE_OK) return rc;
+    }
+    if (y_dev) {
+        const int last = (int)st->tensors.size() - 1;
+        const Tensor &O = st->tensors[last];
+        const void *src = in_ptr(st, last, c);
+        if (st->opts.io_layout == BAPIPE_NCHW && O.esize == dt_size(dt) && O.H * O.W > 1)
+            HIPCHK(nhwc_to_nchw(dt, src, y_dev, st->mb, O.C, O.H, O.W, s));
+        else
+            HIPCHK(hipMemcpyAsync(y_dev, src, O.bytes(), hipMemcpyDeviceToDevice, s));
+    }
+    st->n_fwd++;
+    return BAPIPE_OK;
+}
+
+int bapipe_stage_backward(bapipe_stage_t *st, int mb_id, const void *dy_dev_or_labels, void *dx_dev)
+{
+    if (!st || !dy_dev_or_labels) return st ? st->fail(BAPIPE_E_INVALID, "backward: NULL argument") : BAPIPE_E_INVALID;
+    if (mb_id != st->n_bwd || mb_id >= st->n_fwd)
+        return st->fail(BAPIPE_E_ORDER, "backward: expected micro-batch %d (forwarded so far: %d), got %d", st->n_bwd, st->n_fwd, mb_id);
+    const int nl = (int)st->layers.size(), last = nl;
+    const int dt = st->dt;
+    hipStream_t s = st->stream;
+    const bool nhwc = st->opts.io_layout == BAPIPE_NHWC;
+    BwdCtx c;
+    c.mbid = mb_id;
+    c.x_direct = nullptr;
+    c.dy_direct = nullptr;
+    c.dx_direct = nullptr;
+    c.labels = nullptr;
+    c.written.assign(st->tensors.size(), 0);
+    const Tensor &In = st->tensors[0];
+    const bool want_dx = In.need_grad && dx_dev != nullptr;
+    if (want_dx && (nhwc || In.H * In.W == 1)) c.dx_direct = dx_dev;
+    if (st->layers[nl - 1].d.kind == BAPIPE_SOFTMAX_XENT) {
+        c.labels = (const int32_t *)dy_dev_or_labels;
+    } else {
+        const int r = st->tensors[last].root;
+        const Tensor &O = st->tensors[last];
+        GradEpi e{nullptr, 0};
+        if (st->tensors[r].gated) e.gate = st->tptr(r, mb_id);
+        if (!nhwc && O.H * O.W > 1) {
+            HIPCHK(nchw_to_nhwc(dt, dy_dev_or_labels, st->gptr(last), e, st->mb, O.C, O.H, O.W, s));
+        } else if (e.gate || r == 0) {
+            HIPCHK(grad_copy(dt, dy_dev_or_labels, st->gptr(last), e, O.elems, s));
+        } else {
+            c.dy_direct = dy_dev_or_labels;
+        }
+        c.written[r] = 1;
+    }
+    for (int i = nl - 1; i >= 0; --i) {
+        int rc = layer_backward(st, i, c);
+        if (rc != BAPIPE_OK) return rc;
+    }
+    if (want_dx && !c.dx_direct)
+        HIPCHK(nhwc_to_nchw(dt, st->gptr(0), dx_dev, st->mb, In.C, In.H, In.W, s));
+    if (c.labels) st->loss_valid[mb_id] = 1;
+    st->n_bwd++;
+    return BAPIPE_OK;
+}
+
+int bapipe_stage_step(bapipe_stage_t *st, float lr)
+{
+    if (!st) return BAPIPE_E_INVALID;
+    if (st->n_bwd != st->M)
+        return st->fail(BAPIPE_E_ORDER, "step: %d of %d backward passes done", st->n_bwd, st->M);
+    for (auto &L : st->layers) {
+        if (!L.w_elems) continue;
+        const bool mat = L.d.kind != BAPIPE_BATCHNORM2D;
+        HIPCHK(sgd_step(st->dt, L.w, L.dw, lr, mat ? L.w_work : nullptr, L.w_elems, st->stream));
+        if (L.b_elems) HIPCHK(sgd_step(st->dt, L.bias, L.db, lr, nullptr, L.b_elems, st->stream));
+        if (mat) {
+            int R = L.d.kind == BAPIPE_LINEAR ? 1 : L.d.kh, S = L.d.kind == BAPIPE_LINEAR ? 1 : L.d.kw;
+            HIPCHK(make_dgrad_filter(st->dt, L.w, L.w_t, L.d.cout, R, S, L.d.cin, st->stream));
+        }
+    }
+    st->n_fwd = st->n_bwd = 0;
+    return BAPIPE_OK;
+}
+
+int bapipe_stage_set_params(bapipe_stage_t *st, int layer, const float *w_host, const float *b_host)
+{
+    if (!st) return BAPIPE_E_INVALID;
+    if (layer < 0 || layer >= (int)st->layers.size() || !st->layers[layer].w_elems)
+        return st->fail(BAPIPE_E_INVALID, "set_params: layer %d has no parameters", layer);
+    Layer &L = st->layers[layer];
+    HIPCHK(hipStreamSynchronize(st->stream));
+    if (w_host) {
+        if (L.d.kind == BAPIPE_BATCHNORM2D) {
+            HIPCHK(hipMemcpy(L.w, w_host, L.w_elems * 4, hipMemcpyHostToDevice));
+        } else {
+            std::vector<float> tmp(L.w_elems);
+            to_internal(L, w_host, tmp.data());
+            HIPCHK(hipMemcpy(L.w, tmp.data(), L.w_elems * 4, hipMemcpyHostToDevice));
+            HIPCHK(refresh_work(st, L));
+            HIPCHK(hipStreamSynchronize(st->stream));
+        }
+    }
+    if (b_host) {
+        if (!L.b_elems) return st->fail(BAPIPE_E_INVALID, "set_params: layer %d has no bias", layer);
+        HIPCHK(hipMemcpy(L.bias, b_host, L.b_elems * 4, hipMemcpyHostToDevice));
+    }
+    return BAPIPE_OK;
+}
+
+static int get_vectors(bapipe_stage_t *st, int layer, float *w_host, float *b_host, bool grads, const char *what)
+{
+    if (!st) return BAPIPE_E_INVALID;
+    if (layer < 0 || layer >= (int)st->layers.size() || !st->layers[layer].w_elems)
+        return st->fail(BAPIPE_E_INVALID, "%s: layer %d has no parameters", what, layer);
+    Layer &L = st->layers[layer];
+    HIPCHK(hipStreamSynchronize(st->stream));
+    if (w_host) {
+        const float *src = grads ? L.dw : L.w;
+        if (L.d.kind == BAPIPE_BATCHNORM2D) {
+            HIPCHK(hipMemcpy(w_host, src, L.w_elems * 4, hipMemcpyDeviceToHost));
+        } else {
+            std::vector<float> tmp(L.w_elems);
+            HIPCHK(hipMemcpy(tmp.data(), src, L.w_elems * 4, hipMemcpyDeviceToHost));
+            from_internal(L, tmp.data(), w_host);
+        }
+    }
+    if (b_host) {
+        if (!L.b_elems) return st->fail(BAPIPE_E_INVALID, "%s: layer %d has no bias", what, layer);
+        HIPCHK(hipMemcpy(b_host, grads ? L.db : L.bias, L.b_elems * 4, hipMemcpyDeviceToHost));
+    }
+    return BAPIPE_OK;
+}
+
+int bapipe_stage_get_params(bapipe_stage_t *st, int layer, float *w_host, float *b_host)
+{
+    return get_vectors(st, layer, w_host, b_host, false, "get_params");
+}
+
+int bapipe_stage_get_grads(bapipe_stage_t *st, int layer, float *dw_host, float *db_host)
+{
+    return get_vectors(st, layer, dw_host, db_host, true, "get_grads");
+}
+
+int bapipe_stage_get_pool_indices(bapipe_stage_t *st, int layer, int mb_id, uint8_t *idx_host)
+{
+    if (!st || !idx_host) return st ? st->fail(BAPIPE_E_INVALID, "get_pool_indices: NULL argument") : BAPIPE_E_INVALID;
+    if (layer < 0 || layer >= (int)st->layers.size() || st->layers[layer].d.kind != BAPIPE_MAXPOOL2D)
+        return st->fail(BAPIPE_E_INVALID, "get_pool_indices: layer %d is not a max-pool", layer);
+    if (mb_id < st->n_bwd || mb_id >= st->n_fwd)
+        return st->fail(BAPIPE_E_ORDER, "get_pool_indices: micro-batch %d is not in flight", mb_id);
+    const Layer &L = st->layers[layer];
+    const Tensor &O = st->tensors[L.o];
+    // NHWC on the device -> NCHW for the caller, through the workspace if it is large enough
+    std::vector<uint8_t> tmp(O.elems);
+    HIPCHK(hipStreamSynchronize(st->stream));
+    HIPCHK(hipMemcpy(tmp.data(), st->slot(mb_id) + L.aux_off, O.elems, hipMemcpyDeviceToHost));
+    const int N = st->mb, C = O.C, H = O.H, W = O.W;
+    for (int n = 0; n < N; ++n)
+        for (int c = 0; c < C; ++c)
+            for (int h = 0; h < H; ++h)
+                for (int w = 0; w < W; ++w)
+                    idx_host[(((size_t)n * C + c) * H + h) * W + w] = tmp[(((size_t)n * H + h) * W + w) * C + c];
+    return BAPIPE_OK;
+}
+
+int bapipe_stage_get_loss(bapipe_stage_t *st, int mb_id, float *loss_host)
+{
+    if (!st || !loss_host) return st ? st->fail(BAPIPE_E_INVALID, "get_loss: NULL argument") : BAPIPE_E_INVALID;
+    if (st->layers.back().d.kind != BAPIPE_SOFTMAX_XENT) return st->fail(BAPIPE_E_ORDER, "get_loss: stage has no loss layer");
+    if (mb_id < 0 || mb_id >= st->M || !st->loss_valid[mb_id])
+        return st->fail(BAPIPE_E_ORDER, "get_loss: micro-batch %d has not been backwarded", mb_id);
+    HIPCHK(hipStreamSynchronize(st->stream));
+    HIPCHK(hipMemcpy(loss_host, st->losses + mb_id, sizeof(float), hipMemcpyDeviceToHost));
+    return BAPIPE_OK;
+}
+
+int bapipe_stage_stash_bytes(const bapipe_stage_t *st, uint64_t *per_mb, int *depth)
+{
+    if (!st) return BAPIPE_E_INVALID;
+    if (per_mb) *per_mb = st->slot_bytes;
+    if (depth) *depth = st->depth;
+    return BAPIPE_OK;
+}
+
+int bapipe_profile_layers(bapipe_stage_t *st, int warmup, int iters, bapipe_layer_profile_t *out, int cap, int *n)
+{
+    if (!st || !out || !n || iters <= 0 || warmup < 0) return st ? st->fail(BAPIPE_E_INVALID, "profile: bad argument") : BAPIPE_E_INVALID;
+    const int nl = (int)st->layers.size();
+    if (cap < nl) return st->fail(BAPIPE_E_INVALID, "profile: %d records needed, cap is %d", nl, cap);
+    if (st->n_fwd != 0) return st->fail(BAPIPE_E_ORDER, "profile: only between mini-batches (after create or step)");
+    hipStream_t s = st->stream;
+    // defined (zero) scratch data in slot 0, the transient arena and the gradient buffers
+    HIPCHK(fill_f32((float *)st->slot(0), 0.f, st->slot_bytes / 4, s));
+    HIPCHK(fill_f32((float *)st->transient, 0.f, st->transient_bytes / 4, s));
+    HIPCHK(fill_f32((float *)st->grads, 0.f, st->grads_bytes / 4, s));
+    hipEvent_t e0, e1;
+    HIPCHK(hipEventCreate(&e0));
+    HIPCHK(hipEventCreate(&e1));
+    int rc = BAPIPE_OK;
+    FwdCtx fc{0, nullptr};
+    std::vector<int32_t> zero_labels(st->mb, 0);
+    int32_t *labels_dev = (int32_t *)st->work;   // xent reads labels only; no kernel of that layer uses the workspace
+    for (int i = 0; i < nl && rc == BAPIPE_OK; ++i) {
+        Layer &L = st->layers[i];
+        const Tensor &O = st->tensors[L.o];
+        float ms = 0.f;
+        for (int k = 0; k < warmup && rc == BAPIPE_OK; ++k) rc = layer_forward(st, i, fc);
+        if (rc != BAPIPE_OK) break;
+        (void)hipEventRecord(e0, s);
+        for (int k = 0; k < iters && rc == BAPIPE_OK; ++k) rc = layer_forward(st, i, fc);
+        (void)hipEventRecord(e1, s);
+        if (hipEventSynchronize(e1) != hipSuccess) { rc = st->fail(BAPIPE_E_DEVICE, "profile: event sync failed"); break; }
+        (void)hipEventElapsedTime(&ms, e0, e1);
+        out[i].fwd_ms = ms / iters;
+
+        BwdCtx bc;
+        bc.mbid = 0; bc.x_direct = bc.dy_direct = nullptr; bc.dx_direct = nullptr; bc.labels = nullptr;
+        if (L.d.kind == BAPIPE_SOFTMAX_XENT) {
+            if (hipMemcpyAsync(labels_dev, zero_labels.data(), sizeof(int32_t) * st->mb, hipMemcpyHostToDevice, s) != hipSuccess) { rc = st->fail(BAPIPE_E_DEVICE, "profile: label upload"); break; }
+            (void)hipStreamSynchronize(s);
+            bc.labels = labels_dev;
+        }
+        for (int k = 0; k < warmup + iters && rc == BAPIPE_OK; ++k) {
+            if (k == warmup) (void)hipEventRecord(e0, s);
+            bc.written.assign(st->tensors.size(), 0);
+            rc = layer_backward(st, i, bc);
+        }
+        (void)hipEventRecord(e1, s);
+        if (hipEventSynchronize(e1) != hipSuccess) { rc = st->fail(BAPIPE_E_DEVICE, "profile: event sync failed"); break; }
+        (void)hipEventElapsedTime(&ms, e0, e1);
+        out[i].bwd_ms = ms / iters;
+        out[i].weight_bytes = (uint64_t)(L.w_elems + L.b_elems) * 4;
+        out[i].out_feature_bytes = (uint64_t)O.bytes();
+        uint64_t sb = L.aux_bytes;
+        if (O.root == L.o && O.stashed) sb += O.bytes();
+        out[i].stash_bytes = sb;
+    }
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    // the timed backward passes added into the accumulators: restore zeros and the loss slots
+    if (rc == BAPIPE_OK) {
+        HIPCHK(fill_f32((float *)(st->params + st->accum_off), 0.f, st->accum_bytes / 4, s));
+        HIPCHK(fill_f32(st->losses, 0.f, st->M, s));
+        HIPCHK(hipStreamSynchronize(s));
+        *n = nl;
+    }
+    return rc;
+}
+
+}  // extern "C"

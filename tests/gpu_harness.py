@@ -1,0 +1,209 @@
+"""Shared helpers of the GPU parity tests: run a workload through the C ABI (via the ctypes
+binding) and through the CPU oracle on the same seeded inputs, and compare tensor by tensor.
+Only marshalling happens here (dtype / layout conversion of inputs and outputs)."""
+import ctypes as ct
+
+import numpy as np
+import torch
+
+from oracle.stage import OracleStage, one_f_one_b_order
+from paper_2012_12544_amd import binding as B
+from stage_inputs import configs as C
+from stage_inputs import gen
+
+DEV = "cuda:0"
+TOL = {C.FP32: 1e-4, C.BF16: 2e-2}     # max|gpu-ref| / max|ref|, per tensor
+
+
+def tdtype(stage):
+    return torch.bfloat16 if stage["dtype"] == C.BF16 else torch.float32
+
+
+def to_dev(stage, a_nchw, layout):
+    """numpy NCHW float32 -> device tensor of the stage's storage type in the io layout."""
+    t = torch.from_numpy(np.ascontiguousarray(a_nchw)).to(DEV)
+    if layout == B.NHWC and t.dim() == 4:
+        t = t.permute(0, 2, 3, 1)
+    return t.contiguous().to(tdtype(stage))
+
+
+def from_dev(t, shape_nchw, layout):
+    """device tensor in io layout -> numpy float64 NCHW."""
+    t = t.to(torch.float32)
+    if layout == B.NHWC and len(shape_nchw) == 4:
+        n, c, h, w = shape_nchw
+        t = t.reshape(n, h, w, c).permute(0, 3, 1, 2)
+    return t.contiguous().cpu().numpy().astype(np.float64).reshape(shape_nchw)
+
+
+def rel_err(got, ref):
+    ref = np.asarray(ref, np.float64)
+    got = np.asarray(got, np.float64)
+    assert got.shape == ref.shape, (got.shape, ref.shape)
+    if not np.all(np.isfinite(got)):
+        return float("inf")
+    d = np.max(np.abs(got - ref)) if ref.size else 0.0
+    m = np.max(np.abs(ref)) if ref.size else 0.0
+    return d / m if m > 0 else d
+
+
+class GpuStage:
+    def __init__(self, stage, params, layout=B.NHWC, loss_scale=0.0, use_torch_alloc=True, stream=None):
+        self.stage = stage
+        self.layout = layout
+        self.alloc = B.TorchAllocator(DEV) if use_torch_alloc else None
+        self.stream = stream if stream is not None else torch.cuda.Stream(device=DEV)
+        self.opts = B.make_opts(stage, io_layout=layout, stream=self.stream.cuda_stream,
+                                allocator=self.alloc, loss_scale=loss_scale)
+        self.h = B.bapipe_stage_create(stage["layers"], stage["micro_batch"], stage["n_micro"], self.opts)
+        self.shapes = C.infer_shapes(stage)
+        self.params = params
+        for i, (w, b) in enumerate(params):
+            if w is not None:
+                B.bapipe_stage_set_params(self.h, i, w, b)
+        self.keep = []
+        self.is_loss = gen.ends_in_loss(stage)
+
+    def close(self):
+        if self.h is not None:
+            B.bapipe_stage_destroy(self.h)
+            self.h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def out_shape(self):
+        return (self.stage["micro_batch"],) + tuple(self.shapes[-1])
+
+    def in_shape(self):
+        s = self.stage
+        return (s["micro_batch"], s["in_c"], s["in_h"], s["in_w"])
+
+    def forward(self, mb, x_nchw):
+        x = to_dev(self.stage, x_nchw, self.layout)
+        n = int(np.prod(self.out_shape()))
+        y = torch.empty(n, dtype=torch.float32 if self.is_loss else tdtype(self.stage), device=DEV)
+        torch.cuda.synchronize()
+        B.bapipe_stage_forward(self.h, mb, x.data_ptr(), y.data_ptr())
+        self.stream.synchronize()
+        return from_dev(y, self.out_shape(), self.layout)
+
+    def backward(self, mb, dy_or_labels, want_dx=True):
+        if self.is_loss:
+            g = torch.from_numpy(np.ascontiguousarray(dy_or_labels, np.int32)).to(DEV)
+        else:
+            g = to_dev(self.stage, dy_or_labels, self.layout)
+        dx = None
+        if self.stage["need_input_grad"] and want_dx:
+            dx = torch.empty(int(np.prod(self.in_shape())), dtype=tdtype(self.stage), device=DEV)
+        torch.cuda.synchronize()
+        B.bapipe_stage_backward(self.h, mb, g.data_ptr(), None if dx is None else dx.data_ptr())
+        self.stream.synchronize()
+        return None if dx is None else from_dev(dx, self.in_shape(), self.layout)
+
+    def grads(self, i):
+        w, b = self.params[i]
+        return B.bapipe_stage_get_grads(self.h, i, None if w is None else w.shape, None if b is None else b.shape)
+
+    def get_params(self, i):
+        w, b = self.params[i]
+        return B.bapipe_stage_get_params(self.h, i, None if w is None else w.shape, None if b is None else b.shape)
+
+    def pool_indices(self, layer, mb):
+        shp = (self.stage["micro_batch"],) + tuple(self.shapes[layer])
+        return B.bapipe_stage_get_pool_indices(self.h, layer, mb, shp)
+
+
+def stage_io(stage):
+    M = stage["n_micro"]
+    xs = [gen.stage_input(stage, m) for m in range(M)]
+    if gen.ends_in_loss(stage):
+        gs = [gen.labels(stage, m) for m in range(M)]
+    else:
+        gs = [gen.upstream_grad(stage, m) for m in range(M)]
+    return xs, gs
+
+
+def pool_index_mismatch_ok(orc_stash_x, layer_in, idx_ref, idx_gpu, bf16):
+    """Where the arg-max differs, the oracle's window must hold (nearly) tied top values."""
+    bad = np.argwhere(idx_ref != idx_gpu)
+    for n, c, p, q in bad:
+        win = layer_in[n, c, 2 * p:2 * p + 2, 2 * q:2 * q + 2].reshape(-1)
+        a, b = win[idx_ref[n, c, p, q]], win[idx_gpu[n, c, p, q]]
+        tol = (2.0 ** -7 if bf16 else 1e-6) * max(abs(a), abs(b), 1e-30)
+        if abs(a - b) > tol:
+            return False
+    return True
+
+
+def compare_minibatch(stage, layout=B.NHWC, perturb=True, order=None, lr=0.05, check_pool=True,
+                      tol=None, verbose=None):
+    """Full parity of one mini-batch: y, dx per micro-batch, pool indices, loss, every weight
+    gradient after M micro-batches and the updated weights after step.  Returns the worst
+    relative errors by tensor name."""
+    tol = TOL[stage["dtype"]] if tol is None else tol
+    params = gen.all_params(stage, perturb=perturb)
+    xs, gs = stage_io(stage)
+    orc = OracleStage(stage, params)
+    gpu = GpuStage(stage, params, layout=layout)
+    M = stage["n_micro"]
+    order = order or one_f_one_b_order(M, orc.depth)
+    per, depth = B.bapipe_stage_stash_bytes(gpu.h)
+    assert depth == orc.depth
+    errs = {}
+    bf16 = stage["dtype"] == C.BF16
+    pools = [i for i, L in enumerate(stage["layers"]) if L["kind"] == C.MAXPOOL2D]
+    exact_pool = True
+    for t, m in order:
+        if t == "F":
+            y_ref = orc.forward(m, xs[m])
+            y = gpu.forward(m, xs[m])
+            errs["y%d" % m] = rel_err(y, y_ref)
+            if check_pool:
+                for li in pools:
+                    ir, ig = orc.pool_indices(m, li), gpu.pool_indices(li, m)
+                    assert ig.max() < 4
+                    if not np.array_equal(ir, ig):
+                        exact_pool = False
+                        src = stage["layers"][li]["src0"]
+                        xin = orc.stash[m][0] if src < 0 else orc.stash[m][1][src]
+                        assert pool_index_mismatch_ok(None, xin, ir, ig, bf16), "pool arg-max differs beyond a tie"
+                        frac = np.mean(ir != ig)
+                        assert frac < (5e-3 if bf16 else 1e-5), frac
+        else:
+            dx_ref = orc.backward(m, gs[m])
+            dx = gpu.backward(m, gs[m])
+            if dx_ref is not None:
+                errs["dx%d" % m] = rel_err(dx, dx_ref)
+            if gpu.is_loss:
+                l_ref, l = orc.loss[m], B.bapipe_stage_get_loss(gpu.h, m)
+                errs["loss%d" % m] = abs(l - l_ref) / max(abs(l_ref), 1e-30)
+    for i, (w, b) in enumerate(params):
+        if w is None:
+            continue
+        dw, db = gpu.grads(i)
+        errs["dw%d" % i] = rel_err(dw, orc.dw[i])
+        if b is not None:
+            errs["db%d" % i] = rel_err(db, orc.db[i])
+    orc.step(lr)
+    B.bapipe_stage_step(gpu.h, lr)
+    for i, (w, b) in enumerate(params):
+        if w is None:
+            continue
+        w2, b2 = gpu.get_params(i)
+        errs["w%d" % i] = rel_err(w2, orc.w[i])
+        if b is not None:
+            errs["b%d" % i] = rel_err(b2, orc.b[i])
+        dw, db = gpu.grads(i)
+        assert not dw.any(), "step must clear the accumulators"
+    gpu.close()
+    worst = max(errs.values())
+    if verbose:
+        print(verbose, "worst rel err %.3e" % worst, "exact pool idx" if exact_pool else "pool idx tie-level diffs",
+              {k: "%.2e" % v for k, v in sorted(errs.items(), key=lambda kv: -kv[1])[:4]}, flush=True)
+    bad = {k: v for k, v in errs.items() if not (v <= tol)}
+    assert not bad, (stage["name"], bad)
+    return errs

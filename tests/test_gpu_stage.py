@@ -1,0 +1,126 @@
+"""GPU parity: the HIP library (through its C ABI) against the CPU oracle, element by element,
+on seeded workloads small enough for the oracle yet spanning several tiles with ragged tails."""
+import numpy as np
+import pytest
+
+from gpu_harness import GpuStage, compare_minibatch, stage_io
+from oracle.stage import one_f_one_b_order
+from paper_2012_12544_amd import binding as B
+from stage_inputs import configs as C
+from stage_inputs import gen
+
+pytestmark = pytest.mark.gpu
+
+
+def single(kind_builder, cin, hw, dtype, micro_batch=3, n_micro=2, need_input_grad=1, name="single"):
+    b = C._Builder()
+    kind_builder(b)
+    return C._stage(name, b.layers, dtype, (cin, hw[0], hw[1]), micro_batch, n_micro, 1, 2,
+                    need_input_grad, C.BASE_SEED + 77, "kaiming")
+
+
+DT = [C.FP32, C.BF16]
+
+
+@pytest.mark.parametrize("dtype", DT)
+@pytest.mark.parametrize("k,stride,cin,cout,hw,relu", [
+    (3, 1, 3, 16, (9, 11), 1), (3, 1, 16, 24, (13, 10), 1), (3, 2, 8, 16, (15, 14), 0),
+    (1, 1, 16, 40, (7, 9), 0), (1, 2, 24, 8, (9, 9), 1), (3, 1, 5, 7, (6, 5), 0),
+])
+def test_conv_layer(dtype, k, stride, cin, cout, hw, relu):
+    st = single(lambda b: b.conv(cin, cout, k, stride=stride, relu=relu, src=-1), cin, hw, dtype)
+    compare_minibatch(st, verbose="conv k%d s%d %d->%d" % (k, stride, cin, cout))
+
+
+@pytest.mark.parametrize("dtype", DT)
+@pytest.mark.parametrize("layout", [B.NCHW, B.NHWC])
+def test_relu_pool_layers_and_layouts(dtype, layout):
+    def build(b):
+        b.conv(8, 8, 3, relu=0, src=-1)
+        b.relu()
+        b.pool()
+    st = single(build, 8, (10, 12), dtype)
+    compare_minibatch(st, layout=layout, verbose="conv-relu-pool layout %d" % layout)
+
+
+@pytest.mark.parametrize("dtype", DT)
+def test_pool_odd_size_and_vector_tail(dtype):
+    st = single(lambda b: (b.conv(6, 6, 1, relu=1, src=-1), b.pool()), 6, (9, 7), dtype)
+    compare_minibatch(st, verbose="pool odd")
+
+
+@pytest.mark.parametrize("dtype", DT)
+@pytest.mark.parametrize("c,hw", [(16, (6, 5)), (6, (7, 3)), (256, (4, 4))])
+def test_batchnorm_layer(dtype, c, hw):
+    def build(b):
+        b.conv(c, c, 1, bias=0, src=-1)
+        b.bn(c, relu=1)
+    st = single(build, c, hw, dtype, micro_batch=5)
+    compare_minibatch(st, verbose="bn c%d" % c)
+
+
+@pytest.mark.parametrize("dtype", DT)
+def test_residual_block(dtype):
+    st = C.resnet50_stage(cin=16, mid3=8, mid4=8, hw=8, n3=2, n4=1, micro_batch=3, n_micro=2, dtype=dtype)
+    compare_minibatch(st, verbose="residual blocks")
+
+
+@pytest.mark.parametrize("dtype", DT)
+def test_classifier(dtype):
+    st = C.vgg16_classifier(c=8, hw=3, hidden=40, classes=13, micro_batch=5, n_micro=3, dtype=dtype)
+    for layout in (B.NCHW, B.NHWC):
+        compare_minibatch(st, layout=layout, verbose="classifier layout %d" % layout)
+
+
+def test_config1_tiny_fp32_full_size():
+    compare_minibatch(C.tiny_stage(), perturb=False, verbose="cfg1 tiny")
+    compare_minibatch(C.tiny_stage(), perturb=True, layout=B.NCHW, verbose="cfg1 tiny perturbed NCHW")
+
+
+@pytest.mark.parametrize("name,stage", [
+    ("vgg16_stage1", C.vgg16_stage1(c1=16, c2=24, hw=20, micro_batch=3, n_micro=5)),
+    ("vgg16_deep", C.vgg16_deep(cin=16, c=24, hw=12, micro_batch=3, n_micro=3)),
+    ("resnet50_stage", C.resnet50_stage(cin=16, mid3=8, mid4=16, hw=12, n3=2, n4=2, micro_batch=4, n_micro=4)),
+])
+def test_shrunken_workloads_bf16(name, stage):
+    compare_minibatch(stage, verbose=name)
+
+
+def test_schedule_violations_and_stash_depth():
+    st = C.vgg16_deep(cin=8, c=8, hw=4, micro_batch=2, n_micro=4)        # stage 3 of 4: depth 2
+    g = GpuStage(st, gen.all_params(st))
+    per, depth = B.bapipe_stage_stash_bytes(g.h)
+    assert depth == 2 and per > 0
+    xs, gs = stage_io(st)
+    with pytest.raises(B.BapipeError) as e:
+        g.backward(0, gs[0])
+    assert e.value.status == B.E_ORDER
+    with pytest.raises(B.BapipeError) as e:
+        g.forward(1, xs[1])
+    assert e.value.status == B.E_ORDER
+    g.forward(0, xs[0])
+    g.forward(1, xs[1])
+    with pytest.raises(B.BapipeError) as e:
+        g.forward(2, xs[2])                       # third in flight exceeds N-i+1 = 2
+    assert e.value.status == B.E_ORDER
+    with pytest.raises(B.BapipeError) as e:
+        g.backward(1, gs[1])                      # FIFO
+    assert e.value.status == B.E_ORDER
+    with pytest.raises(B.BapipeError) as e:
+        B.bapipe_stage_step(g.h, 0.1)
+    assert e.value.status == B.E_ORDER
+    g.backward(0, gs[0])
+    g.forward(2, xs[2]); g.backward(1, gs[1]); g.forward(3, xs[3]); g.backward(2, gs[2]); g.backward(3, gs[3])
+    B.bapipe_stage_step(g.h, 0.1)
+    g.close()
+
+
+def test_allocator_failure_is_reported_and_leaks_nothing():
+    st = C.tiny_stage(c=4, hw=8, micro_batch=2, n_micro=2)
+    for k in range(0, 6):
+        alloc = B.TorchAllocator("cuda:0", fail_after=k)
+        opts = B.make_opts(st, allocator=alloc)
+        with pytest.raises(B.BapipeError) as e:
+            B.bapipe_stage_create(st["layers"], 2, 2, opts)
+        assert e.value.status == B.E_OOM
+        assert not alloc.live
