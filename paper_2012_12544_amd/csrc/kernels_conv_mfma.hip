@@ -1,9 +1,567 @@
-// placeholder until the MFMA kernels land
+// bf16 MFMA implicit-GEMM convolution for gfx950 (CDNA4): forward / dgrad ("gather" form) and
+// wgrad.  fp32 accumulation in v_mfma_f32_32x32x16_bf16; operands staged through LDS.
+//
+// Gather form (forward and dgrad share it, see GatherConv):
+//     out[pixel][ko] = sum_k  X[pixel][k] * Wt[ko][k],   k = (r, s, ki), ki fastest
+// is a GEMM whose K index is contiguous in memory for both operands (NHWC activations,
+// [Ko][R][S][Ki] filters), which is exactly the per-lane fragment the MFMA wants (8 consecutive
+// k for one row).  A block owns BP output pixels x BC output channels; 16-byte chunks of the
+// operand rows are gathered from HBM into registers one K-tile ahead of the MFMAs and written
+// to a double-buffered LDS tile whose 16-byte chunk index is XOR-swizzled with the row so that
+// both the chunk stores and the ds_read_b128 fragment loads are bank-conflict free.
+// The MFMA's A operand is the filter tile and its B operand the pixel tile, so a lane ends up
+// with 4 consecutive output channels of one pixel per accumulator quad; the tile is then
+// staged through LDS as [pixel][channel] to leave the kernel as 16-byte, fully coalesced rows
+// (with bias / ReLU, or with the gradient epilogue: accumulate + ReLU gate of the producer).
+//
+// wgrad:  dw[ko][r][s][c] += sum_pixels dy[pixel][ko] * x[pixel @ tap (r,s)][c]
+// contracts over pixels, which are NOT contiguous for either operand: tiles are stored in LDS
+// as [pixel][channel] exactly as they come from HBM, and the fragments are fetched with the
+// CDNA4 transposing LDS read (ds_read_b64_tr_b16), which hands each lane 4 consecutive
+// pixels of one channel.  The pixel range is split over blocks (split-K); partial sums go to
+// a workspace and a second kernel adds them in a fixed order into the fp32 accumulators.
+#include "dev_common.h"
 #include "kernels.h"
+
 namespace bapipe {
-bool conv_gather_mfma_supported(const GatherConv &) { return false; }
-hipError_t conv_gather_mfma(const void *, const void *, const float *, void *, int, GradEpi, const GatherConv &, hipStream_t) { return hipErrorNotSupported; }
-bool conv_wgrad_mfma_supported(const ConvShape &) { return false; }
-size_t conv_wgrad_mfma_workspace(const ConvShape &) { return 0; }
-hipError_t conv_wgrad_mfma(const void *, const void *, float *, void *, const ConvShape &, hipStream_t) { return hipErrorNotSupported; }
+namespace {
+
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef short s16x4_t __attribute__((ext_vector_type(4)));
+typedef float f32x16_t __attribute__((ext_vector_type(16)));
+
+typedef uint32_t chunk16 __attribute__((ext_vector_type(4)));   // 8 bf16, one 16-byte access
+typedef uint32_t chunk8 __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ bf16x8_t as_frag(chunk16 c) { return __builtin_bit_cast(bf16x8_t, c); }
+
+// XCD-aware block order: hardware deals consecutive block ids round-robin to the 8 XCDs
+// (each with its own L2).  Re-number so that every XCD walks one contiguous range of tiles
+// and the blocks that share an input tile run on the same L2.
+__device__ __forceinline__ int xcd_remap(int id, int nb)
+{
+    const int x = id & 7, q = nb >> 3, rem = nb & 7;
+    return x * q + (x < rem ? x : rem) + (id >> 3);
 }
+
+template <int BK> __device__ __forceinline__ int swz(int row)
+{
+    // 16-byte slots of 16 consecutive rows must fall into 16 different bank groups
+    return BK == 32 ? ((row >> 2) & 3) : ((row >> 1) & 7);
+}
+
+// ------------------------------------------------------------------------------------------
+// gather convolution
+// ------------------------------------------------------------------------------------------
+template <int BP, int BC, int WP, int WC, int BK, bool S1>
+__global__ __launch_bounds__(WP *WC * 64, 2) void k_gather_mfma(
+    const bf16_t *__restrict__ in, const bf16_t *__restrict__ wt, const float *__restrict__ bias,
+    bf16_t *out, const bf16_t *__restrict__ gate, int accum, int relu, int is_grad, GatherConv g,
+    int tiles_c)
+{
+    constexpr int NT = WP * WC * 64;
+    constexpr int CPR = BK / 8;              // 16-byte chunks per tile row
+    constexpr int RPP = NT / CPR;            // tile rows covered by one pass of all threads
+    constexpr int XP = BP / RPP;             // passes over the pixel tile
+    constexpr int WPASS = BC / RPP;          // passes over the filter tile
+    constexpr int WT_P = BP / WP, WT_C = BC / WC;
+    constexpr int TP = WT_P / 32, TC = WT_C / 32;
+    constexpr int KSUB = BK / 16;
+    constexpr int SROW = BC + 4;             // staging row (elements): 8-byte aligned, odd multiple of 8 bytes
+    static_assert(XP >= 1 && WPASS >= 1 && BP % RPP == 0 && BC % RPP == 0, "tile/thread mismatch");
+
+    extern __shared__ __align__(16) unsigned char smem[];
+    uint16_t *sW = reinterpret_cast<uint16_t *>(smem);                 // [2][BC*BK]
+    uint16_t *sX = sW + 2 * BC * BK;                                   // [2][BP*BK]
+    uint16_t *sO = reinterpret_cast<uint16_t *>(smem);                 // [WT_P][SROW] (epilogue)
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wp = wave % WP, wc = wave / WP;
+    const int lc = tid % CPR, lr = tid / CPR;
+
+    const int bid = xcd_remap(blockIdx.x, gridDim.x);
+    const int tile_c = bid % tiles_c, tile_p = bid / tiles_c;
+    const int co0 = tile_c * BC;
+    const long long pix0 = (long long)tile_p * BP;
+    const long long npix = (long long)g.N * g.Ho * g.Wo;
+    const int K = g.R * g.S * g.Ci;
+    const int KT = (K + BK - 1) / BK;
+
+    // ---- per-thread gather state: the pixel rows this thread loads
+    int hb[XP], wb[XP];
+    const bf16_t *xbase[XP];
+#pragma unroll
+    for (int i = 0; i < XP; ++i) {
+        long long p = pix0 + lr + i * RPP;
+        if (p < npix) {
+            int ow = (int)(p % g.Wo);
+            long long t = p / g.Wo;
+            int oh = (int)(t % g.Ho);
+            int n = (int)(t / g.Ho);
+            hb[i] = oh * g.s_out - g.pad_h;
+            wb[i] = ow * g.s_out - g.pad_w;
+            xbase[i] = in + (size_t)n * g.Hi * g.Wi * g.Ci;
+        } else {
+            hb[i] = -(1 << 28);          // fails every bounds check below
+            wb[i] = 0;
+            xbase[i] = in;
+        }
+    }
+    const bf16_t *wbase[WPASS];
+    bool wok[WPASS];
+#pragma unroll
+    for (int i = 0; i < WPASS; ++i) {
+        int co = co0 + lr + i * RPP;
+        wok[i] = co < g.Co;
+        wbase[i] = wt + (size_t)(wok[i] ? co : 0) * K;
+    }
+    // k position (r, s, ci) of this thread's chunk column, advanced by BK per K-tile
+    int kk = 8 * lc;
+    int kr = kk / (g.S * g.Ci), ks = (kk / g.Ci) % g.S, kc = kk % g.Ci;
+
+    chunk16 rx[XP], rw[WPASS];
+    const chunk16 zero16 = {0u, 0u, 0u, 0u};
+
+    auto load_tile = [&]() {
+        const bool kin = kr < g.R;
+#pragma unroll
+        for (int i = 0; i < XP; ++i) {
+            int hn = hb[i] + kr, wn = wb[i] + ks;
+            int ih, iw;
+            bool ok;
+            if (S1) {
+                ih = hn;
+                iw = wn;
+                ok = kin && (unsigned)ih < (unsigned)g.Hi && (unsigned)iw < (unsigned)g.Wi;
+            } else {
+                ih = hn / g.s_in;
+                iw = wn / g.s_in;
+                ok = kin && hn >= 0 && wn >= 0 && ih * g.s_in == hn && iw * g.s_in == wn && ih < g.Hi && iw < g.Wi;
+            }
+            rx[i] = ok ? *reinterpret_cast<const chunk16 *>(xbase[i] + ((size_t)ih * g.Wi + iw) * g.Ci + kc)
+                       : zero16;
+        }
+#pragma unroll
+        for (int i = 0; i < WPASS; ++i)
+            rw[i] = (wok[i] && kin) ? *reinterpret_cast<const chunk16 *>(wbase[i] + kk) : zero16;
+    };
+    auto advance_k = [&]() {
+        kk += BK;
+        kc += BK;
+        while (kc >= g.Ci) {
+            kc -= g.Ci;
+            if (++ks == g.S) {
+                ks = 0;
+                ++kr;
+            }
+        }
+    };
+    auto store_tile = [&](int buf) {
+        uint16_t *dx = sX + buf * BP * BK, *dw = sW + buf * BC * BK;
+#pragma unroll
+        for (int i = 0; i < XP; ++i) {
+            int row = lr + i * RPP;
+            *reinterpret_cast<chunk16 *>(dx + row * BK + ((lc ^ swz<BK>(row)) << 3)) = rx[i];
+        }
+#pragma unroll
+        for (int i = 0; i < WPASS; ++i) {
+            int row = lr + i * RPP;
+            *reinterpret_cast<chunk16 *>(dw + row * BK + ((lc ^ swz<BK>(row)) << 3)) = rw[i];
+        }
+    };
+
+    f32x16_t acc[TC][TP];
+#pragma unroll
+    for (int a = 0; a < TC; ++a)
+#pragma unroll
+        for (int b = 0; b < TP; ++b)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.0f;
+
+    load_tile();
+    advance_k();
+    store_tile(0);
+    __syncthreads();
+
+    const int frow = lane & 31, fhalf = lane >> 5;
+    for (int kt = 0; kt < KT; ++kt) {
+        const int buf = kt & 1;
+        const bool more = kt + 1 < KT;
+        if (more) {
+            load_tile();
+            advance_k();
+        }
+        const uint16_t *cx = sX + buf * BP * BK, *cw = sW + buf * BC * BK;
+#pragma unroll
+        for (int ks16 = 0; ks16 < KSUB; ++ks16) {
+            const int ch = 2 * ks16 + fhalf;
+            bf16x8_t fa[TC], fb[TP];
+#pragma unroll
+            for (int a = 0; a < TC; ++a) {
+                int row = wc * WT_C + a * 32 + frow;
+                fa[a] = as_frag(*reinterpret_cast<const chunk16 *>(cw + row * BK + ((ch ^ swz<BK>(row)) << 3)));
+            }
+#pragma unroll
+            for (int b = 0; b < TP; ++b) {
+                int row = wp * WT_P + b * 32 + frow;
+                fb[b] = as_frag(*reinterpret_cast<const chunk16 *>(cx + row * BK + ((ch ^ swz<BK>(row)) << 3)));
+            }
+#pragma unroll
+            for (int a = 0; a < TC; ++a)
+#pragma unroll
+                for (int b = 0; b < TP; ++b)
+                    acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[a], fb[b], acc[a][b], 0, 0, 0);
+        }
+        if (more) store_tile(buf ^ 1);
+        __syncthreads();
+    }
+
+    // ---- epilogue: one pixel band (the rows of the waves with the same wp) at a time
+    for (int band = 0; band < WP; ++band) {
+        if (wp == band) {
+#pragma unroll
+            for (int a = 0; a < TC; ++a) {
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int col = wc * WT_C + a * 32 + 8 * q + 4 * fhalf;      // channel inside the tile
+                    float bv[4] = {0.f, 0.f, 0.f, 0.f};
+                    if (bias) {
+#pragma unroll
+                        for (int j = 0; j < 4; ++j)
+                            if (co0 + col + j < g.Co) bv[j] = bias[co0 + col + j];
+                    }
+#pragma unroll
+                    for (int b = 0; b < TP; ++b) {
+                        const int prow = b * 32 + frow;                          // pixel inside the band
+                        uint16_t h[4];
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) {
+                            float v = acc[a][b][4 * q + j] + bv[j];
+                            if (relu) v = fmaxf(v, 0.0f);
+                            h[j] = f32_to_bf16_bits(v);
+                        }
+                        chunk8 c8;
+                        c8[0] = (uint32_t)h[0] | ((uint32_t)h[1] << 16);
+                        c8[1] = (uint32_t)h[2] | ((uint32_t)h[3] << 16);
+                        *reinterpret_cast<chunk8 *>(sO + prow * SROW + col) = c8;
+                    }
+                }
+            }
+        }
+        __syncthreads();
+        constexpr int CH8 = BC / 8;     // 16-byte units per pixel row
+        for (int u = tid; u < WT_P * CH8; u += NT) {
+            const int prow = u / CH8, c8i = u % CH8;
+            const long long p = pix0 + band * WT_P + prow;
+            const int co = co0 + c8i * 8;
+            if (p < npix && co < g.Co) {
+                chunk8 lo = *reinterpret_cast<const chunk8 *>(sO + prow * SROW + c8i * 8);
+                chunk8 hi = *reinterpret_cast<const chunk8 *>(sO + prow * SROW + c8i * 8 + 4);
+                chunk16 v = {lo[0], lo[1], hi[0], hi[1]};
+                bf16_t *dst = out + (size_t)p * g.Co + co;
+                if (is_grad) {
+                    chunk16 old = zero16, gt = zero16, r;
+                    if (accum) old = *reinterpret_cast<const chunk16 *>(dst);
+                    if (gate) gt = *reinterpret_cast<const chunk16 *>(gate + (size_t)p * g.Co + co);
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        uint32_t packed = 0;
+#pragma unroll
+                        for (int hsel = 0; hsel < 2; ++hsel) {
+                            bf16_t a, o, gg;
+                            a.v = (uint16_t)(v[j] >> (16 * hsel));
+                            o.v = (uint16_t)(old[j] >> (16 * hsel));
+                            gg.v = (uint16_t)(gt[j] >> (16 * hsel));
+                            bf16_t res = grad_out<bf16_t>(to_f32(a), accum != 0, o, gate != nullptr, gg);
+                            packed |= (uint32_t)res.v << (16 * hsel);
+                        }
+                        r[j] = packed;
+                    }
+                    *reinterpret_cast<chunk16 *>(dst) = r;
+                } else {
+                    *reinterpret_cast<chunk16 *>(dst) = v;
+                }
+            }
+        }
+        __syncthreads();
+    }
+}
+
+template <int BP, int BC, int WP, int WC, int BK>
+hipError_t launch_gather(const void *in, const void *wt, const float *bias, void *out, int relu, GradEpi epi,
+                         const GatherConv &g, hipStream_t s)
+{
+    constexpr int NT = WP * WC * 64;
+    constexpr size_t main_bytes = (size_t)2 * (BP + BC) * BK * 2;
+    constexpr size_t epi_bytes = (size_t)(BP / WP) * (BC + 4) * 2;
+    constexpr size_t smem = main_bytes > epi_bytes ? main_bytes : epi_bytes;
+    static_assert(smem <= 64 * 1024, "dynamic LDS above the default limit");
+    const long long npix = (long long)g.N * g.Ho * g.Wo;
+    const int tiles_p = (int)((npix + BP - 1) / BP), tiles_c = (g.Co + BC - 1) / BC;
+    const int is_grad = (epi.gate != nullptr || epi.accum) ? 1 : 0;
+    dim3 grid((unsigned)(tiles_p * tiles_c));
+    if (g.s_in == 1)
+        hipLaunchKernelGGL((k_gather_mfma<BP, BC, WP, WC, BK, true>), grid, dim3(NT), smem, s, (const bf16_t *)in,
+                           (const bf16_t *)wt, bias, (bf16_t *)out, (const bf16_t *)epi.gate, epi.accum, relu,
+                           is_grad, g, tiles_c);
+    else
+        hipLaunchKernelGGL((k_gather_mfma<BP, BC, WP, WC, BK, false>), grid, dim3(NT), smem, s, (const bf16_t *)in,
+                           (const bf16_t *)wt, bias, (bf16_t *)out, (const bf16_t *)epi.gate, epi.accum, relu,
+                           is_grad, g, tiles_c);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------
+// wgrad
+// ------------------------------------------------------------------------------------------
+// LDS tile [BKP pixels][CH channels], row stride CH + 32 elements (CH*2 + 64 bytes): the four
+// rows touched by one 16-lane group of a transposing read then fall into disjoint banks.
+template <int CH> struct WgLds {
+    static constexpr int STRIDE = CH + 32;
+};
+
+// fragment for v_mfma_f32_32x32x16_bf16 out of a [pixel][channel] LDS tile:
+// lane -> channel ch0 + (lane & 31), pixels k0 + 8*(lane >> 5) .. +7  (two transposing reads)
+template <int STRIDE>
+__device__ __forceinline__ bf16x8_t tr_frag(const uint16_t *tile, int ch0, int k0, int lane)
+{
+    const int blk = lane >> 4, sl = lane & 15;
+    const int row = k0 + 8 * (blk >> 1) + (sl >> 2);
+    const int col = ch0 + 16 * (blk & 1) + 4 * (sl & 3);
+    const uint16_t *p = tile + row * STRIDE + col;
+    typedef __attribute__((address_space(3))) s16x4_t lds_v4;
+    s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4 *)(p));
+    s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4 *)(p + 4 * STRIDE));
+    typedef short s16x8_t __attribute__((ext_vector_type(8)));
+    s16x8_t both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    return __builtin_bit_cast(bf16x8_t, both);
+}
+
+// grid: x = (ko tile, tap, c tile) ; y = split over pixel chunks
+template <int BKO, int BCI, int WKO, int WCI, int BKP>
+__global__ __launch_bounds__(WKO *WCI * 64, 2) void k_wgrad_mfma(const bf16_t *__restrict__ x,
+                                                                  const bf16_t *__restrict__ dy,
+                                                                  float *__restrict__ part, ConvShape c,
+                                                                  int tiles_ko, int tiles_ci, int pix_per_split)
+{
+    constexpr int NT = WKO * WCI * 64;
+    constexpr int SA = WgLds<BKO>::STRIDE, SB = WgLds<BCI>::STRIDE;
+    constexpr int ACH = BKO / 8, BCH = BCI / 8;       // 16-byte chunks per pixel row
+    constexpr int APASS = (BKP * ACH + NT - 1) / NT, BPASS = (BKP * BCH + NT - 1) / NT;
+    constexpr int WT_KO = BKO / WKO, WT_CI = BCI / WCI;
+    constexpr int TA = WT_KO / 32, TB = WT_CI / 32;
+    static_assert((BKP * ACH) % NT == 0 && (BKP * BCH) % NT == 0, "tile/thread mismatch");
+
+    __shared__ __align__(16) uint16_t sA[2][BKP * SA];
+    __shared__ __align__(16) uint16_t sB[2][BKP * SB];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wk = wave % WKO, wi = wave / WKO;
+    int bid = blockIdx.x;
+    const int tci = bid % tiles_ci;
+    bid /= tiles_ci;
+    const int tap = bid % (c.R * c.S);
+    const int tko = bid / (c.R * c.S);
+    const int r = tap / c.S, s = tap % c.S;
+    const int ko0 = tko * BKO, ci0 = tci * BCI;
+    const long long npix = (long long)c.N * c.P * c.Q;
+    const long long p_begin = (long long)blockIdx.y * pix_per_split;
+    long long p_end = p_begin + pix_per_split;
+    if (p_end > npix) p_end = npix;
+    const int KT = (int)((p_end - p_begin + BKP - 1) / BKP);
+
+    chunk16 ra[APASS], rb[BPASS];
+    const chunk16 zero16 = {0u, 0u, 0u, 0u};
+
+    auto load_tile = [&](int kt) {
+        const long long pt = p_begin + (long long)kt * BKP;
+#pragma unroll
+        for (int i = 0; i < APASS; ++i) {
+            int u = tid + i * NT;
+            int row = u / ACH, ch = u % ACH;
+            long long p = pt + row;
+            int ko = ko0 + ch * 8;
+            ra[i] = (p < p_end && ko < c.K) ? *reinterpret_cast<const chunk16 *>(dy + (size_t)p * c.K + ko) : zero16;
+        }
+#pragma unroll
+        for (int i = 0; i < BPASS; ++i) {
+            int u = tid + i * NT;
+            int row = u / BCH, ch = u % BCH;
+            long long p = pt + row;
+            int ci = ci0 + ch * 8;
+            bool ok = p < p_end && ci < c.C;
+            size_t off = 0;
+            if (ok) {
+                int q = (int)(p % c.Q);
+                long long t = p / c.Q;
+                int pp = (int)(t % c.P);
+                int n = (int)(t / c.P);
+                int ih = pp * c.stride + r - c.pad, iw = q * c.stride + s - c.pad;
+                ok = (unsigned)ih < (unsigned)c.H && (unsigned)iw < (unsigned)c.W;
+                off = (((size_t)n * c.H + ih) * c.W + iw) * c.C + ci;
+            }
+            rb[i] = ok ? *reinterpret_cast<const chunk16 *>(x + off) : zero16;
+        }
+    };
+    auto store_tile = [&](int buf) {
+#pragma unroll
+        for (int i = 0; i < APASS; ++i) {
+            int u = tid + i * NT;
+            *reinterpret_cast<chunk16 *>(&sA[buf][(u / ACH) * SA + (u % ACH) * 8]) = ra[i];
+        }
+#pragma unroll
+        for (int i = 0; i < BPASS; ++i) {
+            int u = tid + i * NT;
+            *reinterpret_cast<chunk16 *>(&sB[buf][(u / BCH) * SB + (u % BCH) * 8]) = rb[i];
+        }
+    };
+
+    f32x16_t acc[TA][TB];
+#pragma unroll
+    for (int a = 0; a < TA; ++a)
+#pragma unroll
+        for (int b = 0; b < TB; ++b)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.0f;
+
+    if (KT > 0) {
+        load_tile(0);
+        store_tile(0);
+    }
+    __syncthreads();
+    for (int kt = 0; kt < KT; ++kt) {
+        const int buf = kt & 1;
+        const bool more = kt + 1 < KT;
+        if (more) load_tile(kt + 1);
+#pragma unroll
+        for (int k0 = 0; k0 < BKP; k0 += 16) {
+            bf16x8_t fa[TA], fb[TB];
+#pragma unroll
+            for (int a = 0; a < TA; ++a) fa[a] = tr_frag<SA>(sA[buf], wk * WT_KO + a * 32, k0, lane);
+#pragma unroll
+            for (int b = 0; b < TB; ++b) fb[b] = tr_frag<SB>(sB[buf], wi * WT_CI + b * 32, k0, lane);
+#pragma unroll
+            for (int a = 0; a < TA; ++a)
+#pragma unroll
+                for (int b = 0; b < TB; ++b)
+                    acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[a], fb[b], acc[a][b], 0, 0, 0);
+        }
+        if (more) store_tile(buf ^ 1);
+        __syncthreads();
+    }
+
+    // partial[split][ko][r][s][ci]: lanes of a wave write 32 consecutive ci (128 bytes)
+    const size_t total = (size_t)c.K * c.R * c.S * c.C;
+    float *dst = part + (size_t)blockIdx.y * total;
+    const int col = lane & 31, half = lane >> 5;
+#pragma unroll
+    for (int a = 0; a < TA; ++a)
+#pragma unroll
+        for (int b = 0; b < TB; ++b) {
+            const int ci = ci0 + wi * WT_CI + b * 32 + col;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int ko = ko0 + wk * WT_KO + a * 32 + 8 * (v >> 2) + 4 * half + (v & 3);
+                if (ko < c.K && ci < c.C) dst[(((size_t)ko * c.R + r) * c.S + s) * c.C + ci] = acc[a][b][v];
+            }
+        }
+}
+
+__global__ void k_splitk_reduce(const float *__restrict__ part, float *dw, size_t total, int splits)
+{
+    size_t i = ((size_t)blockIdx.x * 256 + threadIdx.x) * 4;
+    if (i >= total) return;
+    if (i + 4 <= total) {
+        float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+        for (int k = 0; k < splits; ++k) {
+            float4 v = *reinterpret_cast<const float4 *>(part + (size_t)k * total + i);
+            acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
+        }
+        float4 d = *reinterpret_cast<float4 *>(dw + i);
+        d.x += acc.x; d.y += acc.y; d.z += acc.z; d.w += acc.w;
+        *reinterpret_cast<float4 *>(dw + i) = d;
+    } else {
+        for (size_t j = i; j < total; ++j) {
+            float acc = 0.f;
+            for (int k = 0; k < splits; ++k) acc += part[(size_t)k * total + j];
+            dw[j] += acc;
+        }
+    }
+}
+
+struct WgradPlan {
+    int bko, bci, tiles_ko, tiles_ci, splits, pix_per_split;
+};
+
+WgradPlan wgrad_plan(const ConvShape &c)
+{
+    WgradPlan p;
+    p.bko = 128;
+    p.bci = c.C >= 128 ? 128 : 64;
+    p.tiles_ko = (c.K + p.bko - 1) / p.bko;
+    p.tiles_ci = (c.C + p.bci - 1) / p.bci;
+    long long npix = (long long)c.N * c.P * c.Q;
+    long long tiles = (long long)p.tiles_ko * p.tiles_ci * c.R * c.S;
+    long long want = (1024 + tiles - 1) / tiles;          // ~4 blocks per CU
+    long long max_by_work = (npix + 511) / 512;             // at least 512 pixels per split
+    if (want > max_by_work) want = max_by_work;
+    if (want < 1) want = 1;
+    if (want > 256) want = 256;
+    long long pps = (npix + want - 1) / want;
+    pps = (pps + 31) / 32 * 32;
+    if (pps < 32) pps = 32;
+    p.pix_per_split = (int)pps;
+    p.splits = (int)((npix + pps - 1) / pps);
+    if (p.splits < 1) p.splits = 1;
+    return p;
+}
+
+}  // namespace
+
+bool conv_gather_mfma_supported(const GatherConv &g)
+{
+    return g.Ci % 8 == 0 && g.Co % 8 == 0 && g.Ci >= 8 && g.s_in >= 1 && g.s_out >= 1 &&
+           (long long)g.N * g.Hi * g.Wi * g.Ci < (1ll << 40);
+}
+
+hipError_t conv_gather_mfma(const void *in, const void *wt, const float *bias, void *out, int relu,
+                            GradEpi epi, const GatherConv &g, hipStream_t s)
+{
+    if (!conv_gather_mfma_supported(g)) return hipErrorInvalidValue;
+    if ((long long)g.N * g.Ho * g.Wo == 0) return hipSuccess;
+    if (g.Co <= 64) return launch_gather<256, 64, 4, 1, 32>(in, wt, bias, out, relu, epi, g, s);
+    return launch_gather<256, 128, 2, 2, 32>(in, wt, bias, out, relu, epi, g, s);
+}
+
+bool conv_wgrad_mfma_supported(const ConvShape &c)
+{
+    return c.C % 8 == 0 && c.K % 8 == 0 && c.C >= 8 && c.K >= 8;
+}
+
+size_t conv_wgrad_mfma_workspace(const ConvShape &c)
+{
+    WgradPlan p = wgrad_plan(c);
+    return (size_t)p.splits * c.K * c.R * c.S * c.C * sizeof(float);
+}
+
+hipError_t conv_wgrad_mfma(const void *x, const void *dy, float *dw, void *workspace, const ConvShape &c,
+                           hipStream_t s)
+{
+    if (!conv_wgrad_mfma_supported(c)) return hipErrorInvalidValue;
+    if ((long long)c.N * c.P * c.Q == 0) return hipSuccess;
+    WgradPlan p = wgrad_plan(c);
+    dim3 grid((unsigned)(p.tiles_ko * c.R * c.S * p.tiles_ci), (unsigned)p.splits);
+    float *part = (float *)workspace;
+    if (p.bci == 128)
+        hipLaunchKernelGGL((k_wgrad_mfma<128, 128, 2, 2, 32>), grid, dim3(256), 0, s, (const bf16_t *)x,
+                           (const bf16_t *)dy, part, c, p.tiles_ko, p.tiles_ci, p.pix_per_split);
+    else
+        hipLaunchKernelGGL((k_wgrad_mfma<128, 64, 2, 2, 32>), grid, dim3(256), 0, s, (const bf16_t *)x,
+                           (const bf16_t *)dy, part, c, p.tiles_ko, p.tiles_ci, p.pix_per_split);
+    size_t total = (size_t)c.K * c.R * c.S * c.C;
+    hipLaunchKernelGGL(k_splitk_reduce, dim3((unsigned)((total / 4 + 255) / 256 + 1)), dim3(256), 0, s, part, dw,
+                       total, p.splits);
+    return hipGetLastError();
+}
+
+}  // namespace bapipe

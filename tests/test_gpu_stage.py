@@ -32,6 +32,19 @@ def test_conv_layer(dtype, k, stride, cin, cout, hw, relu):
     compare_minibatch(st, verbose="conv k%d s%d %d->%d" % (k, stride, cin, cout))
 
 
+@pytest.mark.parametrize("k,stride,cin,cout,hw,mb", [
+    (3, 1, 64, 64, (20, 23), 3),      # several pixel tiles, ragged last tile, K = 576
+    (3, 1, 24, 136, (18, 18), 2),     # ragged K tile (216) and ragged channel tile (136 = 128 + 8)
+    (3, 2, 32, 72, (21, 19), 3),      # stride-2 forward, strided dgrad
+    (1, 1, 128, 256, (9, 7), 5),      # 1x1
+    (1, 2, 72, 40, (15, 15), 2),      # 1x1 stride 2
+    (3, 1, 8, 8, (5, 4), 1),          # smaller than one tile in every dimension
+])
+def test_conv_mfma_tiling(k, stride, cin, cout, hw, mb):
+    st = single(lambda b: b.conv(cin, cout, k, stride=stride, relu=1, src=-1), cin, hw, C.BF16, micro_batch=mb)
+    compare_minibatch(st, verbose="mfma conv k%d s%d %d->%d %s" % (k, stride, cin, cout, hw))
+
+
 @pytest.mark.parametrize("dtype", DT)
 @pytest.mark.parametrize("layout", [B.NCHW, B.NHWC])
 def test_relu_pool_layers_and_layouts(dtype, layout):
