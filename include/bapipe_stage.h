@@ -170,6 +170,26 @@ int bapipe_stage_get_loss(bapipe_stage_t *st, int mb_id, float *loss_host);
  * min(M, N-i+1) resp. min(M, 2(N-i+1)) (Table I / II). */
 int bapipe_stage_stash_bytes(const bapipe_stage_t *st, uint64_t *per_mb, int *depth);
 
+/* Measurement tap (Sec. III-A profiles layers; this profiles one kernel class inside the real
+ * schedule).  While enabled, every launch of the chosen class made by forward / backward is
+ * bracketed by two HIP events on the stage's stream.  _read synchronises the stream and
+ * returns the summed event time, the number of launches, and the algorithmic work of those
+ * launches: FLOP (2 per multiply-accumulate) for the convolution classes, HBM bytes each
+ * element must move once for the others.  Reading resets the counters; at most 4096 launches
+ * are recorded between reads.  kernel_class < 0 disables the tap. */
+enum {
+    BAPIPE_KC_CONV_GATHER_MFMA = 0, /* bf16 MFMA forward / dgrad implicit GEMM           */
+    BAPIPE_KC_CONV_WGRAD_MFMA = 1,  /* bf16 MFMA wgrad incl. its split-K reduction       */
+    BAPIPE_KC_CONV_DIRECT = 2,      /* vector-ALU convolution (fp32 stages, odd channels) */
+    BAPIPE_KC_POOL = 3,
+    BAPIPE_KC_BATCHNORM = 4,
+    BAPIPE_KC_ELEMENTWISE = 5,      /* ReLU, add, gradient copies, bias-gradient sums     */
+    BAPIPE_KC_COUNT = 6
+};
+int bapipe_stage_kernel_timing(bapipe_stage_t *st, int kernel_class);
+int bapipe_stage_kernel_timing_read(bapipe_stage_t *st, double *total_ms, uint64_t *launches,
+                                    double *flop, double *bytes);
+
 /* Message of the last failed call on this handle (or of the last failed create when st is
  * NULL); valid until the next call on the same handle. */
 const char *bapipe_last_error(const bapipe_stage_t *st);

@@ -23,7 +23,9 @@ EXPORTS = [
     "bapipe_profile_layers", "bapipe_stage_set_params", "bapipe_stage_get_params",
     "bapipe_stage_get_grads", "bapipe_stage_get_pool_indices", "bapipe_stage_get_loss",
     "bapipe_stage_stash_bytes", "bapipe_last_error", "bapipe_stage_destroy",
+    "bapipe_stage_kernel_timing", "bapipe_stage_kernel_timing_read",
 ]
+KC_CONV_GATHER_MFMA, KC_CONV_WGRAD_MFMA, KC_CONV_DIRECT, KC_POOL, KC_BATCHNORM, KC_ELEMENTWISE = range(6)
 
 
 class LayerDesc(ct.Structure):
@@ -84,6 +86,9 @@ def load():
     lib.bapipe_stage_get_pool_indices.argtypes = [vp, i32, i32, ct.POINTER(ct.c_uint8)]
     lib.bapipe_stage_get_loss.argtypes = [vp, i32, fp]
     lib.bapipe_stage_stash_bytes.argtypes = [vp, ct.POINTER(ct.c_uint64), ct.POINTER(i32)]
+    lib.bapipe_stage_kernel_timing.argtypes = [vp, i32]
+    lib.bapipe_stage_kernel_timing_read.argtypes = [vp, ct.POINTER(ct.c_double), ct.POINTER(ct.c_uint64),
+                                                    ct.POINTER(ct.c_double), ct.POINTER(ct.c_double)]
     lib.bapipe_last_error.argtypes = [vp]
     lib.bapipe_last_error.restype = ct.c_char_p
     lib.bapipe_stage_destroy.argtypes = [vp]
@@ -212,6 +217,16 @@ def bapipe_stage_stash_bytes(h):
     depth = ct.c_int(0)
     _check(load().bapipe_stage_stash_bytes(h, ct.byref(per), ct.byref(depth)), h)
     return per.value, depth.value
+
+
+def bapipe_stage_kernel_timing(h, kernel_class):
+    _check(load().bapipe_stage_kernel_timing(h, kernel_class), h)
+
+
+def bapipe_stage_kernel_timing_read(h):
+    ms, n, fl, by = ct.c_double(0), ct.c_uint64(0), ct.c_double(0), ct.c_double(0)
+    _check(load().bapipe_stage_kernel_timing_read(h, ct.byref(ms), ct.byref(n), ct.byref(fl), ct.byref(by)), h)
+    return dict(total_ms=ms.value, launches=n.value, flop=fl.value, bytes=by.value)
 
 
 def bapipe_stage_destroy(h):

@@ -87,10 +87,14 @@ hipError_t recast(int dt, const float *w, void *work, size_t n, hipStream_t s);
 hipError_t make_dgrad_filter(int dt, const float *w, void *wt, int K, int R, int S, int C, hipStream_t s);
 hipError_t fill_f32(float *p, float v, size_t n, hipStream_t s);
 
-// ---- boundary layout conversion NCHW <-> NHWC (same storage type); optional ReLU gate
+// ---- boundary layout conversion NCHW <-> NHWC (same storage type); optional ReLU gate.
+// The NHWC side has Cp >= C physical channels (zero padded); nhwc_repad changes the channel
+// count of an NHWC tensor (zero fill or truncation).
 hipError_t nchw_to_nhwc(int dt, const void *src, void *dst, GradEpi epi, int N, int C, int H, int W,
+                        int Cp, hipStream_t s);
+hipError_t nhwc_to_nchw(int dt, const void *src, void *dst, int N, int C, int H, int W, int Cp,
                         hipStream_t s);
-hipError_t nhwc_to_nchw(int dt, const void *src, void *dst, int N, int C, int H, int W, hipStream_t s);
+hipError_t nhwc_repad(int dt, const void *src, void *dst, size_t rows, int Cs, int Cd, hipStream_t s);
 hipError_t nhwc_to_nchw_u8(const uint8_t *src, uint8_t *dst, int N, int C, int H, int W, hipStream_t s);
 
 }  // namespace bapipe

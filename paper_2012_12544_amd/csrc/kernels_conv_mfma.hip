@@ -337,12 +337,14 @@ __device__ __forceinline__ bf16x8_t tr_frag(const uint16_t *tile, int ch0, int k
     return __builtin_bit_cast(bf16x8_t, both);
 }
 
-// grid: x = (ko tile, tap, c tile) ; y = split over pixel chunks
+// The GEMM's N index is the flattened (r, s, c) filter position n = (r*S + s)*C + c, so a tile
+// of BCI columns covers one tap (or part of it) when C >= BCI and several taps when C is small.
+// grid: x = (ko tile, n tile) ; y = split over pixel chunks
 template <int BKO, int BCI, int WKO, int WCI, int BKP>
 __global__ __launch_bounds__(WKO *WCI * 64, 2) void k_wgrad_mfma(const bf16_t *__restrict__ x,
                                                                   const bf16_t *__restrict__ dy,
                                                                   float *__restrict__ part, ConvShape c,
-                                                                  int tiles_ko, int tiles_ci, int pix_per_split)
+                                                                  int tiles_n, int pix_per_split)
 {
     constexpr int NT = WKO * WCI * 64;
     constexpr int SA = WgLds<BKO>::STRIDE, SB = WgLds<BCI>::STRIDE;
@@ -357,13 +359,9 @@ __global__ __launch_bounds__(WKO *WCI * 64, 2) void k_wgrad_mfma(const bf16_t *_
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wk = wave % WKO, wi = wave / WKO;
-    int bid = blockIdx.x;
-    const int tci = bid % tiles_ci;
-    bid /= tiles_ci;
-    const int tap = bid % (c.R * c.S);
-    const int tko = bid / (c.R * c.S);
-    const int r = tap / c.S, s = tap % c.S;
-    const int ko0 = tko * BKO, ci0 = tci * BCI;
+    const int tn = blockIdx.x % tiles_n, tko = blockIdx.x / tiles_n;
+    const int ko0 = tko * BKO, n0 = tn * BCI;
+    const int Ntot = c.R * c.S * c.C;
     const long long npix = (long long)c.N * c.P * c.Q;
     const long long p_begin = (long long)blockIdx.y * pix_per_split;
     long long p_end = p_begin + pix_per_split;
@@ -372,6 +370,22 @@ __global__ __launch_bounds__(WKO *WCI * 64, 2) void k_wgrad_mfma(const bf16_t *_
 
     chunk16 ra[APASS], rb[BPASS];
     const chunk16 zero16 = {0u, 0u, 0u, 0u};
+
+    // filter position of the B-tile chunk column(s) this thread loads (fixed over the K loop)
+    int br[BPASS], bs[BPASS], bc[BPASS];
+#pragma unroll
+    for (int i = 0; i < BPASS; ++i) {
+        int n = n0 + ((tid + i * NT) % BCH) * 8;
+        if (n < Ntot) {
+            int tap = n / c.C;
+            bc[i] = n % c.C;
+            br[i] = tap / c.S - c.pad;
+            bs[i] = tap % c.S - c.pad;
+        } else {
+            bc[i] = -1;
+            br[i] = bs[i] = 0;
+        }
+    }
 
     auto load_tile = [&](int kt) {
         const long long pt = p_begin + (long long)kt * BKP;
@@ -386,19 +400,18 @@ __global__ __launch_bounds__(WKO *WCI * 64, 2) void k_wgrad_mfma(const bf16_t *_
 #pragma unroll
         for (int i = 0; i < BPASS; ++i) {
             int u = tid + i * NT;
-            int row = u / BCH, ch = u % BCH;
+            int row = u / BCH;
             long long p = pt + row;
-            int ci = ci0 + ch * 8;
-            bool ok = p < p_end && ci < c.C;
+            bool ok = p < p_end && bc[i] >= 0;
             size_t off = 0;
             if (ok) {
                 int q = (int)(p % c.Q);
                 long long t = p / c.Q;
                 int pp = (int)(t % c.P);
                 int n = (int)(t / c.P);
-                int ih = pp * c.stride + r - c.pad, iw = q * c.stride + s - c.pad;
+                int ih = pp * c.stride + br[i], iw = q * c.stride + bs[i];
                 ok = (unsigned)ih < (unsigned)c.H && (unsigned)iw < (unsigned)c.W;
-                off = (((size_t)n * c.H + ih) * c.W + iw) * c.C + ci;
+                off = (((size_t)n * c.H + ih) * c.W + iw) * c.C + bc[i];
             }
             rb[i] = ok ? *reinterpret_cast<const chunk16 *>(x + off) : zero16;
         }
@@ -450,19 +463,19 @@ __global__ __launch_bounds__(WKO *WCI * 64, 2) void k_wgrad_mfma(const bf16_t *_
         __syncthreads();
     }
 
-    // partial[split][ko][r][s][ci]: lanes of a wave write 32 consecutive ci (128 bytes)
-    const size_t total = (size_t)c.K * c.R * c.S * c.C;
+    // partial[split][ko][n]: lanes of a wave write 32 consecutive n (128 bytes)
+    const size_t total = (size_t)c.K * Ntot;
     float *dst = part + (size_t)blockIdx.y * total;
     const int col = lane & 31, half = lane >> 5;
 #pragma unroll
     for (int a = 0; a < TA; ++a)
 #pragma unroll
         for (int b = 0; b < TB; ++b) {
-            const int ci = ci0 + wi * WT_CI + b * 32 + col;
+            const int n = n0 + wi * WT_CI + b * 32 + col;
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
                 const int ko = ko0 + wk * WT_KO + a * 32 + 8 * (v >> 2) + 4 * half + (v & 3);
-                if (ko < c.K && ci < c.C) dst[(((size_t)ko * c.R + r) * c.S + s) * c.C + ci] = acc[a][b][v];
+                if (ko < c.K && n < Ntot) dst[(size_t)ko * Ntot + n] = acc[a][b][v];
             }
         }
 }
@@ -490,18 +503,19 @@ __global__ void k_splitk_reduce(const float *__restrict__ part, float *dw, size_
 }
 
 struct WgradPlan {
-    int bko, bci, tiles_ko, tiles_ci, splits, pix_per_split;
+    int bko, bci, tiles_ko, tiles_n, splits, pix_per_split;
 };
 
 WgradPlan wgrad_plan(const ConvShape &c)
 {
     WgradPlan p;
-    p.bko = 128;
-    p.bci = c.C >= 128 ? 128 : 64;
+    const int Ntot = c.R * c.S * c.C;
+    p.bko = c.K > 64 ? 128 : 64;
+    p.bci = Ntot > 64 ? 128 : 64;
     p.tiles_ko = (c.K + p.bko - 1) / p.bko;
-    p.tiles_ci = (c.C + p.bci - 1) / p.bci;
+    p.tiles_n = (Ntot + p.bci - 1) / p.bci;
     long long npix = (long long)c.N * c.P * c.Q;
-    long long tiles = (long long)p.tiles_ko * p.tiles_ci * c.R * c.S;
+    long long tiles = (long long)p.tiles_ko * p.tiles_n;
     long long want = (1024 + tiles - 1) / tiles;          // ~4 blocks per CU
     long long max_by_work = (npix + 511) / 512;             // at least 512 pixels per split
     if (want > max_by_work) want = max_by_work;
@@ -550,14 +564,20 @@ hipError_t conv_wgrad_mfma(const void *x, const void *dy, float *dw, void *works
     if (!conv_wgrad_mfma_supported(c)) return hipErrorInvalidValue;
     if ((long long)c.N * c.P * c.Q == 0) return hipSuccess;
     WgradPlan p = wgrad_plan(c);
-    dim3 grid((unsigned)(p.tiles_ko * c.R * c.S * p.tiles_ci), (unsigned)p.splits);
+    dim3 grid((unsigned)(p.tiles_ko * p.tiles_n), (unsigned)p.splits);
     float *part = (float *)workspace;
-    if (p.bci == 128)
-        hipLaunchKernelGGL((k_wgrad_mfma<128, 128, 2, 2, 32>), grid, dim3(256), 0, s, (const bf16_t *)x,
-                           (const bf16_t *)dy, part, c, p.tiles_ko, p.tiles_ci, p.pix_per_split);
+#define WG_LAUNCH(BKO_, BCI_, WKO_, WCI_)                                                                  \
+    hipLaunchKernelGGL((k_wgrad_mfma<BKO_, BCI_, WKO_, WCI_, 32>), grid, dim3(WKO_ * WCI_ * 64), 0, s,      \
+                       (const bf16_t *)x, (const bf16_t *)dy, part, c, p.tiles_n, p.pix_per_split)
+    if (p.bko == 128 && p.bci == 128)
+        WG_LAUNCH(128, 128, 2, 2);
+    else if (p.bko == 64 && p.bci == 128)
+        WG_LAUNCH(64, 128, 1, 4);
+    else if (p.bko == 128 && p.bci == 64)
+        WG_LAUNCH(128, 64, 4, 1);
     else
-        hipLaunchKernelGGL((k_wgrad_mfma<128, 64, 2, 2, 32>), grid, dim3(256), 0, s, (const bf16_t *)x,
-                           (const bf16_t *)dy, part, c, p.tiles_ko, p.tiles_ci, p.pix_per_split);
+        WG_LAUNCH(64, 64, 2, 2);
+#undef WG_LAUNCH
     size_t total = (size_t)c.K * c.R * c.S * c.C;
     hipLaunchKernelGGL(k_splitk_reduce, dim3((unsigned)((total / 4 + 255) / 256 + 1)), dim3(256), 0, s, part, dw,
                        total, p.splits);

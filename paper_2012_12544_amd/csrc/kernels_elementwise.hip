@@ -166,7 +166,7 @@ inline ColPlan col_plan(int rows, int C, int V)
     p.RY = TPB / p.CGB;
     p.gx = (p.CV + p.CGB - 1) / p.CGB;
     int want = (rows + p.RY * 8 - 1) / (p.RY * 8);
-    int cap = 2048 / p.gx;
+    int cap = 1024 / p.gx;
     if (cap < 1) cap = 1;
     p.chunks = want < 1 ? 1 : (want > cap ? cap : want);
     p.rows_per_chunk = (rows + p.chunks - 1) / p.chunks;
@@ -237,13 +237,44 @@ __global__ void k_colsum_partial(const T *__restrict__ a, int rows, int C, ColPl
     col_partial_body<T, V, 1>(f, rows, p, part, C);
 }
 
+// Final pass over the per-chunk partials: a block owns 16 channels, 16 lanes per channel walk
+// the chunks with stride 16, and the lanes are combined through LDS in lane order, so the
+// result does not depend on scheduling.  Returns true in the lane that holds the totals.
+constexpr int FIN_CH = 16, FIN_LANES = TPB / FIN_CH;
+template <int NQ>
+__device__ __forceinline__ bool col_final_sums(const float *__restrict__ part, int chunks, int C, int &c,
+                                               double (&tot)[NQ])
+{
+    __shared__ double red[NQ][FIN_LANES][FIN_CH];
+    const int cc = threadIdx.x % FIN_CH, cl = threadIdx.x / FIN_CH;
+    c = blockIdx.x * FIN_CH + cc;
+    double s[NQ];
+#pragma unroll
+    for (int q = 0; q < NQ; ++q) s[q] = 0.0;
+    if (c < C)
+        for (int k = cl; k < chunks; k += FIN_LANES)
+#pragma unroll
+            for (int q = 0; q < NQ; ++q) s[q] += (double)part[((size_t)q * chunks + k) * C + c];
+#pragma unroll
+    for (int q = 0; q < NQ; ++q) red[q][cl][cc] = s[q];
+    __syncthreads();
+    if (cl != 0 || c >= C) return false;
+#pragma unroll
+    for (int q = 0; q < NQ; ++q) {
+        double t = 0.0;
+        for (int k = 0; k < FIN_LANES; ++k) t += red[q][k][cc];
+        tot[q] = t;
+    }
+    return true;
+}
+
+inline unsigned final_blocks(int C) { return (unsigned)((C + FIN_CH - 1) / FIN_CH); }
+
 __global__ void k_colsum_final(const float *__restrict__ part, int chunks, int C, float *out)
 {
-    int c = blockIdx.x * TPB + threadIdx.x;
-    if (c >= C) return;
-    double s = 0.0;
-    for (int k = 0; k < chunks; ++k) s += (double)part[(size_t)k * C + c];
-    out[c] += (float)s;
+    int c;
+    double t[1];
+    if (col_final_sums<1>(part, chunks, C, c, t)) out[c] += (float)t[0];
 }
 
 // ------------------------------------------------------------------ batch-norm
@@ -266,14 +297,10 @@ __global__ void k_bn_stat_partial(const T *__restrict__ x, int rows, int C, ColP
 __global__ void k_bn_stat_final(const float *__restrict__ part, int chunks, int C, int rows, float eps,
                                 float *stats)
 {
-    int c = blockIdx.x * TPB + threadIdx.x;
-    if (c >= C) return;
-    double s = 0.0, ss = 0.0;
-    for (int k = 0; k < chunks; ++k) {
-        s += (double)part[(size_t)k * C + c];
-        ss += (double)part[((size_t)chunks + k) * C + c];
-    }
-    double m = (double)rows, mu = s / m, var = ss / m - mu * mu;
+    int c;
+    double t[2];
+    if (!col_final_sums<2>(part, chunks, C, c, t)) return;
+    double m = (double)rows, mu = t[0] / m, var = t[1] / m - mu * mu;
     if (var < 0.0) var = 0.0;
     stats[c] = (float)mu;
     stats[C + c] = (float)(1.0 / sqrt(var + (double)eps));
@@ -322,17 +349,13 @@ __global__ void k_bn_bwd_partial(const T *__restrict__ x, const T *__restrict__ 
 __global__ void k_bn_bwd_final(const float *__restrict__ part, int chunks, int C, float *sums,
                                float *dgamma, float *dbeta)
 {
-    int c = blockIdx.x * TPB + threadIdx.x;
-    if (c >= C) return;
-    double s1 = 0.0, s2 = 0.0;
-    for (int k = 0; k < chunks; ++k) {
-        s1 += (double)part[(size_t)k * C + c];
-        s2 += (double)part[((size_t)chunks + k) * C + c];
-    }
-    sums[c] = (float)s1;
-    sums[C + c] = (float)s2;
-    dbeta[c] += (float)s1;
-    dgamma[c] += (float)s2;
+    int c;
+    double t[2];
+    if (!col_final_sums<2>(part, chunks, C, c, t)) return;
+    sums[c] = (float)t[0];
+    sums[C + c] = (float)t[1];
+    dbeta[c] += (float)t[0];
+    dgamma[c] += (float)t[1];
 }
 
 template <class T, int V>
@@ -468,20 +491,22 @@ __global__ void k_fill(float *p, float v, size_t n)
 }
 
 // ------------------------------------------------------------------ layout changes
+// NCHW (C channels) -> NHWC with Cp >= C physical channels, the extra ones zero
 template <class T>
 __global__ void k_nchw_to_nhwc(const T *__restrict__ src, T *dst, const T *__restrict__ gate, int accum,
-                               int N, int C, int H, int W)
+                               int N, int C, int H, int W, int Cp)
 {
     size_t i = (size_t)blockIdx.x * TPB + threadIdx.x;       // index into dst (NHWC)
-    size_t total = (size_t)N * C * H * W;
+    size_t total = (size_t)N * Cp * H * W;
     if (i >= total) return;
-    int c = (int)(i % C);
-    size_t t = i / C;
+    int c = (int)(i % Cp);
+    size_t t = i / Cp;
     int w = (int)(t % W);
     t /= W;
     int h = (int)(t % H);
     int n = (int)(t / H);
-    T v = src[(((size_t)n * C + c) * H + h) * W + w];
+    T v = from_f32<T>(0.0f);
+    if (c < C) v = src[(((size_t)n * C + c) * H + h) * W + w];
     if (gate || accum) {
         T old = v, gt = v;
         if (accum) old = dst[i];
@@ -491,8 +516,10 @@ __global__ void k_nchw_to_nhwc(const T *__restrict__ src, T *dst, const T *__res
     dst[i] = v;
 }
 
+// NHWC with Cp physical channels -> NCHW with the first C of them
 template <class T>
-__global__ void k_nhwc_to_nchw(const T *__restrict__ src, T *__restrict__ dst, int N, int C, int H, int W)
+__global__ void k_nhwc_to_nchw(const T *__restrict__ src, T *__restrict__ dst, int N, int C, int H, int W,
+                               int Cp)
 {
     size_t i = (size_t)blockIdx.x * TPB + threadIdx.x;       // index into dst (NCHW)
     size_t total = (size_t)N * C * H * W;
@@ -503,7 +530,18 @@ __global__ void k_nhwc_to_nchw(const T *__restrict__ src, T *__restrict__ dst, i
     t /= H;
     int c = (int)(t % C);
     int n = (int)(t / C);
-    dst[i] = src[(((size_t)n * H + h) * W + w) * C + c];
+    dst[i] = src[(((size_t)n * H + h) * W + w) * Cp + c];
+}
+
+// rows x Cs -> rows x Cd (zero fill when Cd > Cs, truncate when Cd < Cs)
+template <class T>
+__global__ void k_repad(const T *__restrict__ src, T *__restrict__ dst, size_t rows, int Cs, int Cd)
+{
+    size_t i = (size_t)blockIdx.x * TPB + threadIdx.x;
+    if (i >= rows * Cd) return;
+    int c = (int)(i % Cd);
+    size_t r = i / Cd;
+    dst[i] = c < Cs ? src[r * Cs + c] : from_f32<T>(0.0f);
 }
 
 #define DISPATCH_T(dt, ...)                        \
@@ -655,7 +693,7 @@ hipError_t colsum_accumulate(int dt, const void *a, int rows, int C, float *out,
         ColPlan p = col_plan(rows, C, V);
         hipLaunchKernelGGL((k_colsum_partial<T, V>), dim3(p.gx, p.chunks), dim3(TPB), 0, s, (const T *)a, rows,
                            C, p, part);
-        hipLaunchKernelGGL(k_colsum_final, dim3(blocks_for(C)), dim3(TPB), 0, s, part, p.chunks, C, out);
+        hipLaunchKernelGGL(k_colsum_final, dim3(final_blocks(C)), dim3(TPB), 0, s, part, p.chunks, C, out);
     });
     return hipGetLastError();
 }
@@ -670,7 +708,7 @@ hipError_t bn_fwd(int dt, const void *x, const float *gamma, const float *beta, 
         ColPlan p = col_plan(rows, C, V);
         hipLaunchKernelGGL((k_bn_stat_partial<T, V>), dim3(p.gx, p.chunks), dim3(TPB), 0, s, (const T *)x,
                            rows, C, p, part);
-        hipLaunchKernelGGL(k_bn_stat_final, dim3(blocks_for(C)), dim3(TPB), 0, s, part, p.chunks, C, rows,
+        hipLaunchKernelGGL(k_bn_stat_final, dim3(final_blocks(C)), dim3(TPB), 0, s, part, p.chunks, C, rows,
                            eps, stats);
         size_t nv = (size_t)rows * C / V;
         hipLaunchKernelGGL((k_bn_apply<T, V>), dim3(blocks_for(nv)), dim3(TPB), 0, s, (const T *)x, gamma,
@@ -692,7 +730,7 @@ hipError_t bn_bwd(int dt, const void *x, const void *dy, const float *gamma, con
         float *sums = part + (size_t)2 * p.chunks * C;
         hipLaunchKernelGGL((k_bn_bwd_partial<T, V>), dim3(p.gx, p.chunks), dim3(TPB), 0, s, (const T *)x,
                            (const T *)dy, stats, rows, C, p, part);
-        hipLaunchKernelGGL(k_bn_bwd_final, dim3(blocks_for(C)), dim3(TPB), 0, s, part, p.chunks, C, sums,
+        hipLaunchKernelGGL(k_bn_bwd_final, dim3(final_blocks(C)), dim3(TPB), 0, s, part, p.chunks, C, sums,
                            dgamma, dbeta);
         if (dx) {
             size_t nv = (size_t)rows * C / V;
@@ -760,24 +798,35 @@ hipError_t fill_f32(float *p, float v, size_t n, hipStream_t s)
 }
 
 hipError_t nchw_to_nhwc(int dt, const void *src, void *dst, GradEpi epi, int N, int C, int H, int W,
+                        int Cp, hipStream_t s)
+{
+    size_t n = (size_t)N * Cp * H * W;
+    if (n == 0) return hipSuccess;
+    DISPATCH_T(dt, {
+        hipLaunchKernelGGL((k_nchw_to_nhwc<T>), dim3(blocks_for(n)), dim3(TPB), 0, s, (const T *)src, (T *)dst,
+                           (const T *)epi.gate, epi.accum, N, C, H, W, Cp);
+    });
+    return hipGetLastError();
+}
+
+hipError_t nhwc_to_nchw(int dt, const void *src, void *dst, int N, int C, int H, int W, int Cp,
                         hipStream_t s)
 {
     size_t n = (size_t)N * C * H * W;
     if (n == 0) return hipSuccess;
     DISPATCH_T(dt, {
-        hipLaunchKernelGGL((k_nchw_to_nhwc<T>), dim3(blocks_for(n)), dim3(TPB), 0, s, (const T *)src, (T *)dst,
-                           (const T *)epi.gate, epi.accum, N, C, H, W);
+        hipLaunchKernelGGL((k_nhwc_to_nchw<T>), dim3(blocks_for(n)), dim3(TPB), 0, s, (const T *)src, (T *)dst,
+                           N, C, H, W, Cp);
     });
     return hipGetLastError();
 }
 
-hipError_t nhwc_to_nchw(int dt, const void *src, void *dst, int N, int C, int H, int W, hipStream_t s)
+hipError_t nhwc_repad(int dt, const void *src, void *dst, size_t rows, int Cs, int Cd, hipStream_t s)
 {
-    size_t n = (size_t)N * C * H * W;
+    size_t n = rows * Cd;
     if (n == 0) return hipSuccess;
     DISPATCH_T(dt, {
-        hipLaunchKernelGGL((k_nhwc_to_nchw<T>), dim3(blocks_for(n)), dim3(TPB), 0, s, (const T *)src, (T *)dst,
-                           N, C, H, W);
+        hipLaunchKernelGGL((k_repad<T>), dim3(blocks_for(n)), dim3(TPB), 0, s, (const T *)src, (T *)dst, rows, Cs, Cd);
     });
     return hipGetLastError();
 }
@@ -786,7 +835,7 @@ hipError_t nhwc_to_nchw_u8(const uint8_t *src, uint8_t *dst, int N, int C, int H
 {
     size_t n = (size_t)N * C * H * W;
     if (n == 0) return hipSuccess;
-    hipLaunchKernelGGL((k_nhwc_to_nchw<uint8_t>), dim3(blocks_for(n)), dim3(TPB), 0, s, src, dst, N, C, H, W);
+    hipLaunchKernelGGL((k_nhwc_to_nchw<uint8_t>), dim3(blocks_for(n)), dim3(TPB), 0, s, src, dst, N, C, H, W, C);
     return hipGetLastError();
 }
 

@@ -33,7 +33,8 @@ size_t align_up(size_t v, size_t a = 256) { return (v + a - 1) / a * a; }
 
 struct Tensor {
     int C = 0, H = 0, W = 0;
-    size_t elems = 0;      // per micro-batch
+    int Cp = 0;            // channels as laid out in HBM (>= C: a narrow stage input is zero-padded)
+    size_t elems = 0;      // per micro-batch, physical (Cp channels)
     size_t esize = 0;      // bytes per element
     int root = -1;         // storage owner (FLATTEN outputs alias their input)
     int producer = -1;     // layer index, -1 for the stage input
@@ -53,6 +54,7 @@ struct Layer {
     float *w = nullptr, *bias = nullptr, *dw = nullptr, *db = nullptr;
     void *w_work = nullptr, *w_t = nullptr;
     size_t aux_off = 0, aux_bytes = 0;   // pool indices / BN statistics inside the slot
+    int cin_p = 0;                       // input channels as laid out in HBM (conv / linear)
     bool permute_in = false;             // LINEAR fed by a flattened (C,H,W) tensor
     int pc = 0, ph = 0, pw = 0;
 };
@@ -76,6 +78,25 @@ struct bapipe_stage {
     int n_fwd = 0, n_bwd = 0;
     std::vector<char> loss_valid;
     std::string err;
+    // measurement tap: event pairs around launches of one kernel class
+    int tap_class = -1;
+    std::vector<hipEvent_t> tap_events;
+    size_t tap_used = 0;
+    double tap_flop = 0.0, tap_bytes = 0.0;
+    bool tap_begin(int cls)
+    {
+        if (cls != tap_class || tap_used + 2 > tap_events.size()) return false;
+        (void)hipEventRecord(tap_events[tap_used], stream);
+        return true;
+    }
+    void tap_end(bool on, double flop, double bytes)
+    {
+        if (!on) return;
+        (void)hipEventRecord(tap_events[tap_used + 1], stream);
+        tap_used += 2;
+        tap_flop += flop;
+        tap_bytes += bytes;
+    }
 
     void *dev_alloc(size_t bytes)
     {
@@ -145,7 +166,7 @@ GatherConv fwd_geom(const bapipe_stage *st, const Layer &L)
         g.pad_h = g.pad_w = 0;
         return g;
     }
-    g.Hi = A.H; g.Wi = A.W; g.Ci = A.C;
+    g.Hi = A.H; g.Wi = A.W; g.Ci = A.Cp;
     g.Ho = O.H; g.Wo = O.W; g.Co = O.C;
     g.R = L.d.kh; g.S = L.d.kw;
     g.s_out = L.d.stride; g.s_in = 1;
@@ -176,6 +197,11 @@ ConvShape conv_shape(const bapipe_stage *st, const Layer &L)
     return c;
 }
 
+double conv_flop(const GatherConv &f, int logical_ci)
+{
+    return 2.0 * (double)f.N * f.Ho * f.Wo * f.Co * f.R * f.S * logical_ci;
+}
+
 bool use_mfma_gather(const bapipe_stage *st, const GatherConv &g) { return st->dt == DT_BF16 && conv_gather_mfma_supported(g); }
 bool use_mfma_wgrad(const bapipe_stage *st, const ConvShape &c) { return st->dt == DT_BF16 && conv_wgrad_mfma_supported(c); }
 
@@ -203,12 +229,13 @@ void to_internal(const Layer &L, const float *src, float *dst)
                             src[(size_t)k * In + ((size_t)c * L.ph + h) * L.pw + w];
         return;
     }
-    const int C = L.d.cin, R = L.d.kh, S = L.d.kw;
+    const int C = L.d.cin, Cp = L.cin_p, R = L.d.kh, S = L.d.kw;
+    memset(dst, 0, sizeof(float) * L.w_elems);
     for (int k = 0; k < K; ++k)
         for (int c = 0; c < C; ++c)
             for (int r = 0; r < R; ++r)
                 for (int s = 0; s < S; ++s)
-                    dst[(((size_t)k * R + r) * S + s) * C + c] = src[(((size_t)k * C + c) * R + r) * S + s];
+                    dst[(((size_t)k * R + r) * S + s) * Cp + c] = src[(((size_t)k * C + c) * R + r) * S + s];
 }
 
 void from_internal(const Layer &L, const float *src, float *dst)
@@ -228,12 +255,12 @@ void from_internal(const Layer &L, const float *src, float *dst)
                             src[(size_t)k * In + ((size_t)h * L.pw + w) * L.pc + c];
         return;
     }
-    const int C = L.d.cin, R = L.d.kh, S = L.d.kw;
+    const int C = L.d.cin, Cp = L.cin_p, R = L.d.kh, S = L.d.kw;
     for (int k = 0; k < K; ++k)
         for (int c = 0; c < C; ++c)
             for (int r = 0; r < R; ++r)
                 for (int s = 0; s < S; ++s)
-                    dst[(((size_t)k * C + c) * R + r) * S + s] = src[(((size_t)k * R + r) * S + s) * C + c];
+                    dst[(((size_t)k * C + c) * R + r) * S + s] = src[(((size_t)k * R + r) * S + s) * Cp + c];
 }
 
 // working copies of one layer's weights from its fp32 master
@@ -243,7 +270,7 @@ hipError_t refresh_work(bapipe_stage *st, Layer &L)
     hipError_t e = recast(st->dt, L.w, L.w_work, L.w_elems, st->stream);
     if (e != hipSuccess) return e;
     int R = L.d.kind == BAPIPE_LINEAR ? 1 : L.d.kh, S = L.d.kind == BAPIPE_LINEAR ? 1 : L.d.kw;
-    return make_dgrad_filter(st->dt, L.w, L.w_t, L.d.cout, R, S, L.d.cin, st->stream);
+    return make_dgrad_filter(st->dt, L.w, L.w_t, L.d.cout, R, S, L.cin_p, st->stream);
 }
 
 // ---------------------------------------------------------------- per-layer forward
@@ -273,29 +300,42 @@ int layer_forward(bapipe_stage *st, int li, const FwdCtx &c)
     case BAPIPE_LINEAR: {
         GatherConv g = fwd_geom(st, L);
         GradEpi none{nullptr, 0};
-        if (use_mfma_gather(st, g))
+        const bool mf = use_mfma_gather(st, g);
+        const bool tp = st->tap_begin(mf ? BAPIPE_KC_CONV_GATHER_MFMA : BAPIPE_KC_CONV_DIRECT);
+        if (mf)
             HIPCHK(conv_gather_mfma(a, L.w_work, L.bias, o, L.d.fuse_relu, none, g, s));
         else
             HIPCHK(conv_gather_direct(dt, a, L.w_work, L.bias, o, L.d.fuse_relu, none, g, s));
+        st->tap_end(tp, conv_flop(g, L.d.cin), 0.0);
         break;
     }
-    case BAPIPE_RELU:
+    case BAPIPE_RELU: {
+        const bool tp = st->tap_begin(BAPIPE_KC_ELEMENTWISE);
         HIPCHK(relu_fwd(dt, a, o, O.elems, s));
+        st->tap_end(tp, 0.0, 2.0 * O.bytes());
         break;
+    }
     case BAPIPE_MAXPOOL2D: {
         const Tensor &A = st->tensors[L.a];
+        const bool tp = st->tap_begin(BAPIPE_KC_POOL);
         HIPCHK(maxpool2x2_fwd(dt, a, o, (uint8_t *)(st->slot(c.mbid) + L.aux_off), st->mb, A.H, A.W, A.C, s));
+        st->tap_end(tp, 0.0, (double)A.bytes() + O.bytes() + O.elems);           // read x, write y + idx
         break;
     }
     case BAPIPE_BATCHNORM2D: {
         const Tensor &A = st->tensors[L.a];
+        const bool tp = st->tap_begin(BAPIPE_KC_BATCHNORM);
         HIPCHK(bn_fwd(dt, a, L.w, L.bias, L.d.eps, o, (float *)(st->slot(c.mbid) + L.aux_off), L.d.fuse_relu,
                       st->mb * A.H * A.W, A.C, st->work, s));
+        st->tap_end(tp, 0.0, 3.0 * A.bytes());                                   // read x twice, write y
         break;
     }
-    case BAPIPE_ADD:
+    case BAPIPE_ADD: {
+        const bool tp = st->tap_begin(BAPIPE_KC_ELEMENTWISE);
         HIPCHK(add_fwd(dt, a, in_ptr(st, L.b, c), o, L.d.fuse_relu, O.elems, s));
+        st->tap_end(tp, 0.0, 3.0 * O.bytes());
         break;
+    }
     case BAPIPE_FLATTEN:
         break;   // alias of its input
     case BAPIPE_SOFTMAX_XENT:
@@ -351,35 +391,50 @@ int layer_backward(bapipe_stage *st, int li, BwdCtx &c)
         const void *g = grad_ptr(st, L.o, c);
         const void *x = st->tptr(L.a, c.mbid);
         ConvShape cs = conv_shape(st, L);
-        if (use_mfma_wgrad(st, cs))
-            HIPCHK(conv_wgrad_mfma(x, g, L.dw, st->work, cs, s));
-        else
-            HIPCHK(conv_wgrad_direct(dt, x, g, L.dw, st->work, cs, s));
-        if (L.db) HIPCHK(colsum_accumulate(dt, g, cs.N * cs.P * cs.Q, cs.K, L.db, st->work, s));
+        const double flop = conv_flop(fwd_geom(st, L), L.d.cin);
+        {
+            const bool mf = use_mfma_wgrad(st, cs);
+            const bool tp = st->tap_begin(mf ? BAPIPE_KC_CONV_WGRAD_MFMA : BAPIPE_KC_CONV_DIRECT);
+            if (mf)
+                HIPCHK(conv_wgrad_mfma(x, g, L.dw, st->work, cs, s));
+            else
+                HIPCHK(conv_wgrad_direct(dt, x, g, L.dw, st->work, cs, s));
+            st->tap_end(tp, flop, 0.0);
+        }
+        if (L.db) {
+            const bool tp = st->tap_begin(BAPIPE_KC_ELEMENTWISE);
+            HIPCHK(colsum_accumulate(dt, g, cs.N * cs.P * cs.Q, cs.K, L.db, st->work, s));
+            st->tap_end(tp, 0.0, (double)O.bytes());
+        }
         if (a_grad) {
             GatherConv dg = dgrad_geom(st, L);
             GradEpi e = epi_for(st, L.a, c);
             void *dx = grad_ptr(st, L.a, c);
-            if (use_mfma_gather(st, dg))
+            const bool mf = use_mfma_gather(st, dg);
+            const bool tp = st->tap_begin(mf ? BAPIPE_KC_CONV_GATHER_MFMA : BAPIPE_KC_CONV_DIRECT);
+            if (mf)
                 HIPCHK(conv_gather_mfma(g, L.w_t, nullptr, dx, 0, e, dg, s));
-            else {
-                // the direct kernel takes the plain-store path unless told it writes a gradient
+            else
                 HIPCHK(conv_gather_direct(dt, g, L.w_t, nullptr, dx, 0, e, dg, s));
-            }
+            st->tap_end(tp, flop, 0.0);
         }
         break;
     }
     case BAPIPE_RELU:
         if (a_grad) {
             GradEpi e = epi_for(st, L.a, c);
+            const bool tp = st->tap_begin(BAPIPE_KC_ELEMENTWISE);
             HIPCHK(relu_bwd(dt, st->tptr(L.o, c.mbid), grad_ptr(st, L.o, c), grad_ptr(st, L.a, c), e, O.elems, s));
+            st->tap_end(tp, 0.0, 3.0 * O.bytes());
         }
         break;
     case BAPIPE_MAXPOOL2D:
         if (a_grad) {
             GradEpi e = epi_for(st, L.a, c, L.o);
+            const bool tp = st->tap_begin(BAPIPE_KC_POOL);
             HIPCHK(maxpool2x2_bwd(dt, grad_ptr(st, L.o, c), (const uint8_t *)(st->slot(c.mbid) + L.aux_off),
                                   grad_ptr(st, L.a, c), e, st->mb, A.H, A.W, A.C, s));
+            st->tap_end(tp, 0.0, (double)O.bytes() + O.elems + A.bytes() + (e.gate ? O.bytes() : 0));
         }
         break;
     case BAPIPE_BATCHNORM2D: {
@@ -389,21 +444,28 @@ int layer_backward(bapipe_stage *st, int li, BwdCtx &c)
             e = epi_for(st, L.a, c);
             dx = grad_ptr(st, L.a, c);
         }
+        const bool tp = st->tap_begin(BAPIPE_KC_BATCHNORM);
         HIPCHK(bn_bwd(dt, st->tptr(L.a, c.mbid), grad_ptr(st, L.o, c), L.w,
                       (const float *)(st->slot(c.mbid) + L.aux_off), dx, L.dw, L.db, e, st->mb * A.H * A.W, A.C,
                       st->work, s));
+        st->tap_end(tp, 0.0, 5.0 * A.bytes());                                   // x, dy twice each; dx once
         break;
     }
     case BAPIPE_ADD: {
         const void *g = grad_ptr(st, L.o, c);
+        const bool tp = st->tap_begin(BAPIPE_KC_ELEMENTWISE);
+        double bytes = 0.0;
         if (a_grad) {
             GradEpi e = epi_for(st, L.a, c);
             HIPCHK(grad_copy(dt, g, grad_ptr(st, L.a, c), e, O.elems, s));
+            bytes += 2.0 * O.bytes();
         }
         if (st->tensors[st->tensors[L.b].root].need_grad) {
             GradEpi e = epi_for(st, L.b, c);
             HIPCHK(grad_copy(dt, g, grad_ptr(st, L.b, c), e, O.elems, s));
+            bytes += 2.0 * O.bytes();
         }
+        st->tap_end(tp, 0.0, bytes);
         break;
     }
     case BAPIPE_FLATTEN:
@@ -438,6 +500,7 @@ void bapipe_stage_destroy(bapipe_stage_t *st)
     st->dev_free(st->grads);
     st->dev_free(st->work);
     st->dev_free(st->losses);
+    for (hipEvent_t e : st->tap_events) (void)hipEventDestroy(e);
     delete st;
 }
 
@@ -479,8 +542,16 @@ int bapipe_stage_create(const bapipe_layer_desc_t *layers, int n_layers, int mic
     st->tensors.resize(n_layers + 1);
     {
         Tensor &T = st->tensors[0];
-        T.C = opts->in_c; T.H = opts->in_h; T.W = opts->in_w;
-        T.elems = (size_t)micro_batch * T.C * T.H * T.W;
+        T.C = T.Cp = opts->in_c; T.H = opts->in_h; T.W = opts->in_w;
+        // a bf16 stage input with a channel count that is not a multiple of 8 (e.g. RGB) is
+        // zero-padded to 8 in HBM when only convolutions read it, so that they can take the MFMA path
+        bool only_convs = true;
+        for (int i = 0; i < n_layers; ++i)
+            if ((layers[i].src0 == -1 && layers[i].kind != BAPIPE_CONV2D) ||
+                (layers[i].kind == BAPIPE_ADD && layers[i].src1 == -1))
+                only_convs = false;
+        if (st->dt == DT_BF16 && T.C % 8 != 0 && only_convs) T.Cp = (T.C + 7) / 8 * 8;
+        T.elems = (size_t)micro_batch * T.Cp * T.H * T.W;
         T.esize = es; T.root = 0; T.producer = -1;
     }
     st->layers.resize(n_layers);
@@ -506,7 +577,8 @@ int bapipe_stage_create(const bapipe_layer_desc_t *layers, int n_layers, int mic
             if (A.H + 2 * d.pad < d.kh || A.W + 2 * d.pad < d.kw || ho <= 0 || wo <= 0)
                 return create_fail(BAPIPE_E_SHAPE, "layer %d: filter larger than padded input", i);
             O.C = d.cout; O.H = ho; O.W = wo;
-            L.w_elems = (size_t)d.cout * d.kh * d.kw * d.cin;
+            L.cin_p = A.Cp;
+            L.w_elems = (size_t)d.cout * d.kh * d.kw * L.cin_p;
             L.b_elems = d.has_bias ? d.cout : 0;
             break;
         }
@@ -515,6 +587,7 @@ int bapipe_stage_create(const bapipe_layer_desc_t *layers, int n_layers, int mic
             if ((size_t)A.C * A.H * A.W != (size_t)d.cin)
                 return create_fail(BAPIPE_E_SHAPE, "layer %d: cin=%d but input has %zu features", i, d.cin, (size_t)A.C * A.H * A.W);
             O.C = d.cout; O.H = O.W = 1;
+            L.cin_p = d.cin;
             L.w_elems = (size_t)d.cout * d.cin;
             L.b_elems = d.has_bias ? d.cout : 0;
             const Tensor &R = st->tensors[A.root];
@@ -558,6 +631,7 @@ int bapipe_stage_create(const bapipe_layer_desc_t *layers, int n_layers, int mic
         default:
             return create_fail(BAPIPE_E_INVALID, "layer %d: unknown kind %d", i, d.kind);
         }
+        O.Cp = O.C;
         O.elems = (size_t)micro_batch * O.C * O.H * O.W;
         st->tensors[L.a].consumers.push_back(i);
         if (L.b >= 0) st->tensors[L.b].consumers.push_back(i);
@@ -710,7 +784,9 @@ int bapipe_stage_forward(bapipe_stage_t *st, int mb_id, const void *x_dev, void 
     FwdCtx c{mb_id, nullptr};
     GradEpi none{nullptr, 0};
     if (st->opts.io_layout == BAPIPE_NCHW) {
-        HIPCHK(nchw_to_nhwc(dt, x_dev, st->tptr(0, mb_id), none, st->mb, In.C, In.H, In.W, s));
+        HIPCHK(nchw_to_nhwc(dt, x_dev, st->tptr(0, mb_id), none, st->mb, In.C, In.H, In.W, In.Cp, s));
+    } else if (In.Cp != In.C) {
+        HIPCHK(nhwc_repad(dt, x_dev, st->tptr(0, mb_id), (size_t)st->mb * In.H * In.W, In.C, In.Cp, s));
     } else if (In.stashed) {
         HIPCHK(hipMemcpyAsync(st->tptr(0, mb_id), x_dev, In.bytes(), hipMemcpyDeviceToDevice, s));
     } else {
@@ -725,7 +801,7 @@ int bapipe_stage_forward(bapipe_stage_t *st, int mb_id, const void *x_dev, void 
         const Tensor &O = st->tensors[last];
         const void *src = in_ptr(st, last, c);
         if (st->opts.io_layout == BAPIPE_NCHW && O.esize == dt_size(dt) && O.H * O.W > 1)
-            HIPCHK(nhwc_to_nchw(dt, src, y_dev, st->mb, O.C, O.H, O.W, s));
+            HIPCHK(nhwc_to_nchw(dt, src, y_dev, st->mb, O.C, O.H, O.W, O.Cp, s));
         else
             HIPCHK(hipMemcpyAsync(y_dev, src, O.bytes(), hipMemcpyDeviceToDevice, s));
     }
@@ -751,7 +827,7 @@ int bapipe_stage_backward(bapipe_stage_t *st, int mb_id, const void *dy_dev_or_l
     c.written.assign(st->tensors.size(), 0);
     const Tensor &In = st->tensors[0];
     const bool want_dx = In.need_grad && dx_dev != nullptr;
-    if (want_dx && (nhwc || In.H * In.W == 1)) c.dx_direct = dx_dev;
+    if (want_dx && (nhwc || In.H * In.W == 1) && In.Cp == In.C) c.dx_direct = dx_dev;
     if (st->layers[nl - 1].d.kind == BAPIPE_SOFTMAX_XENT) {
         c.labels = (const int32_t *)dy_dev_or_labels;
     } else {
@@ -760,7 +836,7 @@ int bapipe_stage_backward(bapipe_stage_t *st, int mb_id, const void *dy_dev_or_l
         GradEpi e{nullptr, 0};
         if (st->tensors[r].gated) e.gate = st->tptr(r, mb_id);
         if (!nhwc && O.H * O.W > 1) {
-            HIPCHK(nchw_to_nhwc(dt, dy_dev_or_labels, st->gptr(last), e, st->mb, O.C, O.H, O.W, s));
+            HIPCHK(nchw_to_nhwc(dt, dy_dev_or_labels, st->gptr(last), e, st->mb, O.C, O.H, O.W, O.Cp, s));
         } else if (e.gate || r == 0) {
             HIPCHK(grad_copy(dt, dy_dev_or_labels, st->gptr(last), e, O.elems, s));
         } else {
@@ -772,8 +848,12 @@ int bapipe_stage_backward(bapipe_stage_t *st, int mb_id, const void *dy_dev_or_l
         int rc = layer_backward(st, i, c);
         if (rc != BAPIPE_OK) return rc;
     }
-    if (want_dx && !c.dx_direct)
-        HIPCHK(nhwc_to_nchw(dt, st->gptr(0), dx_dev, st->mb, In.C, In.H, In.W, s));
+    if (want_dx && !c.dx_direct) {
+        if (nhwc)
+            HIPCHK(nhwc_repad(dt, st->gptr(0), dx_dev, (size_t)st->mb * In.H * In.W, In.Cp, In.C, s));
+        else
+            HIPCHK(nhwc_to_nchw(dt, st->gptr(0), dx_dev, st->mb, In.C, In.H, In.W, In.Cp, s));
+    }
     if (c.labels) st->loss_valid[mb_id] = 1;
     st->n_bwd++;
     return BAPIPE_OK;
@@ -791,7 +871,7 @@ int bapipe_stage_step(bapipe_stage_t *st, float lr)
         if (L.b_elems) HIPCHK(sgd_step(st->dt, L.bias, L.db, lr, nullptr, L.b_elems, st->stream));
         if (mat) {
             int R = L.d.kind == BAPIPE_LINEAR ? 1 : L.d.kh, S = L.d.kind == BAPIPE_LINEAR ? 1 : L.d.kw;
-            HIPCHK(make_dgrad_filter(st->dt, L.w, L.w_t, L.d.cout, R, S, L.d.cin, st->stream));
+            HIPCHK(make_dgrad_filter(st->dt, L.w, L.w_t, L.d.cout, R, S, L.cin_p, st->stream));
         }
     }
     st->n_fwd = st->n_bwd = 0;
@@ -895,6 +975,41 @@ int bapipe_stage_stash_bytes(const bapipe_stage_t *st, uint64_t *per_mb, int *de
     if (!st) return BAPIPE_E_INVALID;
     if (per_mb) *per_mb = st->slot_bytes;
     if (depth) *depth = st->depth;
+    return BAPIPE_OK;
+}
+
+int bapipe_stage_kernel_timing(bapipe_stage_t *st, int kernel_class)
+{
+    if (!st) return BAPIPE_E_INVALID;
+    if (kernel_class >= BAPIPE_KC_COUNT) return st->fail(BAPIPE_E_INVALID, "kernel_timing: class %d", kernel_class);
+    HIPCHK(hipStreamSynchronize(st->stream));
+    if (kernel_class >= 0 && st->tap_events.empty()) {
+        st->tap_events.resize(2 * 4096);
+        for (auto &e : st->tap_events) HIPCHK(hipEventCreate(&e));
+    }
+    st->tap_class = kernel_class < 0 ? -1 : kernel_class;
+    st->tap_used = 0;
+    st->tap_flop = st->tap_bytes = 0.0;
+    return BAPIPE_OK;
+}
+
+int bapipe_stage_kernel_timing_read(bapipe_stage_t *st, double *total_ms, uint64_t *launches, double *flop,
+                                    double *bytes)
+{
+    if (!st) return BAPIPE_E_INVALID;
+    HIPCHK(hipStreamSynchronize(st->stream));
+    double ms = 0.0;
+    for (size_t i = 0; i + 1 < st->tap_used; i += 2) {
+        float t = 0.f;
+        HIPCHK(hipEventElapsedTime(&t, st->tap_events[i], st->tap_events[i + 1]));
+        ms += t;
+    }
+    if (total_ms) *total_ms = ms;
+    if (launches) *launches = st->tap_used / 2;
+    if (flop) *flop = st->tap_flop;
+    if (bytes) *bytes = st->tap_bytes;
+    st->tap_used = 0;
+    st->tap_flop = st->tap_bytes = 0.0;
     return BAPIPE_OK;
 }
 
