@@ -53,79 +53,104 @@ template <int BK> __device__ __forceinline__ int swz(int row)
 // ------------------------------------------------------------------------------------------
 // gather convolution
 // ------------------------------------------------------------------------------------------
-template <int BP, int BC, int WP, int WC, int BK, bool S1>
+typedef __attribute__((address_space(3))) void lds_void_t;
+
+// s_waitcnt with only the vector-memory counter set: wait until at most n loads are in flight
+#define WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(0x0F70 | ((n) & 15) | (((n) >> 4) << 14))
+
+// The operand tiles travel HBM/L2 -> LDS without touching registers: buffer_load_dwordx4 ... lds
+// writes the 64 lanes' 16-byte chunks to 64 consecutive LDS slots starting at a wave-uniform
+// address, and a lane whose offset is outside the buffer gets zeros (that is the zero padding of
+// the convolution and the ragged tile edges).  The XOR swizzle of the tile layout is applied by
+// choosing WHICH chunk a lane fetches, since WHERE it lands is fixed by the lane id.
+// STAGES tiles form a ring; tile kt+STAGES-1 is requested right after the barrier that retires
+// tile kt-1, so STAGES-1 K-tiles of latency are covered while the MFMAs run.
+template <int BP, int BC, int WP, int WC, int BK, int STAGES, bool S1, bool TAPS_INNER>
 __global__ __launch_bounds__(WP *WC * 64, 2) void k_gather_mfma(
     const bf16_t *__restrict__ in, const bf16_t *__restrict__ wt, const float *__restrict__ bias,
     bf16_t *out, const bf16_t *__restrict__ gate, int accum, int relu, int is_grad, GatherConv g,
-    int tiles_c)
+    int tiles_c, unsigned in_bytes, unsigned wt_bytes)
 {
-    constexpr int NT = WP * WC * 64;
+    constexpr int NT = WP * WC * 64, NW = WP * WC;
     constexpr int CPR = BK / 8;              // 16-byte chunks per tile row
-    constexpr int RPP = NT / CPR;            // tile rows covered by one pass of all threads
-    constexpr int XP = BP / RPP;             // passes over the pixel tile
-    constexpr int WPASS = BC / RPP;          // passes over the filter tile
+    constexpr int RPW = 64 / CPR;            // tile rows one wave-wide load covers
+    constexpr int XL = BP / (RPW * NW);      // loads per wave for the pixel tile
+    constexpr int WL = BC / (RPW * NW);      // loads per wave for the filter tile
     constexpr int WT_P = BP / WP, WT_C = BC / WC;
     constexpr int TP = WT_P / 32, TC = WT_C / 32;
     constexpr int KSUB = BK / 16;
     constexpr int SROW = BC + 4;             // staging row (elements): 8-byte aligned, odd multiple of 8 bytes
-    static_assert(XP >= 1 && WPASS >= 1 && BP % RPP == 0 && BC % RPP == 0, "tile/thread mismatch");
+    constexpr int STAGE_ELEMS = (BP + BC) * BK;
+    static_assert(XL >= 1 && WL >= 1 && BP % (RPW * NW) == 0 && BC % (RPW * NW) == 0, "tile/thread mismatch");
+    static_assert(BK == 32, "swizzle below assumes 4 chunks per row");
 
     extern __shared__ __align__(16) unsigned char smem[];
-    uint16_t *sW = reinterpret_cast<uint16_t *>(smem);                 // [2][BC*BK]
-    uint16_t *sX = sW + 2 * BC * BK;                                   // [2][BP*BK]
+    uint16_t *ring = reinterpret_cast<uint16_t *>(smem);               // [STAGES][ W tile | X tile ]
     uint16_t *sO = reinterpret_cast<uint16_t *>(smem);                 // [WT_P][SROW] (epilogue)
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wp = wave % WP, wc = wave / WP;
-    const int lc = tid % CPR, lr = tid / CPR;
+    // slot (row, c') a lane fills inside one wave-wide load, and the chunk column it must fetch
+    const int lrow = lane >> 2;
+    const int lc = (lane & 3) ^ ((lane >> 4) & 3);       // = c' ^ swz(row); the same for every load
 
     const int bid = xcd_remap(blockIdx.x, gridDim.x);
     const int tile_c = bid % tiles_c, tile_p = bid / tiles_c;
     const int co0 = tile_c * BC;
-    const long long pix0 = (long long)tile_p * BP;
-    const long long npix = (long long)g.N * g.Ho * g.Wo;
+    const int pix0 = tile_p * BP;                    // pixel counts fit 31 bits (checked by the launcher)
+    const int npix = g.N * g.Ho * g.Wo;
     const int K = g.R * g.S * g.Ci;
-    const int KT = (K + BK - 1) / BK;
+    const int KT = TAPS_INNER ? (g.Ci / BK) * g.R * g.S : (K + BK - 1) / BK;
+    constexpr unsigned OOB = 0x80000000u;
 
-    // ---- per-thread gather state: the pixel rows this thread loads
-    int hb[XP], wb[XP];
-    const bf16_t *xbase[XP];
+    __amdgpu_buffer_rsrc_t xrsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t *>(in), 0, (int)in_bytes, 0x00020000);
+    __amdgpu_buffer_rsrc_t wrsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t *>(wt), 0, (int)wt_bytes, 0x00020000);
+
+    // ---- per-lane gather state: the pixel rows this lane fetches (row = (i*NW + wave)*RPW + lrow)
+    int hb[XL], wb[XL];
+    unsigned xoff[XL];                       // byte offset of pixel (n, 0, 0), channel 0
 #pragma unroll
-    for (int i = 0; i < XP; ++i) {
-        long long p = pix0 + lr + i * RPP;
+    for (int i = 0; i < XL; ++i) {
+        int p = pix0 + (i * NW + wave) * RPW + lrow;
         if (p < npix) {
-            int ow = (int)(p % g.Wo);
-            long long t = p / g.Wo;
-            int oh = (int)(t % g.Ho);
-            int n = (int)(t / g.Ho);
+            int ow = p % g.Wo;
+            int t = p / g.Wo;
+            int oh = t % g.Ho;
+            int n = t / g.Ho;
             hb[i] = oh * g.s_out - g.pad_h;
             wb[i] = ow * g.s_out - g.pad_w;
-            xbase[i] = in + (size_t)n * g.Hi * g.Wi * g.Ci;
+            xoff[i] = (unsigned)n * (unsigned)(g.Hi * g.Wi * g.Ci) * 2u;
         } else {
             hb[i] = -(1 << 28);          // fails every bounds check below
             wb[i] = 0;
-            xbase[i] = in;
+            xoff[i] = 0;
         }
     }
-    const bf16_t *wbase[WPASS];
-    bool wok[WPASS];
+    unsigned woff[WL];
 #pragma unroll
-    for (int i = 0; i < WPASS; ++i) {
-        int co = co0 + lr + i * RPP;
-        wok[i] = co < g.Co;
-        wbase[i] = wt + (size_t)(wok[i] ? co : 0) * K;
+    for (int i = 0; i < WL; ++i) {
+        int co = co0 + (i * NW + wave) * RPW + lrow;
+        woff[i] = co < g.Co ? (unsigned)co * (unsigned)K * 2u : OOB;
     }
-    // k position (r, s, ci) of this thread's chunk column, advanced by BK per K-tile
-    int kk = 8 * lc;
+    // K order.  TAPS_INNER (Ci a multiple of BK): tile kt covers channels [cit*BK, +BK) of tap
+    // (kt % RS), taps innermost, so that consecutive tiles re-read almost the same pixels (shifted
+    // by one column / one row) and hit in the CU's vector L1.  Otherwise k = (r, s, ci) flattened,
+    // ci fastest, and a tile may straddle taps.  Both operands use the same order.
+    int kk = 8 * lc;                                   // flattened k of this lane's chunk (generic order)
     int kr = kk / (g.S * g.Ci), ks = (kk / g.Ci) % g.S, kc = kk % g.Ci;
+    if (TAPS_INNER) {
+        kr = 0;
+        ks = 0;
+        kc = 8 * lc;                                   // channel offset; tap = (kr, ks)
+    }
 
-    chunk16 rx[XP], rw[WPASS];
-    const chunk16 zero16 = {0u, 0u, 0u, 0u};
-
-    auto load_tile = [&]() {
-        const bool kin = kr < g.R;
+    auto issue_tile = [&](int stage) {
+        uint16_t *sw = ring + stage * STAGE_ELEMS, *sx = sw + BC * BK;
+        const bool kin = TAPS_INNER ? (kc < g.Ci) : (kr < g.R);
+        const unsigned koff = (unsigned)(TAPS_INNER ? (kr * g.S + ks) * g.Ci + kc : kk) * 2u;
 #pragma unroll
-        for (int i = 0; i < XP; ++i) {
+        for (int i = 0; i < XL; ++i) {
             int hn = hb[i] + kr, wn = wb[i] + ks;
             int ih, iw;
             bool ok;
@@ -138,35 +163,33 @@ __global__ __launch_bounds__(WP *WC * 64, 2) void k_gather_mfma(
                 iw = wn / g.s_in;
                 ok = kin && hn >= 0 && wn >= 0 && ih * g.s_in == hn && iw * g.s_in == wn && ih < g.Hi && iw < g.Wi;
             }
-            rx[i] = ok ? *reinterpret_cast<const chunk16 *>(xbase[i] + ((size_t)ih * g.Wi + iw) * g.Ci + kc)
-                       : zero16;
+            unsigned vo = ok ? xoff[i] + (unsigned)((ih * g.Wi + iw) * g.Ci + kc) * 2u : OOB;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(xrsrc, (lds_void_t *)(sx + (i * NW + wave) * RPW * BK), 16, (int)vo, 0, 0, 0);
         }
 #pragma unroll
-        for (int i = 0; i < WPASS; ++i)
-            rw[i] = (wok[i] && kin) ? *reinterpret_cast<const chunk16 *>(wbase[i] + kk) : zero16;
-    };
-    auto advance_k = [&]() {
-        kk += BK;
-        kc += BK;
-        while (kc >= g.Ci) {
-            kc -= g.Ci;
+        for (int i = 0; i < WL; ++i) {
+            unsigned vo = (kin && woff[i] != OOB) ? woff[i] + koff : OOB;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(wrsrc, (lds_void_t *)(sw + (i * NW + wave) * RPW * BK), 16, (int)vo, 0, 0, 0);
+        }
+        // advance to the next K-tile
+        if (TAPS_INNER) {
             if (++ks == g.S) {
                 ks = 0;
-                ++kr;
+                if (++kr == g.R) {
+                    kr = 0;
+                    kc += BK;
+                }
             }
-        }
-    };
-    auto store_tile = [&](int buf) {
-        uint16_t *dx = sX + buf * BP * BK, *dw = sW + buf * BC * BK;
-#pragma unroll
-        for (int i = 0; i < XP; ++i) {
-            int row = lr + i * RPP;
-            *reinterpret_cast<chunk16 *>(dx + row * BK + ((lc ^ swz<BK>(row)) << 3)) = rx[i];
-        }
-#pragma unroll
-        for (int i = 0; i < WPASS; ++i) {
-            int row = lr + i * RPP;
-            *reinterpret_cast<chunk16 *>(dw + row * BK + ((lc ^ swz<BK>(row)) << 3)) = rw[i];
+        } else {
+            kk += BK;
+            kc += BK;
+            while (kc >= g.Ci) {
+                kc -= g.Ci;
+                if (++ks == g.S) {
+                    ks = 0;
+                    ++kr;
+                }
+            }
         }
     };
 
@@ -178,20 +201,9 @@ __global__ __launch_bounds__(WP *WC * 64, 2) void k_gather_mfma(
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.0f;
 
-    load_tile();
-    advance_k();
-    store_tile(0);
-    __syncthreads();
-
     const int frow = lane & 31, fhalf = lane >> 5;
-    for (int kt = 0; kt < KT; ++kt) {
-        const int buf = kt & 1;
-        const bool more = kt + 1 < KT;
-        if (more) {
-            load_tile();
-            advance_k();
-        }
-        const uint16_t *cx = sX + buf * BP * BK, *cw = sW + buf * BC * BK;
+    auto compute_tile = [&](int stage) {
+        const uint16_t *cw = ring + stage * STAGE_ELEMS, *cx = cw + BC * BK;
 #pragma unroll
         for (int ks16 = 0; ks16 < KSUB; ++ks16) {
             const int ch = 2 * ks16 + fhalf;
@@ -212,11 +224,27 @@ __global__ __launch_bounds__(WP *WC * 64, 2) void k_gather_mfma(
                 for (int b = 0; b < TP; ++b)
                     acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[a], fb[b], acc[a][b], 0, 0, 0);
         }
-        if (more) store_tile(buf ^ 1);
-        __syncthreads();
+    };
+
+    // every iteration requests exactly XL+WL loads per wave (tiles past the end fetch zeros into a
+    // stage nobody reads), so "at most (STAGES-2)*(XL+WL) in flight" means tile kt has landed
+    constexpr int NLOAD = XL + WL;
+#pragma unroll
+    for (int st = 0; st < STAGES - 1; ++st) issue_tile(st);
+    int rd = 0, wr = STAGES - 1;
+    for (int kt = 0; kt < KT; ++kt) {
+        WAIT_VMCNT((STAGES - 2) * NLOAD);
+        __builtin_amdgcn_s_barrier();
+        issue_tile(wr);
+        compute_tile(rd);
+        rd = rd + 1 == STAGES ? 0 : rd + 1;
+        wr = wr + 1 == STAGES ? 0 : wr + 1;
     }
+    WAIT_VMCNT(0);
+    __syncthreads();
 
     // ---- epilogue: one pixel band (the rows of the waves with the same wp) at a time
+    const chunk16 zero16 = {0u, 0u, 0u, 0u};
     for (int band = 0; band < WP; ++band) {
         if (wp == band) {
 #pragma unroll
@@ -252,7 +280,7 @@ __global__ __launch_bounds__(WP *WC * 64, 2) void k_gather_mfma(
         constexpr int CH8 = BC / 8;     // 16-byte units per pixel row
         for (int u = tid; u < WT_P * CH8; u += NT) {
             const int prow = u / CH8, c8i = u % CH8;
-            const long long p = pix0 + band * WT_P + prow;
+            const int p = pix0 + band * WT_P + prow;
             const int co = co0 + c8i * 8;
             if (p < npix && co < g.Co) {
                 chunk8 lo = *reinterpret_cast<const chunk8 *>(sO + prow * SROW + c8i * 8);
@@ -287,27 +315,43 @@ __global__ __launch_bounds__(WP *WC * 64, 2) void k_gather_mfma(
     }
 }
 
-template <int BP, int BC, int WP, int WC, int BK>
+template <int BP, int BC, int WP, int WC, int BK, int STAGES>
 hipError_t launch_gather(const void *in, const void *wt, const float *bias, void *out, int relu, GradEpi epi,
                          const GatherConv &g, hipStream_t s)
 {
     constexpr int NT = WP * WC * 64;
-    constexpr size_t main_bytes = (size_t)2 * (BP + BC) * BK * 2;
+    constexpr size_t main_bytes = (size_t)STAGES * (BP + BC) * BK * 2;
     constexpr size_t epi_bytes = (size_t)(BP / WP) * (BC + 4) * 2;
     constexpr size_t smem = main_bytes > epi_bytes ? main_bytes : epi_bytes;
-    static_assert(smem <= 64 * 1024, "dynamic LDS above the default limit");
+    static_assert(smem <= 80 * 1024, "two blocks must fit the 160 KB LDS of a CU");
     const long long npix = (long long)g.N * g.Ho * g.Wo;
     const int tiles_p = (int)((npix + BP - 1) / BP), tiles_c = (g.Co + BC - 1) / BC;
     const int is_grad = (epi.gate != nullptr || epi.accum) ? 1 : 0;
+    const unsigned in_bytes = (unsigned)((size_t)g.N * g.Hi * g.Wi * g.Ci * 2);
+    const unsigned wt_bytes = (unsigned)((size_t)g.Co * g.R * g.S * g.Ci * 2);
     dim3 grid((unsigned)(tiles_p * tiles_c));
-    if (g.s_in == 1)
-        hipLaunchKernelGGL((k_gather_mfma<BP, BC, WP, WC, BK, true>), grid, dim3(NT), smem, s, (const bf16_t *)in,
-                           (const bf16_t *)wt, bias, (bf16_t *)out, (const bf16_t *)epi.gate, epi.accum, relu,
-                           is_grad, g, tiles_c);
-    else
-        hipLaunchKernelGGL((k_gather_mfma<BP, BC, WP, WC, BK, false>), grid, dim3(NT), smem, s, (const bf16_t *)in,
-                           (const bf16_t *)wt, bias, (bf16_t *)out, (const bf16_t *)epi.gate, epi.accum, relu,
-                           is_grad, g, tiles_c);
+#define GATHER_LAUNCH(S1_, TI_)                                                                                   \
+    do {                                                                                                          \
+        auto kfn = k_gather_mfma<BP, BC, WP, WC, BK, STAGES, S1_, TI_>;                                           \
+        static bool attr_set = false;                                                                             \
+        if (!attr_set && smem > 64 * 1024) {                                                                      \
+            hipError_t e = hipFuncSetAttribute((const void *)kfn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem); \
+            if (e != hipSuccess) return e;                                                                        \
+            attr_set = true;                                                                                      \
+        }                                                                                                         \
+        hipLaunchKernelGGL(kfn, grid, dim3(NT), smem, s, (const bf16_t *)in, (const bf16_t *)wt, bias,          \
+                           (bf16_t *)out, (const bf16_t *)epi.gate, epi.accum, relu, is_grad, g, tiles_c, in_bytes, \
+                           wt_bytes);                                                                             \
+    } while (0)
+    const bool taps_inner = g.Ci % BK == 0;
+    if (g.s_in == 1) {
+        if (taps_inner) GATHER_LAUNCH(true, true);
+        else GATHER_LAUNCH(true, false);
+    } else {
+        if (taps_inner) GATHER_LAUNCH(false, true);
+        else GATHER_LAUNCH(false, false);
+    }
+#undef GATHER_LAUNCH
     return hipGetLastError();
 }
 
@@ -534,8 +578,10 @@ WgradPlan wgrad_plan(const ConvShape &c)
 
 bool conv_gather_mfma_supported(const GatherConv &g)
 {
+    // byte offsets into the operands are 32-bit (buffer addressing)
     return g.Ci % 8 == 0 && g.Co % 8 == 0 && g.Ci >= 8 && g.s_in >= 1 && g.s_out >= 1 &&
-           (long long)g.N * g.Hi * g.Wi * g.Ci < (1ll << 40);
+           (long long)g.N * g.Hi * g.Wi * g.Ci * 2 < (1ll << 31) && (long long)g.Co * g.R * g.S * g.Ci * 2 < (1ll << 31) &&
+           (long long)g.N * g.Ho * g.Wo < (1ll << 31) - 512;
 }
 
 hipError_t conv_gather_mfma(const void *in, const void *wt, const float *bias, void *out, int relu,
@@ -543,8 +589,8 @@ hipError_t conv_gather_mfma(const void *in, const void *wt, const float *bias, v
 {
     if (!conv_gather_mfma_supported(g)) return hipErrorInvalidValue;
     if ((long long)g.N * g.Ho * g.Wo == 0) return hipSuccess;
-    if (g.Co <= 64) return launch_gather<256, 64, 4, 1, 32>(in, wt, bias, out, relu, epi, g, s);
-    return launch_gather<256, 128, 2, 2, 32>(in, wt, bias, out, relu, epi, g, s);
+    if (g.Co <= 64) return launch_gather<256, 64, 4, 1, 32, 3>(in, wt, bias, out, relu, epi, g, s);
+    return launch_gather<256, 128, 2, 2, 32, 3>(in, wt, bias, out, relu, epi, g, s);
 }
 
 bool conv_wgrad_mfma_supported(const ConvShape &c)
