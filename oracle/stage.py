@@ -46,6 +46,7 @@ class OracleStage:
             self.db.append(None if b is None else np.zeros(b.shape))
         self.stash = {}
         self.loss = {}
+        self.trace = None          # set to {} to record, per (mb, layer), the masked output gradient and dx
         self.n_fwd = self.n_bwd = 0
         self.peak_in_flight = 0
 
@@ -124,10 +125,14 @@ class OracleStage:
         def src(t):
             return x if t < 0 else outs[t]
 
+        cur = [None]
+
         def give(t, c):
             if t < 0 and not need_in:
                 return
             c = q(c)
+            if self.trace is not None:
+                self.trace[(mb, cur[0])]["dx"] = c
             G[t] = c if t not in G else q(G[t] + c)
 
         last = len(self.layers) - 1
@@ -139,6 +144,9 @@ class OracleStage:
             k = L["kind"]
             a = src(L["src0"])
             wants = L["src0"] >= 0 or need_in
+            cur[0] = i
+            if self.trace is not None:
+                self.trace[(mb, i)] = {"x": a, "y": outs[i]}
             if k == C.SOFTMAX_XENT:
                 z = a.reshape(a.shape[0], -1)
                 loss, dz = ops.xent_bwd(z, dy_or_labels, self.loss_scale)
@@ -148,6 +156,8 @@ class OracleStage:
             g = G.pop(i)
             if L["fuse_relu"] and k in (C.CONV2D, C.BATCHNORM2D, C.ADD, C.LINEAR):
                 g = ops.relu_bwd(outs[i].reshape(g.shape), g)
+            if self.trace is not None:
+                self.trace[(mb, i)]["g"] = g
             if k == C.CONV2D:
                 ops.conv2d_wgrad(a, g, self.dw[i], self.db[i], L["stride"], L["pad"])
                 if wants:

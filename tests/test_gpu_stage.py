@@ -57,6 +57,25 @@ def test_relu_pool_layers_and_layouts(dtype, layout):
 
 
 @pytest.mark.parametrize("dtype", DT)
+@pytest.mark.parametrize("c,hw,mb", [(16, (12, 10), 3), (6, (9, 7), 2), (64, (224, 224), 2), (512, (28, 28), 8)])
+def test_pool_only_stage_indices_bit_exact(dtype, c, hw, mb):
+    """Identical inputs on both sides: arg-max indices, outputs and routed gradients are exact."""
+    st = single(lambda b: b.pool(src=-1), c, hw, dtype, micro_batch=mb, n_micro=1)
+    xs, gs = stage_io(st)
+    xs[0][:, :, 1, :] = xs[0][:, :, 0, :]                      # plant ties (vertical, horizontal, all four)
+    xs[0][:, :, :, 3] = xs[0][:, :, :, 2]
+    xs[0][0, 0, :4, :4] = 0.0
+    from oracle.stage import OracleStage
+    orc = OracleStage(st, gen.all_params(st))
+    g = GpuStage(st, gen.all_params(st))
+    y_ref, y = orc.forward(0, xs[0]), g.forward(0, xs[0])
+    assert np.array_equal(orc.pool_indices(0, 0), g.pool_indices(0, 0))
+    assert np.array_equal(y_ref, y)
+    assert np.array_equal(orc.backward(0, gs[0]), g.backward(0, gs[0]))
+    g.close()
+
+
+@pytest.mark.parametrize("dtype", DT)
 def test_pool_odd_size_and_vector_tail(dtype):
     st = single(lambda b: (b.conv(6, 6, 1, relu=1, src=-1), b.pool()), 6, (9, 7), dtype)
     compare_minibatch(st, verbose="pool odd")
