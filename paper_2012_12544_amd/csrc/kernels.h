@@ -41,8 +41,9 @@ hipError_t conv_wgrad_direct(int dt, const void *x, const void *dy, float *dw, v
 
 // ---- bf16 MFMA implicit-GEMM convolution (kernels_conv_mfma.hip)
 bool conv_gather_mfma_supported(const GatherConv &g);
+size_t conv_gather_mfma_workspace(const GatherConv &g);      // split-K partials (0 if K is not split)
 hipError_t conv_gather_mfma(const void *in, const void *wt, const float *bias, void *out, int relu,
-                            GradEpi epi, const GatherConv &g, hipStream_t s);
+                            GradEpi epi, const GatherConv &g, void *workspace, hipStream_t s);
 bool conv_wgrad_mfma_supported(const ConvShape &c);
 size_t conv_wgrad_mfma_workspace(const ConvShape &c);
 hipError_t conv_wgrad_mfma(const void *x, const void *dy, float *dw, void *workspace,

@@ -69,7 +69,7 @@ template <int BP, int BC, int WP, int WC, int BK, int STAGES, bool S1, bool TAPS
 __global__ __launch_bounds__(WP *WC * 64, 2) void k_gather_mfma(
     const bf16_t *__restrict__ in, const bf16_t *__restrict__ wt, const float *__restrict__ bias,
     bf16_t *out, const bf16_t *__restrict__ gate, int accum, int relu, int is_grad, GatherConv g,
-    int tiles_c, unsigned in_bytes, unsigned wt_bytes)
+    int tiles_c, unsigned in_bytes, unsigned wt_bytes, float *__restrict__ part, int kt_per_split)
 {
     constexpr int NT = WP * WC * 64, NW = WP * WC;
     constexpr int CPR = BK / 8;              // 16-byte chunks per tile row
@@ -95,6 +95,7 @@ __global__ __launch_bounds__(WP *WC * 64, 2) void k_gather_mfma(
     const int lrow = lane >> 2;
     const int lc = (lane & 3) ^ ((lane >> 4) & 3);       // = c' ^ swz(row); the same for every load
 
+    // split-K: blockIdx.y owns K-tiles [kt0, kt1) and leaves fp32 partial sums in part[split][pixel][co]
     const int bid = xcd_remap(blockIdx.x, gridDim.x);
     const int tile_c = bid % tiles_c, tile_p = bid / tiles_c;
     const int co0 = tile_c * BC;
@@ -137,12 +138,15 @@ __global__ __launch_bounds__(WP *WC * 64, 2) void k_gather_mfma(
     // (kt % RS), taps innermost, so that consecutive tiles re-read almost the same pixels (shifted
     // by one column / one row) and hit in the CU's vector L1.  Otherwise k = (r, s, ci) flattened,
     // ci fastest, and a tile may straddle taps.  Both operands use the same order.
-    int kk = 8 * lc;                                   // flattened k of this lane's chunk (generic order)
+    const int kt0 = part ? blockIdx.y * kt_per_split : 0;
+    const int kt1 = part ? (kt0 + kt_per_split < KT ? kt0 + kt_per_split : KT) : KT;
+    int kk = kt0 * BK + 8 * lc;                        // flattened k of this lane's chunk (generic order)
     int kr = kk / (g.S * g.Ci), ks = (kk / g.Ci) % g.S, kc = kk % g.Ci;
     if (TAPS_INNER) {
-        kr = 0;
-        ks = 0;
-        kc = 8 * lc;                                   // channel offset; tap = (kr, ks)
+        const int tap = kt0 % (g.R * g.S);
+        kr = tap / g.S;
+        ks = tap % g.S;
+        kc = (kt0 / (g.R * g.S)) * BK + 8 * lc;        // channel offset; tap = (kr, ks)
     }
 
     auto issue_tile = [&](int stage) {
@@ -232,7 +236,7 @@ __global__ __launch_bounds__(WP *WC * 64, 2) void k_gather_mfma(
 #pragma unroll
     for (int st = 0; st < STAGES - 1; ++st) issue_tile(st);
     int rd = 0, wr = STAGES - 1;
-    for (int kt = 0; kt < KT; ++kt) {
+    for (int kt = kt0; kt < kt1; ++kt) {
         WAIT_VMCNT((STAGES - 2) * NLOAD);
         __builtin_amdgcn_s_barrier();
         issue_tile(wr);
@@ -242,6 +246,26 @@ __global__ __launch_bounds__(WP *WC * 64, 2) void k_gather_mfma(
     }
     WAIT_VMCNT(0);
     __syncthreads();
+
+    if (part) {
+        // split-K: raw fp32 sums, 4 consecutive channels of one pixel per store; bias, ReLU and the
+        // gradient epilogue are applied by the reduction kernel
+        float *dst = part + (size_t)blockIdx.y * npix * g.Co;
+#pragma unroll
+        for (int a = 0; a < TC; ++a)
+#pragma unroll
+            for (int b = 0; b < TP; ++b) {
+                const int p = pix0 + wp * WT_P + b * 32 + frow;
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int co = co0 + wc * WT_C + a * 32 + 8 * q + 4 * fhalf;
+                    if (p < npix && co < g.Co)
+                        *reinterpret_cast<float4 *>(dst + (size_t)p * g.Co + co) =
+                            make_float4(acc[a][b][4 * q], acc[a][b][4 * q + 1], acc[a][b][4 * q + 2], acc[a][b][4 * q + 3]);
+                }
+            }
+        return;
+    }
 
     // ---- epilogue: one pixel band (the rows of the waves with the same wp) at a time
     const chunk16 zero16 = {0u, 0u, 0u, 0u};
@@ -315,9 +339,64 @@ __global__ __launch_bounds__(WP *WC * 64, 2) void k_gather_mfma(
     }
 }
 
+// out[p][co] = epilogue( sum_split part[split][p][co] + bias[co] ), 8 channels per thread
+__global__ void k_gather_splitk_reduce(const float *__restrict__ part, int splits, size_t total, int Co,
+                                       const float *__restrict__ bias, bf16_t *out,
+                                       const bf16_t *__restrict__ gate, int accum, int relu, int is_grad)
+{
+    size_t i = ((size_t)blockIdx.x * 256 + threadIdx.x) * 8;
+    if (i >= total) return;
+    float v[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) v[j] = 0.0f;
+    for (int k = 0; k < splits; ++k) {
+        float4 a = *reinterpret_cast<const float4 *>(part + (size_t)k * total + i);
+        float4 b = *reinterpret_cast<const float4 *>(part + (size_t)k * total + i + 4);
+        v[0] += a.x; v[1] += a.y; v[2] += a.z; v[3] += a.w;
+        v[4] += b.x; v[5] += b.y; v[6] += b.z; v[7] += b.w;
+    }
+    const int co = (int)(i % Co);
+    vec_t<bf16_t, 8> old, gt, r;
+    if (is_grad && accum) old = *reinterpret_cast<const vec_t<bf16_t, 8> *>(out + i);
+    if (is_grad && gate) gt = *reinterpret_cast<const vec_t<bf16_t, 8> *>(gate + i);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        float x = v[j] + (bias ? bias[co + j] : 0.0f);
+        if (relu) x = fmaxf(x, 0.0f);
+        r.e[j] = is_grad ? grad_out<bf16_t>(x, accum != 0, old.e[j], gate != nullptr, gt.e[j]) : from_f32<bf16_t>(x);
+    }
+    *reinterpret_cast<vec_t<bf16_t, 8> *>(out + i) = r;
+}
+
+struct GatherPlan {
+    int bp, bc, splits, kt_per_split;
+};
+
+// Tile shape and split-K factor.  K is split when the output tiles alone cannot occupy the chip
+// (256 CUs x 2 resident blocks), e.g. the linear layers (one pixel tile) and the 14x14 layers.
+GatherPlan gather_plan(const GatherConv &g)
+{
+    GatherPlan p;
+    const long long npix = (long long)g.N * g.Ho * g.Wo;
+    p.bp = npix <= 64 ? 64 : 256;
+    p.bc = g.Co <= 64 ? 64 : 128;
+    if (p.bp == 64) p.bc = 128;
+    const long long tiles = ((npix + p.bp - 1) / p.bp) * ((g.Co + p.bc - 1) / p.bc);
+    const int BK = 32;
+    const int KT = g.Ci % BK == 0 ? (g.Ci / BK) * g.R * g.S : (g.R * g.S * g.Ci + BK - 1) / BK;
+    long long want = tiles >= 384 ? 1 : (512 + tiles - 1) / tiles;
+    long long most = KT / 16;                       // at least 16 K-tiles per split
+    if (want > most) want = most;
+    if (want > 32) want = 32;
+    if (want < 1) want = 1;
+    p.kt_per_split = (int)((KT + want - 1) / want);
+    p.splits = (KT + p.kt_per_split - 1) / p.kt_per_split;
+    return p;
+}
+
 template <int BP, int BC, int WP, int WC, int BK, int STAGES>
 hipError_t launch_gather(const void *in, const void *wt, const float *bias, void *out, int relu, GradEpi epi,
-                         const GatherConv &g, hipStream_t s)
+                         const GatherConv &g, const GatherPlan &plan, void *workspace, hipStream_t s)
 {
     constexpr int NT = WP * WC * 64;
     constexpr size_t main_bytes = (size_t)STAGES * (BP + BC) * BK * 2;
@@ -329,7 +408,8 @@ hipError_t launch_gather(const void *in, const void *wt, const float *bias, void
     const int is_grad = (epi.gate != nullptr || epi.accum) ? 1 : 0;
     const unsigned in_bytes = (unsigned)((size_t)g.N * g.Hi * g.Wi * g.Ci * 2);
     const unsigned wt_bytes = (unsigned)((size_t)g.Co * g.R * g.S * g.Ci * 2);
-    dim3 grid((unsigned)(tiles_p * tiles_c));
+    float *part = plan.splits > 1 ? (float *)workspace : nullptr;
+    dim3 grid((unsigned)(tiles_p * tiles_c), (unsigned)plan.splits);
 #define GATHER_LAUNCH(S1_, TI_)                                                                                   \
     do {                                                                                                          \
         auto kfn = k_gather_mfma<BP, BC, WP, WC, BK, STAGES, S1_, TI_>;                                           \
@@ -341,7 +421,7 @@ hipError_t launch_gather(const void *in, const void *wt, const float *bias, void
         }                                                                                                         \
         hipLaunchKernelGGL(kfn, grid, dim3(NT), smem, s, (const bf16_t *)in, (const bf16_t *)wt, bias,          \
                            (bf16_t *)out, (const bf16_t *)epi.gate, epi.accum, relu, is_grad, g, tiles_c, in_bytes, \
-                           wt_bytes);                                                                             \
+                           wt_bytes, part, plan.kt_per_split);                                                    \
     } while (0)
     const bool taps_inner = g.Ci % BK == 0;
     if (g.s_in == 1) {
@@ -352,6 +432,12 @@ hipError_t launch_gather(const void *in, const void *wt, const float *bias, void
         else GATHER_LAUNCH(false, false);
     }
 #undef GATHER_LAUNCH
+    if (part) {
+        const size_t total = (size_t)npix * g.Co;
+        hipLaunchKernelGGL(k_gather_splitk_reduce, dim3((unsigned)((total / 8 + 255) / 256)), dim3(256), 0, s, part,
+                           plan.splits, total, g.Co, bias, (bf16_t *)out, (const bf16_t *)epi.gate, epi.accum, relu,
+                           is_grad);
+    }
     return hipGetLastError();
 }
 
@@ -387,8 +473,8 @@ __device__ __forceinline__ bf16x8_t tr_frag(const uint16_t *tile, int ch0, int k
 template <int BKO, int BCI, int WKO, int WCI, int BKP>
 __global__ __launch_bounds__(WKO *WCI * 64, 2) void k_wgrad_mfma(const bf16_t *__restrict__ x,
                                                                   const bf16_t *__restrict__ dy,
-                                                                  float *__restrict__ part, ConvShape c,
-                                                                  int tiles_n, int pix_per_split)
+                                                                  float *part, ConvShape c, int tiles_n,
+                                                                  int pix_per_split, int add_to_dst)
 {
     constexpr int NT = WKO * WCI * 64;
     constexpr int SA = WgLds<BKO>::STRIDE, SB = WgLds<BCI>::STRIDE;
@@ -519,7 +605,10 @@ __global__ __launch_bounds__(WKO *WCI * 64, 2) void k_wgrad_mfma(const bf16_t *_
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
                 const int ko = ko0 + wk * WT_KO + a * 32 + 8 * (v >> 2) + 4 * half + (v & 3);
-                if (ko < c.K && n < Ntot) dst[(size_t)ko * Ntot + n] = acc[a][b][v];
+                if (ko < c.K && n < Ntot) {
+                    float *d = dst + (size_t)ko * Ntot + n;
+                    *d = add_to_dst ? *d + acc[a][b][v] : acc[a][b][v];     // single split: straight into dw
+                }
             }
         }
 }
@@ -584,13 +673,21 @@ bool conv_gather_mfma_supported(const GatherConv &g)
            (long long)g.N * g.Ho * g.Wo < (1ll << 31) - 512;
 }
 
+size_t conv_gather_mfma_workspace(const GatherConv &g)
+{
+    GatherPlan p = gather_plan(g);
+    return p.splits > 1 ? (size_t)p.splits * g.N * g.Ho * g.Wo * g.Co * sizeof(float) : 0;
+}
+
 hipError_t conv_gather_mfma(const void *in, const void *wt, const float *bias, void *out, int relu,
-                            GradEpi epi, const GatherConv &g, hipStream_t s)
+                            GradEpi epi, const GatherConv &g, void *workspace, hipStream_t s)
 {
     if (!conv_gather_mfma_supported(g)) return hipErrorInvalidValue;
     if ((long long)g.N * g.Ho * g.Wo == 0) return hipSuccess;
-    if (g.Co <= 64) return launch_gather<256, 64, 4, 1, 32, 3>(in, wt, bias, out, relu, epi, g, s);
-    return launch_gather<256, 128, 2, 2, 32, 3>(in, wt, bias, out, relu, epi, g, s);
+    const GatherPlan p = gather_plan(g);
+    if (p.bp == 64) return launch_gather<64, 128, 1, 4, 32, 3>(in, wt, bias, out, relu, epi, g, p, workspace, s);
+    if (p.bc == 64) return launch_gather<256, 64, 4, 1, 32, 3>(in, wt, bias, out, relu, epi, g, p, workspace, s);
+    return launch_gather<256, 128, 2, 2, 32, 3>(in, wt, bias, out, relu, epi, g, p, workspace, s);
 }
 
 bool conv_wgrad_mfma_supported(const ConvShape &c)
@@ -601,7 +698,7 @@ bool conv_wgrad_mfma_supported(const ConvShape &c)
 size_t conv_wgrad_mfma_workspace(const ConvShape &c)
 {
     WgradPlan p = wgrad_plan(c);
-    return (size_t)p.splits * c.K * c.R * c.S * c.C * sizeof(float);
+    return p.splits == 1 ? 0 : (size_t)p.splits * c.K * c.R * c.S * c.C * sizeof(float);
 }
 
 hipError_t conv_wgrad_mfma(const void *x, const void *dy, float *dw, void *workspace, const ConvShape &c,
@@ -611,10 +708,11 @@ hipError_t conv_wgrad_mfma(const void *x, const void *dy, float *dw, void *works
     if ((long long)c.N * c.P * c.Q == 0) return hipSuccess;
     WgradPlan p = wgrad_plan(c);
     dim3 grid((unsigned)(p.tiles_ko * p.tiles_n), (unsigned)p.splits);
-    float *part = (float *)workspace;
+    const int direct = p.splits == 1;
+    float *part = direct ? dw : (float *)workspace;
 #define WG_LAUNCH(BKO_, BCI_, WKO_, WCI_)                                                                  \
     hipLaunchKernelGGL((k_wgrad_mfma<BKO_, BCI_, WKO_, WCI_, 32>), grid, dim3(WKO_ * WCI_ * 64), 0, s,      \
-                       (const bf16_t *)x, (const bf16_t *)dy, part, c, p.tiles_n, p.pix_per_split)
+                       (const bf16_t *)x, (const bf16_t *)dy, part, c, p.tiles_n, p.pix_per_split, direct)
     if (p.bko == 128 && p.bci == 128)
         WG_LAUNCH(128, 128, 2, 2);
     else if (p.bko == 64 && p.bci == 128)
@@ -625,8 +723,9 @@ hipError_t conv_wgrad_mfma(const void *x, const void *dy, float *dw, void *works
         WG_LAUNCH(64, 64, 2, 2);
 #undef WG_LAUNCH
     size_t total = (size_t)c.K * c.R * c.S * c.C;
-    hipLaunchKernelGGL(k_splitk_reduce, dim3((unsigned)((total / 4 + 255) / 256 + 1)), dim3(256), 0, s, part, dw,
-                       total, p.splits);
+    if (!direct)
+        hipLaunchKernelGGL(k_splitk_reduce, dim3((unsigned)((total / 4 + 255) / 256 + 1)), dim3(256), 0, s, part,
+                           dw, total, p.splits);
     return hipGetLastError();
 }
 

@@ -306,23 +306,43 @@ __global__ void k_bn_stat_final(const float *__restrict__ part, int chunks, int 
     stats[C + c] = (float)(1.0 / sqrt(var + (double)eps));
 }
 
+// Normalisation pass.  A thread keeps ONE channel group for its whole life (its V means, inverse
+// deviations, gammas and betas sit in registers) and walks down the rows, so that per 16 bytes
+// of activations there is one 16-byte load and one 16-byte store and nothing else.
+constexpr int BN_ROWS_PER_THREAD = 8;
+
 template <class T, int V>
 __global__ void k_bn_apply(const T *__restrict__ x, const float *__restrict__ gamma,
                            const float *__restrict__ beta, const float *__restrict__ stats,
-                           T *__restrict__ y, int relu, size_t nvec, int CV, int C)
+                           T *__restrict__ y, int relu, int rows, int C, ColPlan p)
 {
-    size_t i = (size_t)blockIdx.x * TPB + threadIdx.x;
-    if (i >= nvec) return;
-    int c0 = (int)(i % CV) * V;
-    vec_t<T, V> a = reinterpret_cast<const vec_t<T, V> *>(x)[i], r;
+    const int cx = threadIdx.x % p.CGB, ry = threadIdx.x / p.CGB;
+    const int cg = blockIdx.x * p.CGB + cx;
+    if (ry >= p.RY || cg >= p.CV) return;
+    float mu[V], inv[V], ga[V], be[V];
 #pragma unroll
     for (int j = 0; j < V; ++j) {
-        float xh = (to_f32(a.e[j]) - stats[c0 + j]) * stats[C + c0 + j];
-        float v = gamma[c0 + j] * xh + beta[c0 + j];
-        if (relu) v = fmaxf(v, 0.0f);
-        r.e[j] = from_f32<T>(v);
+        mu[j] = stats[cg * V + j];
+        inv[j] = stats[C + cg * V + j];
+        ga[j] = gamma[cg * V + j];
+        be[j] = beta[cg * V + j];
     }
-    reinterpret_cast<vec_t<T, V> *>(y)[i] = r;
+    const vec_t<T, V> *xv = reinterpret_cast<const vec_t<T, V> *>(x);
+    vec_t<T, V> *yv = reinterpret_cast<vec_t<T, V> *>(y);
+    const int r0 = blockIdx.y * (p.RY * BN_ROWS_PER_THREAD);
+    int r1 = r0 + p.RY * BN_ROWS_PER_THREAD;
+    if (r1 > rows) r1 = rows;
+    for (int r = r0 + ry; r < r1; r += p.RY) {
+        vec_t<T, V> a = xv[(size_t)r * p.CV + cg], o;
+#pragma unroll
+        for (int j = 0; j < V; ++j) {
+            float xh = (to_f32(a.e[j]) - mu[j]) * inv[j];
+            float v = ga[j] * xh + be[j];
+            if (relu) v = fmaxf(v, 0.0f);
+            o.e[j] = from_f32<T>(v);
+        }
+        yv[(size_t)r * p.CV + cg] = o;
+    }
 }
 
 template <class T, int V>
@@ -331,13 +351,21 @@ __global__ void k_bn_bwd_partial(const T *__restrict__ x, const T *__restrict__ 
 {
     const vec_t<T, V> *xv = reinterpret_cast<const vec_t<T, V> *>(x);
     const vec_t<T, V> *gv = reinterpret_cast<const vec_t<T, V> *>(dy);
+    int cg0 = blockIdx.x * p.CGB + threadIdx.x % p.CGB;
+    if (cg0 >= p.CV) cg0 = p.CV - 1;
+    float mu[V], inv[V];
+#pragma unroll
+    for (int j = 0; j < V; ++j) {
+        mu[j] = stats[cg0 * V + j];
+        inv[j] = stats[C + cg0 * V + j];
+    }
     auto f = [&](int r, int cg, float(&v)[2][V]) {
         vec_t<T, V> a = xv[(size_t)r * p.CV + cg];
         vec_t<T, V> g = gv[(size_t)r * p.CV + cg];
 #pragma unroll
         for (int j = 0; j < V; ++j) {
             float gg = to_f32(g.e[j]);
-            float xh = (to_f32(a.e[j]) - stats[cg * V + j]) * stats[C + cg * V + j];
+            float xh = (to_f32(a.e[j]) - mu[j]) * inv[j];
             v[0][j] = gg;
             v[1][j] = gg * xh;
         }
@@ -362,25 +390,40 @@ template <class T, int V>
 __global__ void k_bn_bwd_apply(const T *__restrict__ x, const T *__restrict__ dy,
                                const float *__restrict__ gamma, const float *__restrict__ stats,
                                const float *__restrict__ sums, T *dx, const T *__restrict__ gate,
-                               int accum, float inv_m, size_t nvec, int CV, int C)
+                               int accum, float inv_m, int rows, int C, ColPlan p)
 {
-    size_t i = (size_t)blockIdx.x * TPB + threadIdx.x;
-    if (i >= nvec) return;
-    int c0 = (int)(i % CV) * V;
-    vec_t<T, V> a = reinterpret_cast<const vec_t<T, V> *>(x)[i];
-    vec_t<T, V> g = reinterpret_cast<const vec_t<T, V> *>(dy)[i];
-    vec_t<T, V> old, gt, r;
-    if (accum) old = reinterpret_cast<const vec_t<T, V> *>(dx)[i];
-    if (gate) gt = reinterpret_cast<const vec_t<T, V> *>(gate)[i];
+    const int cx = threadIdx.x % p.CGB, ry = threadIdx.x / p.CGB;
+    const int cg = blockIdx.x * p.CGB + cx;
+    if (ry >= p.RY || cg >= p.CV) return;
+    float mu[V], inv[V], gi[V], m1[V], m2[V];          // mean, 1/std, gamma/std, sum(dy)/m, sum(dy*xhat)/m
 #pragma unroll
     for (int j = 0; j < V; ++j) {
-        int c = c0 + j;
-        float inv = stats[C + c];
-        float xh = (to_f32(a.e[j]) - stats[c]) * inv;
-        float v = gamma[c] * inv * (to_f32(g.e[j]) - sums[c] * inv_m - xh * sums[C + c] * inv_m);
-        r.e[j] = grad_out<T>(v, accum != 0, old.e[j], gate != nullptr, gt.e[j]);
+        mu[j] = stats[cg * V + j];
+        inv[j] = stats[C + cg * V + j];
+        gi[j] = gamma[cg * V + j] * inv[j];
+        m1[j] = sums[cg * V + j] * inv_m;
+        m2[j] = sums[C + cg * V + j] * inv_m;
     }
-    reinterpret_cast<vec_t<T, V> *>(dx)[i] = r;
+    const vec_t<T, V> *xv = reinterpret_cast<const vec_t<T, V> *>(x);
+    const vec_t<T, V> *gv = reinterpret_cast<const vec_t<T, V> *>(dy);
+    const vec_t<T, V> *tv = reinterpret_cast<const vec_t<T, V> *>(gate);
+    vec_t<T, V> *dv = reinterpret_cast<vec_t<T, V> *>(dx);
+    const int r0 = blockIdx.y * (p.RY * BN_ROWS_PER_THREAD);
+    int r1 = r0 + p.RY * BN_ROWS_PER_THREAD;
+    if (r1 > rows) r1 = rows;
+    for (int r = r0 + ry; r < r1; r += p.RY) {
+        const size_t i = (size_t)r * p.CV + cg;
+        vec_t<T, V> a = xv[i], g = gv[i], old, gt, o;
+        if (accum) old = dv[i];
+        if (gate) gt = tv[i];
+#pragma unroll
+        for (int j = 0; j < V; ++j) {
+            float xh = (to_f32(a.e[j]) - mu[j]) * inv[j];
+            float v = gi[j] * (to_f32(g.e[j]) - m1[j] - xh * m2[j]);
+            o.e[j] = grad_out<T>(v, accum != 0, old.e[j], gate != nullptr, gt.e[j]);
+        }
+        dv[i] = o;
+    }
 }
 
 // ------------------------------------------------------------------ softmax cross-entropy
@@ -710,9 +753,9 @@ hipError_t bn_fwd(int dt, const void *x, const float *gamma, const float *beta, 
                            rows, C, p, part);
         hipLaunchKernelGGL(k_bn_stat_final, dim3(final_blocks(C)), dim3(TPB), 0, s, part, p.chunks, C, rows,
                            eps, stats);
-        size_t nv = (size_t)rows * C / V;
-        hipLaunchKernelGGL((k_bn_apply<T, V>), dim3(blocks_for(nv)), dim3(TPB), 0, s, (const T *)x, gamma,
-                           beta, stats, (T *)y, relu, nv, C / V, C);
+        const int rpb = p.RY * BN_ROWS_PER_THREAD;
+        hipLaunchKernelGGL((k_bn_apply<T, V>), dim3(p.gx, (rows + rpb - 1) / rpb), dim3(TPB), 0, s, (const T *)x,
+                           gamma, beta, stats, (T *)y, relu, rows, C, p);
     });
     return hipGetLastError();
 }
@@ -733,10 +776,10 @@ hipError_t bn_bwd(int dt, const void *x, const void *dy, const float *gamma, con
         hipLaunchKernelGGL(k_bn_bwd_final, dim3(final_blocks(C)), dim3(TPB), 0, s, part, p.chunks, C, sums,
                            dgamma, dbeta);
         if (dx) {
-            size_t nv = (size_t)rows * C / V;
-            hipLaunchKernelGGL((k_bn_bwd_apply<T, V>), dim3(blocks_for(nv)), dim3(TPB), 0, s, (const T *)x,
-                               (const T *)dy, gamma, stats, sums, (T *)dx, (const T *)epi.gate, epi.accum,
-                               1.0f / (float)rows, nv, C / V, C);
+            const int rpb = p.RY * BN_ROWS_PER_THREAD;
+            hipLaunchKernelGGL((k_bn_bwd_apply<T, V>), dim3(p.gx, (rows + rpb - 1) / rpb), dim3(TPB), 0, s,
+                               (const T *)x, (const T *)dy, gamma, stats, sums, (T *)dx, (const T *)epi.gate,
+                               epi.accum, 1.0f / (float)rows, rows, C, p);
         }
     });
     return hipGetLastError();

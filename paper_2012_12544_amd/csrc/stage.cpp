@@ -303,7 +303,7 @@ int layer_forward(bapipe_stage *st, int li, const FwdCtx &c)
         const bool mf = use_mfma_gather(st, g);
         const bool tp = st->tap_begin(mf ? BAPIPE_KC_CONV_GATHER_MFMA : BAPIPE_KC_CONV_DIRECT);
         if (mf)
-            HIPCHK(conv_gather_mfma(a, L.w_work, L.bias, o, L.d.fuse_relu, none, g, s));
+            HIPCHK(conv_gather_mfma(a, L.w_work, L.bias, o, L.d.fuse_relu, none, g, st->work, s));
         else
             HIPCHK(conv_gather_direct(dt, a, L.w_work, L.bias, o, L.d.fuse_relu, none, g, s));
         st->tap_end(tp, conv_flop(g, L.d.cin), 0.0);
@@ -413,7 +413,7 @@ int layer_backward(bapipe_stage *st, int li, BwdCtx &c)
             const bool mf = use_mfma_gather(st, dg);
             const bool tp = st->tap_begin(mf ? BAPIPE_KC_CONV_GATHER_MFMA : BAPIPE_KC_CONV_DIRECT);
             if (mf)
-                HIPCHK(conv_gather_mfma(g, L.w_t, nullptr, dx, 0, e, dg, s));
+                HIPCHK(conv_gather_mfma(g, L.w_t, nullptr, dx, 0, e, dg, st->work, s));
             else
                 HIPCHK(conv_gather_direct(dt, g, L.w_t, nullptr, dx, 0, e, dg, s));
             st->tap_end(tp, flop, 0.0);
@@ -720,6 +720,9 @@ int bapipe_stage_create(const bapipe_layer_desc_t *layers, int n_layers, int mic
             work = w > work ? w : work;
             w = colsum_workspace(cs.N * cs.P * cs.Q, cs.K);
             work = w > work ? w : work;
+            GatherConv fg = fwd_geom(st, L), dg = dgrad_geom(st, L);
+            if (use_mfma_gather(st, fg)) { w = conv_gather_mfma_workspace(fg); work = w > work ? w : work; }
+            if (use_mfma_gather(st, dg)) { w = conv_gather_mfma_workspace(dg); work = w > work ? w : work; }
         }
     }
     st->slot_bytes = align_up(slot);
