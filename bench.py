@@ -66,6 +66,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample", type=int, default=0)
     ap.add_argument("--profile-layers", action="store_true", help="also print the per-layer profile (stderr)")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain 1 GiB device copy (reference point for rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     a = ap.parse_args()
     if a.gpus != 1:
         print("bench.py: this build runs one pipeline stage on ONE GPU; --gpus %d is not supported "
@@ -125,6 +127,14 @@ def main():
                 i, C.KIND_NAMES[stage["layers"][i]["kind"]], p["fwd_ms"], p["bwd_ms"], p["weight_bytes"],
                 p["out_feature_bytes"], p["stash_bytes"]), file=sys.stderr)
 
+    if a.calibrate_copy:
+        src = torch.ones(1 << 28, dtype=torch.float32, device=dev)      # 1 GiB read + 1 GiB written
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        torch.mul(src, 1.0, out=dst)                                     # one element-wise read+write pass
+        torch.cuda.synchronize()
+        del src, dst
+
     torch.cuda.synchronize()
     for _ in range(a.warmup):
         step()
@@ -172,8 +182,15 @@ def main():
     else:
         ach = r["bytes"] / (r["total_ms"] * 1e-3) / 1e9 if r["total_ms"] > 0 else 0.0
         bound, unit, peak = "hbm", "GB/s", PEAK_HBM_GBS
+    # HBM bytes per launch of this class as measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
+    # (profiles/<workload>_traffic.json, written by paper_2012_12544_amd.profile_summary); null if absent
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "%s_traffic.json" % a.workload)
+    if os.path.exists(tpath):
+        traffic = json.load(open(tpath)).get("per_class", {}).get(tap)
     roof = dict(bound=bound, kernel_class=tap, achieved=round(ach, 2), peak=peak, unit=unit,
-                frac=round(ach / peak, 4), traffic=None, launches=int(r["launches"]),
+                frac=round(ach / peak, 4), traffic=None if traffic is None else round(traffic),
+                launches=int(r["launches"]),
                 avg_launch_ms=round(r["total_ms"] / max(1, r["launches"]), 5),
                 share_of_step=round(r["total_ms"] / ms, 4))
 
