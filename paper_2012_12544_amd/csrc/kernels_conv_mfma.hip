@@ -444,24 +444,31 @@ hipError_t launch_gather(const void *in, const void *wt, const float *bias, void
 // ------------------------------------------------------------------------------------------
 // wgrad
 // ------------------------------------------------------------------------------------------
-// LDS tile [BKP pixels][CH channels], row stride CH + 32 elements (CH*2 + 64 bytes): the four
-// rows touched by one 16-lane group of a transposing read then fall into disjoint banks.
-template <int CH> struct WgLds {
-    static constexpr int STRIDE = CH + 32;
-};
+// LDS tile [32 pixels][CH channels], rows unpadded (they are filled by buffer_load ... lds, whose
+// lanes land in consecutive 16-byte slots).  One 16-lane group of a transposing read touches 4
+// consecutive pixel rows x 32 bytes; the 32-byte pair index inside a row is XORed with a function of
+// the row so that the 32 lanes served together hit 8 different 32-byte bank groups.
+template <int CH> __device__ __forceinline__ int wg_swz(int row)
+{
+    constexpr int PPR = CH / 16;                      // 32-byte pairs per row
+    constexpr int RPS = PPR >= 8 ? 1 : 8 / PPR;       // rows per 256-byte bank sweep
+    return (2 * ((row / RPS) & 3)) & (PPR - 1);
+}
 
 // fragment for v_mfma_f32_32x32x16_bf16 out of a [pixel][channel] LDS tile:
 // lane -> channel ch0 + (lane & 31), pixels k0 + 8*(lane >> 5) .. +7  (two transposing reads)
-template <int STRIDE>
+template <int CH>
 __device__ __forceinline__ bf16x8_t tr_frag(const uint16_t *tile, int ch0, int k0, int lane)
 {
     const int blk = lane >> 4, sl = lane & 15;
     const int row = k0 + 8 * (blk >> 1) + (sl >> 2);
     const int col = ch0 + 16 * (blk & 1) + 4 * (sl & 3);
-    const uint16_t *p = tile + row * STRIDE + col;
+    const int chunk = col >> 3;
+    const int sw = (((chunk >> 1) ^ wg_swz<CH>(row)) << 1) | (chunk & 1);
+    const uint16_t *p = tile + row * CH + (sw << 3) + (col & 7);
     typedef __attribute__((address_space(3))) s16x4_t lds_v4;
     s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4 *)(p));
-    s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4 *)(p + 4 * STRIDE));
+    s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4 *)(p + 4 * CH));     // rows +4: same swizzle
     typedef short s16x8_t __attribute__((ext_vector_type(8)));
     s16x8_t both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
     return __builtin_bit_cast(bf16x8_t, both);
@@ -469,45 +476,63 @@ __device__ __forceinline__ bf16x8_t tr_frag(const uint16_t *tile, int ch0, int k
 
 // The GEMM's N index is the flattened (r, s, c) filter position n = (r*S + s)*C + c, so a tile
 // of BCI columns covers one tap (or part of it) when C >= BCI and several taps when C is small.
-// grid: x = (ko tile, n tile) ; y = split over pixel chunks
-template <int BKO, int BCI, int WKO, int WCI, int BKP>
+// grid: x = (ko tile, n tile) ; y = split over pixel chunks.  Same HBM -> LDS ring as the gather
+// kernel: STAGES tiles of 32 pixels, requests issued STAGES-1 tiles ahead, hand-placed vmcnt waits.
+template <int BKO, int BCI, int WKO, int WCI, int STAGES>
 __global__ __launch_bounds__(WKO *WCI * 64, 2) void k_wgrad_mfma(const bf16_t *__restrict__ x,
                                                                   const bf16_t *__restrict__ dy,
                                                                   float *part, ConvShape c, int tiles_n,
-                                                                  int pix_per_split, int add_to_dst)
+                                                                  int pix_per_split, int add_to_dst,
+                                                                  unsigned x_bytes, unsigned dy_bytes)
 {
-    constexpr int NT = WKO * WCI * 64;
-    constexpr int SA = WgLds<BKO>::STRIDE, SB = WgLds<BCI>::STRIDE;
-    constexpr int ACH = BKO / 8, BCH = BCI / 8;       // 16-byte chunks per pixel row
-    constexpr int APASS = (BKP * ACH + NT - 1) / NT, BPASS = (BKP * BCH + NT - 1) / NT;
+    constexpr int BKP = 32;
+    constexpr int NW = WKO * WCI;
+    constexpr int CPA = BKO / 8, CPB = BCI / 8;          // 16-byte chunks per tile row
+    constexpr int AL = (BKP * CPA / 64) / NW, BL = (BKP * CPB / 64) / NW;   // wave-wide loads per wave and tile
     constexpr int WT_KO = BKO / WKO, WT_CI = BCI / WCI;
     constexpr int TA = WT_KO / 32, TB = WT_CI / 32;
-    static_assert((BKP * ACH) % NT == 0 && (BKP * BCH) % NT == 0, "tile/thread mismatch");
+    constexpr int STAGE_ELEMS = BKP * (BKO + BCI);
+    constexpr unsigned OOB = 0x80000000u;
+    static_assert(AL >= 1 && BL >= 1 && (BKP * CPA / 64) % NW == 0 && (BKP * CPB / 64) % NW == 0, "tile/thread mismatch");
 
-    __shared__ __align__(16) uint16_t sA[2][BKP * SA];
-    __shared__ __align__(16) uint16_t sB[2][BKP * SB];
+    extern __shared__ __align__(16) unsigned char smem[];
+    uint16_t *ring = reinterpret_cast<uint16_t *>(smem);         // [STAGES][ A tile | B tile ]
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wk = wave % WKO, wi = wave / WKO;
     const int tn = blockIdx.x % tiles_n, tko = blockIdx.x / tiles_n;
     const int ko0 = tko * BKO, n0 = tn * BCI;
     const int Ntot = c.R * c.S * c.C;
-    const long long npix = (long long)c.N * c.P * c.Q;
-    const long long p_begin = (long long)blockIdx.y * pix_per_split;
-    long long p_end = p_begin + pix_per_split;
-    if (p_end > npix) p_end = npix;
-    const int KT = (int)((p_end - p_begin + BKP - 1) / BKP);
+    const int npix = c.N * c.P * c.Q;
+    const int p_begin = blockIdx.y * pix_per_split;
+    const int p_end = p_begin + pix_per_split < npix ? p_begin + pix_per_split : npix;
+    const int KT = (p_end - p_begin + BKP - 1) / BKP;
 
-    chunk16 ra[APASS], rb[BPASS];
-    const chunk16 zero16 = {0u, 0u, 0u, 0u};
+    __amdgpu_buffer_rsrc_t xrsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t *>(x), 0, (int)x_bytes, 0x00020000);
+    __amdgpu_buffer_rsrc_t grsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t *>(dy), 0, (int)dy_bytes, 0x00020000);
 
-    // filter position of the B-tile chunk column(s) this thread loads (fixed over the K loop)
-    int br[BPASS], bs[BPASS], bc[BPASS];
+    // ---- A (dy) loads: lane fills slot (row, c') of wave-load q = i*NW + wave and fetches chunk c
+    int ap[AL];                  // pixel of the lane's row in the current tile
+    int akoff[AL];               // element offset of its chunk inside a dy row, or -1
 #pragma unroll
-    for (int i = 0; i < BPASS; ++i) {
-        int n = n0 + ((tid + i * NT) % BCH) * 8;
+    for (int i = 0; i < AL; ++i) {
+        const int slot = (i * NW + wave) * 64 + lane;
+        const int row = slot / CPA, cs = slot % CPA;
+        const int ch = ((((cs >> 1) ^ wg_swz<BKO>(row)) << 1) | (cs & 1));
+        ap[i] = p_begin + row;
+        akoff[i] = ko0 + ch * 8 < c.K ? ko0 + ch * 8 : -1;
+    }
+    // ---- B (x) loads: filter position of the lane's chunk column (fixed) and its pixel (advancing)
+    int bp[BL], bq[BL], bpp[BL], bn[BL], br[BL], bs[BL], bc[BL];
+#pragma unroll
+    for (int i = 0; i < BL; ++i) {
+        const int slot = (i * NW + wave) * 64 + lane;
+        const int row = slot / CPB, cs = slot % CPB;
+        const int ch = ((((cs >> 1) ^ wg_swz<BCI>(row)) << 1) | (cs & 1));
+        const int n = n0 + ch * 8;
         if (n < Ntot) {
-            int tap = n / c.C;
+            const int tap = n / c.C;
             bc[i] = n % c.C;
             br[i] = tap / c.S - c.pad;
             bs[i] = tap % c.S - c.pad;
@@ -515,47 +540,36 @@ __global__ __launch_bounds__(WKO *WCI * 64, 2) void k_wgrad_mfma(const bf16_t *_
             bc[i] = -1;
             br[i] = bs[i] = 0;
         }
+        bp[i] = p_begin + row;
+        bq[i] = bp[i] % c.Q;
+        const int t = bp[i] / c.Q;
+        bpp[i] = t % c.P;
+        bn[i] = t / c.P;
     }
 
-    auto load_tile = [&](int kt) {
-        const long long pt = p_begin + (long long)kt * BKP;
+    auto issue_tile = [&](int stage) {
+        uint16_t *sa = ring + stage * STAGE_ELEMS, *sb = sa + BKP * BKO;
 #pragma unroll
-        for (int i = 0; i < APASS; ++i) {
-            int u = tid + i * NT;
-            int row = u / ACH, ch = u % ACH;
-            long long p = pt + row;
-            int ko = ko0 + ch * 8;
-            ra[i] = (p < p_end && ko < c.K) ? *reinterpret_cast<const chunk16 *>(dy + (size_t)p * c.K + ko) : zero16;
+        for (int i = 0; i < AL; ++i) {
+            unsigned vo = (ap[i] < p_end && akoff[i] >= 0) ? ((unsigned)ap[i] * (unsigned)c.K + (unsigned)akoff[i]) * 2u : OOB;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(grsrc, (lds_void_t *)(sa + (i * NW + wave) * 512), 16, (int)vo, 0, 0, 0);
+            ap[i] += BKP;
         }
 #pragma unroll
-        for (int i = 0; i < BPASS; ++i) {
-            int u = tid + i * NT;
-            int row = u / BCH;
-            long long p = pt + row;
-            bool ok = p < p_end && bc[i] >= 0;
-            size_t off = 0;
-            if (ok) {
-                int q = (int)(p % c.Q);
-                long long t = p / c.Q;
-                int pp = (int)(t % c.P);
-                int n = (int)(t / c.P);
-                int ih = pp * c.stride + br[i], iw = q * c.stride + bs[i];
-                ok = (unsigned)ih < (unsigned)c.H && (unsigned)iw < (unsigned)c.W;
-                off = (((size_t)n * c.H + ih) * c.W + iw) * c.C + bc[i];
+        for (int i = 0; i < BL; ++i) {
+            const int ih = bpp[i] * c.stride + br[i], iw = bq[i] * c.stride + bs[i];
+            const bool ok = bp[i] < p_end && bc[i] >= 0 && (unsigned)ih < (unsigned)c.H && (unsigned)iw < (unsigned)c.W;
+            unsigned vo = ok ? (unsigned)(((bn[i] * c.H + ih) * c.W + iw) * c.C + bc[i]) * 2u : OOB;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(xrsrc, (lds_void_t *)(sb + (i * NW + wave) * 512), 16, (int)vo, 0, 0, 0);
+            bp[i] += BKP;
+            bq[i] += BKP;
+            while (bq[i] >= c.Q) {
+                bq[i] -= c.Q;
+                if (++bpp[i] == c.P) {
+                    bpp[i] = 0;
+                    ++bn[i];
+                }
             }
-            rb[i] = ok ? *reinterpret_cast<const chunk16 *>(x + off) : zero16;
-        }
-    };
-    auto store_tile = [&](int buf) {
-#pragma unroll
-        for (int i = 0; i < APASS; ++i) {
-            int u = tid + i * NT;
-            *reinterpret_cast<chunk16 *>(&sA[buf][(u / ACH) * SA + (u % ACH) * 8]) = ra[i];
-        }
-#pragma unroll
-        for (int i = 0; i < BPASS; ++i) {
-            int u = tid + i * NT;
-            *reinterpret_cast<chunk16 *>(&sB[buf][(u / BCH) * SB + (u % BCH) * 8]) = rb[i];
         }
     };
 
@@ -567,31 +581,36 @@ __global__ __launch_bounds__(WKO *WCI * 64, 2) void k_wgrad_mfma(const bf16_t *_
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.0f;
 
-    if (KT > 0) {
-        load_tile(0);
-        store_tile(0);
-    }
-    __syncthreads();
-    for (int kt = 0; kt < KT; ++kt) {
-        const int buf = kt & 1;
-        const bool more = kt + 1 < KT;
-        if (more) load_tile(kt + 1);
+    auto compute_tile = [&](int stage) {
+        const uint16_t *sa = ring + stage * STAGE_ELEMS, *sb = sa + BKP * BKO;
 #pragma unroll
         for (int k0 = 0; k0 < BKP; k0 += 16) {
             bf16x8_t fa[TA], fb[TB];
 #pragma unroll
-            for (int a = 0; a < TA; ++a) fa[a] = tr_frag<SA>(sA[buf], wk * WT_KO + a * 32, k0, lane);
+            for (int a = 0; a < TA; ++a) fa[a] = tr_frag<BKO>(sa, wk * WT_KO + a * 32, k0, lane);
 #pragma unroll
-            for (int b = 0; b < TB; ++b) fb[b] = tr_frag<SB>(sB[buf], wi * WT_CI + b * 32, k0, lane);
+            for (int b = 0; b < TB; ++b) fb[b] = tr_frag<BCI>(sb, wi * WT_CI + b * 32, k0, lane);
 #pragma unroll
             for (int a = 0; a < TA; ++a)
 #pragma unroll
                 for (int b = 0; b < TB; ++b)
                     acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[a], fb[b], acc[a][b], 0, 0, 0);
         }
-        if (more) store_tile(buf ^ 1);
-        __syncthreads();
+    };
+
+    constexpr int NLOAD = AL + BL;
+#pragma unroll
+    for (int st = 0; st < STAGES - 1; ++st) issue_tile(st);
+    int rd = 0, wr = STAGES - 1;
+    for (int kt = 0; kt < KT; ++kt) {
+        WAIT_VMCNT((STAGES - 2) * NLOAD);
+        __builtin_amdgcn_s_barrier();
+        issue_tile(wr);
+        compute_tile(rd);
+        rd = rd + 1 == STAGES ? 0 : rd + 1;
+        wr = wr + 1 == STAGES ? 0 : wr + 1;
     }
+    WAIT_VMCNT(0);
 
     // partial[split][ko][n]: lanes of a wave write 32 consecutive n (128 bytes)
     const size_t total = (size_t)c.K * Ntot;
@@ -643,8 +662,9 @@ WgradPlan wgrad_plan(const ConvShape &c)
 {
     WgradPlan p;
     const int Ntot = c.R * c.S * c.C;
-    p.bko = c.K > 64 ? 128 : 64;
+    p.bko = c.K > 128 ? 256 : (c.K > 64 ? 128 : 64);
     p.bci = Ntot > 64 ? 128 : 64;
+    if (p.bko == 256 && p.bci == 64) p.bko = 128;
     p.tiles_ko = (c.K + p.bko - 1) / p.bko;
     p.tiles_n = (Ntot + p.bci - 1) / p.bci;
     long long npix = (long long)c.N * c.P * c.Q;
@@ -692,7 +712,9 @@ hipError_t conv_gather_mfma(const void *in, const void *wt, const float *bias, v
 
 bool conv_wgrad_mfma_supported(const ConvShape &c)
 {
-    return c.C % 8 == 0 && c.K % 8 == 0 && c.C >= 8 && c.K >= 8;
+    // 32-bit byte offsets into both operands (buffer addressing)
+    return c.C % 8 == 0 && c.K % 8 == 0 && c.C >= 8 && c.K >= 8 &&
+           (long long)c.N * c.H * c.W * c.C * 2 < (1ll << 31) && (long long)c.N * c.P * c.Q * c.K * 2 < (1ll << 31);
 }
 
 size_t conv_wgrad_mfma_workspace(const ConvShape &c)
@@ -711,9 +733,23 @@ hipError_t conv_wgrad_mfma(const void *x, const void *dy, float *dw, void *works
     const int direct = p.splits == 1;
     float *part = direct ? dw : (float *)workspace;
 #define WG_LAUNCH(BKO_, BCI_, WKO_, WCI_)                                                                  \
-    hipLaunchKernelGGL((k_wgrad_mfma<BKO_, BCI_, WKO_, WCI_, 32>), grid, dim3(WKO_ * WCI_ * 64), 0, s,      \
-                       (const bf16_t *)x, (const bf16_t *)dy, part, c, p.tiles_n, p.pix_per_split, direct)
-    if (p.bko == 128 && p.bci == 128)
+    do {                                                                                                   \
+        constexpr size_t smem = (size_t)3 * 32 * (BKO_ + BCI_) * 2;                                        \
+        auto kfn = k_wgrad_mfma<BKO_, BCI_, WKO_, WCI_, 3>;                                                \
+        static bool attr_set = false;                                                                      \
+        if (!attr_set && smem > 64 * 1024) {                                                               \
+            hipError_t e = hipFuncSetAttribute((const void *)kfn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem); \
+            if (e != hipSuccess) return e;                                                                 \
+            attr_set = true;                                                                               \
+        }                                                                                                  \
+        hipLaunchKernelGGL(kfn, grid, dim3(WKO_ * WCI_ * 64), smem, s, (const bf16_t *)x, (const bf16_t *)dy, part, c, \
+                           p.tiles_n, p.pix_per_split, direct, x_bytes, dy_bytes);                         \
+    } while (0)
+    const unsigned x_bytes = (unsigned)((size_t)c.N * c.H * c.W * c.C * 2);
+    const unsigned dy_bytes = (unsigned)((size_t)c.N * c.P * c.Q * c.K * 2);
+    if (p.bko == 256)
+        WG_LAUNCH(256, 128, 2, 2);
+    else if (p.bko == 128 && p.bci == 128)
         WG_LAUNCH(128, 128, 2, 2);
     else if (p.bko == 64 && p.bci == 128)
         WG_LAUNCH(64, 128, 1, 4);
