@@ -44,6 +44,11 @@ bool conv_gather_mfma_supported(const GatherConv &g);
 size_t conv_gather_mfma_workspace(const GatherConv &g);      // split-K partials (0 if K is not split)
 hipError_t conv_gather_mfma(const void *in, const void *wt, const float *bias, void *out, int relu,
                             GradEpi epi, const GatherConv &g, void *workspace, hipStream_t s);
+// 3x3 / stride 1 / pad 1 with the input halo of a 16x16 output patch resident in LDS
+// (kernels_conv_halo.hip); conv_gather_mfma routes to it when it applies
+bool conv3x3_halo_supported(const GatherConv &g);
+hipError_t conv3x3_halo_mfma(const void *in, const void *wt, const float *bias, void *out, int relu,
+                             GradEpi epi, const GatherConv &g, hipStream_t s);
 bool conv_wgrad_mfma_supported(const ConvShape &c);
 size_t conv_wgrad_mfma_workspace(const ConvShape &c);
 hipError_t conv_wgrad_mfma(const void *x, const void *dy, float *dw, void *workspace,

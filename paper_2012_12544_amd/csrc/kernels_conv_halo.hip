@@ -1,0 +1,271 @@
+// 3x3 / stride 1 / pad 1 convolution (forward, and dgrad through the flipped filter) for feature
+// maps whose sides are multiples of 16: the layers of the first VGG stage (224x224 and 112x112,
+// 64 / 128 channels), where the generic gather kernel is bound by L1/L2 traffic because every
+// input pixel is fetched again for each of the 9 taps.
+//
+// A block owns a 16x16 patch of output pixels x BC output channels.  The 18x18 input halo of one
+// 64-channel slice is brought into LDS ONCE (buffer_load ... lds, zero fill outside the image) and
+// all 9 taps read their shifted views of it: the B fragment of tap (r,s) for patch pixel (y,x) is
+// simply halo pixel (y+r, x+s).  Only the 64x(BC) filter tile of the current tap streams through a
+// small LDS ring.  HBM/L2 traffic per output drops from 9 input reads to (18*18)/(16*16) = 1.27.
+// MFMA mapping, swizzles and the epilogue are those of the gather kernel (A = filter rows, B = pixels,
+// v_mfma_f32_32x32x16_bf16, staging through LDS to 16-byte coalesced rows).
+#include "dev_common.h"
+#include "kernels.h"
+
+namespace bapipe {
+namespace {
+
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef float f32x16_t __attribute__((ext_vector_type(16)));
+typedef uint32_t chunk16 __attribute__((ext_vector_type(4)));
+typedef uint32_t chunk8 __attribute__((ext_vector_type(2)));
+typedef __attribute__((address_space(3))) void lds_void_t;
+
+#define WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(0x0F70 | ((n) & 15) | (((n) >> 4) << 14))
+
+__device__ __forceinline__ bf16x8_t as_frag(chunk16 c) { return __builtin_bit_cast(bf16x8_t, c); }
+
+__device__ __forceinline__ int xcd_remap(int id, int nb)
+{
+    const int x = id & 7, q = nb >> 3, rem = nb & 7;
+    return x * q + (x < rem ? x : rem) + (id >> 3);
+}
+
+// rows of 64 bf16 (8 chunks of 16 bytes): 16 consecutive rows read the same chunk column without
+// bank conflicts when the chunk index is XORed with bits 1..3 of the row
+__device__ __forceinline__ int swz8(int row) { return (row >> 1) & 7; }
+
+constexpr int PATCH = 16, HALO = 18, HPIX = HALO * HALO;       // 324 halo pixels
+constexpr int HL = 11;                                          // halo wave-loads per wave (44 x 64 slots >= 2592)
+constexpr int HALO_ELEMS = HL * 4 * 64 * 8;                     // bf16 elements reserved for the halo tile
+
+template <int BC, int WSTAGES>
+__global__ __launch_bounds__(256, 2) void k_conv3x3_halo(const bf16_t *__restrict__ in, const bf16_t *__restrict__ wt,
+                                                         const float *__restrict__ bias, bf16_t *out,
+                                                         const bf16_t *__restrict__ gate, int accum, int relu,
+                                                         int is_grad, int N, int H, int W, int Ci, int Co,
+                                                         unsigned in_bytes, unsigned wt_bytes)
+{
+    constexpr int NW = 4;
+    constexpr int WLD = BC / 32;               // filter-tile wave-loads per wave (BC rows x 8 chunks / 64 / 4)
+    constexpr int TC = BC / 32, TP = 2;        // wave tile: BC channels x 64 pixels
+    constexpr int WT_ELEMS = BC * 64;
+    constexpr int SROW = BC + 4;
+    constexpr unsigned OOB = 0x80000000u;
+
+    extern __shared__ __align__(16) unsigned char smem[];
+    uint16_t *halo = reinterpret_cast<uint16_t *>(smem);
+    uint16_t *wring = halo + HALO_ELEMS;
+    uint16_t *sO = reinterpret_cast<uint16_t *>(smem);                                   // [256][SROW] (epilogue)
+    float *sBias = reinterpret_cast<float *>(smem + (size_t)(HALO_ELEMS + WSTAGES * WT_ELEMS) * 2);   // [BC]
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int tiles_c = Co / BC, px_tiles = W / PATCH, py_tiles = H / PATCH;
+    const int bid = xcd_remap(blockIdx.x, gridDim.x);
+    const int tile_c = bid % tiles_c;
+    int t = bid / tiles_c;
+    const int X0 = (t % px_tiles) * PATCH;
+    t /= px_tiles;
+    const int Y0 = (t % py_tiles) * PATCH;
+    const int n = t / py_tiles;
+    const int co0 = tile_c * BC;
+    const int NS = Ci / 64, T = NS * 9;
+
+    __amdgpu_buffer_rsrc_t xrsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t *>(in), 0, (int)in_bytes, 0x00020000);
+    __amdgpu_buffer_rsrc_t wrsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t *>(wt), 0, (int)wt_bytes, 0x00020000);
+
+    // halo slots of this lane: slot = hr*8 + c', it fetches chunk c = c' ^ swz8(hr) of halo pixel hr
+    unsigned hoff[HL];
+#pragma unroll
+    for (int i = 0; i < HL; ++i) {
+        const int slot = (i * NW + wave) * 64 + lane;
+        const int hr = slot >> 3, c = (slot & 7) ^ swz8(hr);
+        const int hy = hr / HALO, hx = hr - hy * HALO;
+        const int y = Y0 - 1 + hy, x = X0 - 1 + hx;
+        const bool ok = hr < HPIX && (unsigned)y < (unsigned)H && (unsigned)x < (unsigned)W;
+        hoff[i] = ok ? ((unsigned)((n * H + y) * W + x) * (unsigned)Ci + (unsigned)c * 8u) * 2u : OOB;
+    }
+    unsigned woff[WLD];
+#pragma unroll
+    for (int i = 0; i < WLD; ++i) {
+        const int slot = (i * NW + wave) * 64 + lane;
+        const int row = slot >> 3, c = (slot & 7) ^ swz8(row);
+        woff[i] = ((unsigned)(co0 + row) * 9u * (unsigned)Ci + (unsigned)c * 8u) * 2u;
+    }
+    auto issue_halo = [&](int slice) {
+#pragma unroll
+        for (int i = 0; i < HL; ++i) {
+            unsigned vo = hoff[i] == OOB ? OOB : hoff[i] + (unsigned)slice * 128u;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(xrsrc, (lds_void_t *)(halo + (i * NW + wave) * 512), 16, (int)vo, 0, 0, 0);
+        }
+    };
+    auto issue_w = [&](int step) {              // step = slice*9 + tap
+        const int slice = step / 9, tap = step - slice * 9;
+        uint16_t *dst = wring + (step % WSTAGES) * WT_ELEMS;
+#pragma unroll
+        for (int i = 0; i < WLD; ++i) {
+            unsigned vo = step < T ? woff[i] + ((unsigned)tap * (unsigned)Ci + (unsigned)slice * 64u) * 2u : OOB;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(wrsrc, (lds_void_t *)(dst + (i * NW + wave) * 512), 16, (int)vo, 0, 0, 0);
+        }
+    };
+
+    f32x16_t acc[TC][TP];
+#pragma unroll
+    for (int a = 0; a < TC; ++a)
+#pragma unroll
+        for (int b = 0; b < TP; ++b)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.0f;
+
+    const int frow = lane & 31, fhalf = lane >> 5;
+    const int py = 4 * wave + (frow >> 4), px = frow & 15;       // patch pixel of B tile 0 (tile 1: py + 2)
+
+    if (tid < BC) sBias[tid] = bias ? bias[co0 + tid] : 0.0f;          // read after the main loop's barriers
+    issue_halo(0);
+#pragma unroll
+    for (int st = 0; st < WSTAGES - 1; ++st) issue_w(st);
+    for (int step = 0; step < T; ++step) {
+        const int slice = step / 9, tap = step - slice * 9;
+        if (tap == 0 && step > 0) {
+            __builtin_amdgcn_s_barrier();                        // everyone has left the old halo slice
+            issue_halo(slice);
+            WAIT_VMCNT(0);
+        } else {
+            WAIT_VMCNT((WSTAGES - 2) * WLD);
+        }
+        __builtin_amdgcn_s_barrier();
+        issue_w(step + WSTAGES - 1);
+        const uint16_t *cw = wring + (step % WSTAGES) * WT_ELEMS;
+        const int r = tap / 3, s = tap - r * 3;
+        const int hr0 = (py + r) * HALO + px + s, hr1 = hr0 + 2 * HALO;
+#pragma unroll
+        for (int ks16 = 0; ks16 < 4; ++ks16) {
+            const int ch = 2 * ks16 + fhalf;
+            bf16x8_t fa[TC], fb[TP];
+#pragma unroll
+            for (int a = 0; a < TC; ++a) {
+                const int row = a * 32 + frow;
+                fa[a] = as_frag(*reinterpret_cast<const chunk16 *>(cw + row * 64 + ((ch ^ swz8(row)) << 3)));
+            }
+            fb[0] = as_frag(*reinterpret_cast<const chunk16 *>(halo + hr0 * 64 + ((ch ^ swz8(hr0)) << 3)));
+            fb[1] = as_frag(*reinterpret_cast<const chunk16 *>(halo + hr1 * 64 + ((ch ^ swz8(hr1)) << 3)));
+#pragma unroll
+            for (int a = 0; a < TC; ++a)
+#pragma unroll
+                for (int b = 0; b < TP; ++b)
+                    acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[a], fb[b], acc[a][b], 0, 0, 0);
+        }
+    }
+    WAIT_VMCNT(0);
+    __syncthreads();
+
+    // ---- epilogue: every wave parks its 64 pixels x BC channels in LDS (bf16, bias / ReLU applied),
+    // one barrier, then the block streams the patch out as 16-byte coalesced rows
+    const chunk16 zero16 = {0u, 0u, 0u, 0u};
+#pragma unroll
+    for (int a = 0; a < TC; ++a) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int col = a * 32 + 8 * q + 4 * fhalf;
+            const float4 bv = *reinterpret_cast<const float4 *>(sBias + col);
+#pragma unroll
+            for (int b = 0; b < TP; ++b) {
+                const int prow = wave * 64 + b * 32 + frow;
+                float v0 = acc[a][b][4 * q] + bv.x, v1 = acc[a][b][4 * q + 1] + bv.y;
+                float v2 = acc[a][b][4 * q + 2] + bv.z, v3 = acc[a][b][4 * q + 3] + bv.w;
+                if (relu) {
+                    v0 = fmaxf(v0, 0.0f);
+                    v1 = fmaxf(v1, 0.0f);
+                    v2 = fmaxf(v2, 0.0f);
+                    v3 = fmaxf(v3, 0.0f);
+                }
+                chunk8 c8;
+                c8[0] = (uint32_t)f32_to_bf16_bits(v0) | ((uint32_t)f32_to_bf16_bits(v1) << 16);
+                c8[1] = (uint32_t)f32_to_bf16_bits(v2) | ((uint32_t)f32_to_bf16_bits(v3) << 16);
+                *reinterpret_cast<chunk8 *>(sO + prow * SROW + col) = c8;
+            }
+        }
+    }
+    __syncthreads();
+    constexpr int CH8 = BC / 8;
+    constexpr int UNITS = 256 * CH8 / 256;
+#pragma unroll 4
+    for (int it = 0; it < UNITS; ++it) {
+        const int u = tid + it * 256;
+        const int pj = u / CH8, c8i = u % CH8;
+        const size_t p = (size_t)(n * H + Y0 + (pj >> 4)) * W + X0 + (pj & 15);
+        const int co = co0 + c8i * 8;
+        chunk8 lo = *reinterpret_cast<const chunk8 *>(sO + pj * SROW + c8i * 8);
+        chunk8 hi = *reinterpret_cast<const chunk8 *>(sO + pj * SROW + c8i * 8 + 4);
+        chunk16 v = {lo[0], lo[1], hi[0], hi[1]};
+        bf16_t *dst = out + p * Co + co;
+        if (is_grad) {
+            chunk16 old = zero16, gt = zero16, rr;
+            if (accum) old = *reinterpret_cast<const chunk16 *>(dst);
+            if (gate) gt = *reinterpret_cast<const chunk16 *>(gate + p * Co + co);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                uint32_t packed = 0;
+#pragma unroll
+                for (int hsel = 0; hsel < 2; ++hsel) {
+                    bf16_t a, o, gg;
+                    a.v = (uint16_t)(v[j] >> (16 * hsel));
+                    o.v = (uint16_t)(old[j] >> (16 * hsel));
+                    gg.v = (uint16_t)(gt[j] >> (16 * hsel));
+                    bf16_t res = grad_out<bf16_t>(to_f32(a), accum != 0, o, gate != nullptr, gg);
+                    packed |= (uint32_t)res.v << (16 * hsel);
+                }
+                rr[j] = packed;
+            }
+            *reinterpret_cast<chunk16 *>(dst) = rr;
+        } else {
+            *reinterpret_cast<chunk16 *>(dst) = v;
+        }
+    }
+}
+
+template <int BC, int WSTAGES>
+hipError_t launch_halo(const void *in, const void *wt, const float *bias, void *out, int relu, GradEpi epi,
+                       const GatherConv &g, hipStream_t s)
+{
+    constexpr size_t smem = (size_t)HALO_ELEMS * 2 + (size_t)WSTAGES * BC * 64 * 2 + BC * sizeof(float);
+    static_assert((size_t)256 * (BC + 4) * 2 <= (size_t)HALO_ELEMS * 2 + (size_t)WSTAGES * BC * 64 * 2, "epilogue staging fits");
+    static_assert(smem <= 80 * 1024, "two blocks per CU");
+    auto kfn = k_conv3x3_halo<BC, WSTAGES>;
+    static bool attr_set = false;
+    if (!attr_set && smem > 64 * 1024) {
+        hipError_t e = hipFuncSetAttribute((const void *)kfn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    const int is_grad = (epi.gate != nullptr || epi.accum) ? 1 : 0;
+    const unsigned in_bytes = (unsigned)((size_t)g.N * g.Hi * g.Wi * g.Ci * 2);
+    const unsigned wt_bytes = (unsigned)((size_t)g.Co * 9 * g.Ci * 2);
+    dim3 grid((unsigned)(g.N * (g.Ho / PATCH) * (g.Wo / PATCH) * (g.Co / BC)));
+    hipLaunchKernelGGL(kfn, grid, dim3(256), smem, s, (const bf16_t *)in, (const bf16_t *)wt, bias, (bf16_t *)out,
+                       (const bf16_t *)epi.gate, epi.accum, relu, is_grad, g.N, g.Hi, g.Wi, g.Ci, g.Co, in_bytes,
+                       wt_bytes);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+bool conv3x3_halo_supported(const GatherConv &g)
+{
+    return g.R == 3 && g.S == 3 && g.s_out == 1 && g.s_in == 1 && g.pad_h == 1 && g.pad_w == 1 && g.Hi == g.Ho &&
+           g.Wi == g.Wo && g.Ho % PATCH == 0 && g.Wo % PATCH == 0 && g.Ci % 64 == 0 && g.Co % 64 == 0 &&
+           (long long)g.N * g.Hi * g.Wi * g.Ci * 2 < (1ll << 31) && (long long)g.Co * 9 * g.Ci * 2 < (1ll << 31) &&
+           (long long)g.N * g.Ho * g.Wo * g.Co < (1ll << 40);
+}
+
+hipError_t conv3x3_halo_mfma(const void *in, const void *wt, const float *bias, void *out, int relu, GradEpi epi,
+                             const GatherConv &g, hipStream_t s)
+{
+    if (!conv3x3_halo_supported(g)) return hipErrorInvalidValue;
+    if (g.Co % 128 == 0) return launch_halo<128, 2>(in, wt, bias, out, relu, epi, g, s);
+    return launch_halo<64, 3>(in, wt, bias, out, relu, epi, g, s);
+}
+
+}  // namespace bapipe

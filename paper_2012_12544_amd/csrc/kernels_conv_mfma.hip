@@ -86,7 +86,9 @@ __global__ __launch_bounds__(WP *WC * 64, 2) void k_gather_mfma(
 
     extern __shared__ __align__(16) unsigned char smem[];
     uint16_t *ring = reinterpret_cast<uint16_t *>(smem);               // [STAGES][ W tile | X tile ]
-    uint16_t *sO = reinterpret_cast<uint16_t *>(smem);                 // [WT_P][SROW] (epilogue)
+    uint16_t *sO = reinterpret_cast<uint16_t *>(smem);                 // [BP][SROW] (epilogue, reuses the ring)
+    constexpr size_t RING_BYTES = (size_t)STAGES * STAGE_ELEMS * 2, EPI_BYTES = (size_t)BP * SROW * 2;
+    float *sBias = reinterpret_cast<float *>(smem + (RING_BYTES > EPI_BYTES ? RING_BYTES : EPI_BYTES));   // [BC]
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -230,6 +232,9 @@ __global__ __launch_bounds__(WP *WC * 64, 2) void k_gather_mfma(
         }
     };
 
+    // the block's bias slice goes to LDS now; it is read after the barriers of the main loop
+    if (tid < BC) sBias[tid] = (bias && co0 + tid < g.Co) ? bias[co0 + tid] : 0.0f;
+
     // every iteration requests exactly XL+WL loads per wave (tiles past the end fetch zeros into a
     // stage nobody reads), so "at most (STAGES-2)*(XL+WL) in flight" means tile kt has landed
     constexpr int NLOAD = XL + WL;
@@ -267,75 +272,70 @@ __global__ __launch_bounds__(WP *WC * 64, 2) void k_gather_mfma(
         return;
     }
 
-    // ---- epilogue: one pixel band (the rows of the waves with the same wp) at a time
+    // ---- epilogue: every wave parks its sub-tile in LDS as [pixel][channel] (bf16, bias and ReLU
+    // applied), one barrier, then the block streams the tile out as 16-byte coalesced rows
     const chunk16 zero16 = {0u, 0u, 0u, 0u};
-    for (int band = 0; band < WP; ++band) {
-        if (wp == band) {
 #pragma unroll
-            for (int a = 0; a < TC; ++a) {
+    for (int a = 0; a < TC; ++a) {
 #pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const int col = wc * WT_C + a * 32 + 8 * q + 4 * fhalf;      // channel inside the tile
-                    float bv[4] = {0.f, 0.f, 0.f, 0.f};
-                    if (bias) {
+        for (int q = 0; q < 4; ++q) {
+            const int col = wc * WT_C + a * 32 + 8 * q + 4 * fhalf;      // channel inside the tile
+            const float4 bv = *reinterpret_cast<const float4 *>(sBias + col);
 #pragma unroll
-                        for (int j = 0; j < 4; ++j)
-                            if (co0 + col + j < g.Co) bv[j] = bias[co0 + col + j];
-                    }
-#pragma unroll
-                    for (int b = 0; b < TP; ++b) {
-                        const int prow = b * 32 + frow;                          // pixel inside the band
-                        uint16_t h[4];
-#pragma unroll
-                        for (int j = 0; j < 4; ++j) {
-                            float v = acc[a][b][4 * q + j] + bv[j];
-                            if (relu) v = fmaxf(v, 0.0f);
-                            h[j] = f32_to_bf16_bits(v);
-                        }
-                        chunk8 c8;
-                        c8[0] = (uint32_t)h[0] | ((uint32_t)h[1] << 16);
-                        c8[1] = (uint32_t)h[2] | ((uint32_t)h[3] << 16);
-                        *reinterpret_cast<chunk8 *>(sO + prow * SROW + col) = c8;
-                    }
+            for (int b = 0; b < TP; ++b) {
+                const int prow = wp * WT_P + b * 32 + frow;              // pixel inside the tile
+                float v0 = acc[a][b][4 * q] + bv.x, v1 = acc[a][b][4 * q + 1] + bv.y;
+                float v2 = acc[a][b][4 * q + 2] + bv.z, v3 = acc[a][b][4 * q + 3] + bv.w;
+                if (relu) {
+                    v0 = fmaxf(v0, 0.0f);
+                    v1 = fmaxf(v1, 0.0f);
+                    v2 = fmaxf(v2, 0.0f);
+                    v3 = fmaxf(v3, 0.0f);
                 }
+                chunk8 c8;
+                c8[0] = (uint32_t)f32_to_bf16_bits(v0) | ((uint32_t)f32_to_bf16_bits(v1) << 16);
+                c8[1] = (uint32_t)f32_to_bf16_bits(v2) | ((uint32_t)f32_to_bf16_bits(v3) << 16);
+                *reinterpret_cast<chunk8 *>(sO + prow * SROW + col) = c8;
             }
         }
-        __syncthreads();
-        constexpr int CH8 = BC / 8;     // 16-byte units per pixel row
-        for (int u = tid; u < WT_P * CH8; u += NT) {
-            const int prow = u / CH8, c8i = u % CH8;
-            const int p = pix0 + band * WT_P + prow;
-            const int co = co0 + c8i * 8;
-            if (p < npix && co < g.Co) {
-                chunk8 lo = *reinterpret_cast<const chunk8 *>(sO + prow * SROW + c8i * 8);
-                chunk8 hi = *reinterpret_cast<const chunk8 *>(sO + prow * SROW + c8i * 8 + 4);
-                chunk16 v = {lo[0], lo[1], hi[0], hi[1]};
-                bf16_t *dst = out + (size_t)p * g.Co + co;
-                if (is_grad) {
-                    chunk16 old = zero16, gt = zero16, r;
-                    if (accum) old = *reinterpret_cast<const chunk16 *>(dst);
-                    if (gate) gt = *reinterpret_cast<const chunk16 *>(gate + (size_t)p * g.Co + co);
+    }
+    __syncthreads();
+    constexpr int CH8 = BC / 8;                 // 16-byte units per pixel row
+    constexpr int UNITS = BP * CH8 / NT;        // per thread
+#pragma unroll 4
+    for (int it = 0; it < UNITS; ++it) {
+        const int u = tid + it * NT;
+        const int prow = u / CH8, c8i = u % CH8;
+        const int p = pix0 + prow;
+        const int co = co0 + c8i * 8;
+        if (p < npix && co < g.Co) {
+            chunk8 lo = *reinterpret_cast<const chunk8 *>(sO + prow * SROW + c8i * 8);
+            chunk8 hi = *reinterpret_cast<const chunk8 *>(sO + prow * SROW + c8i * 8 + 4);
+            chunk16 v = {lo[0], lo[1], hi[0], hi[1]};
+            bf16_t *dst = out + (size_t)p * g.Co + co;
+            if (is_grad) {
+                chunk16 old = zero16, gt = zero16, r;
+                if (accum) old = *reinterpret_cast<const chunk16 *>(dst);
+                if (gate) gt = *reinterpret_cast<const chunk16 *>(gate + (size_t)p * g.Co + co);
 #pragma unroll
-                    for (int j = 0; j < 4; ++j) {
-                        uint32_t packed = 0;
+                for (int j = 0; j < 4; ++j) {
+                    uint32_t packed = 0;
 #pragma unroll
-                        for (int hsel = 0; hsel < 2; ++hsel) {
-                            bf16_t a, o, gg;
-                            a.v = (uint16_t)(v[j] >> (16 * hsel));
-                            o.v = (uint16_t)(old[j] >> (16 * hsel));
-                            gg.v = (uint16_t)(gt[j] >> (16 * hsel));
-                            bf16_t res = grad_out<bf16_t>(to_f32(a), accum != 0, o, gate != nullptr, gg);
-                            packed |= (uint32_t)res.v << (16 * hsel);
-                        }
-                        r[j] = packed;
+                    for (int hsel = 0; hsel < 2; ++hsel) {
+                        bf16_t a, o, gg;
+                        a.v = (uint16_t)(v[j] >> (16 * hsel));
+                        o.v = (uint16_t)(old[j] >> (16 * hsel));
+                        gg.v = (uint16_t)(gt[j] >> (16 * hsel));
+                        bf16_t res = grad_out<bf16_t>(to_f32(a), accum != 0, o, gate != nullptr, gg);
+                        packed |= (uint32_t)res.v << (16 * hsel);
                     }
-                    *reinterpret_cast<chunk16 *>(dst) = r;
-                } else {
-                    *reinterpret_cast<chunk16 *>(dst) = v;
+                    r[j] = packed;
                 }
+                *reinterpret_cast<chunk16 *>(dst) = r;
+            } else {
+                *reinterpret_cast<chunk16 *>(dst) = v;
             }
         }
-        __syncthreads();
     }
 }
 
@@ -400,8 +400,8 @@ hipError_t launch_gather(const void *in, const void *wt, const float *bias, void
 {
     constexpr int NT = WP * WC * 64;
     constexpr size_t main_bytes = (size_t)STAGES * (BP + BC) * BK * 2;
-    constexpr size_t epi_bytes = (size_t)(BP / WP) * (BC + 4) * 2;
-    constexpr size_t smem = main_bytes > epi_bytes ? main_bytes : epi_bytes;
+    constexpr size_t epi_bytes = (size_t)BP * (BC + 4) * 2;
+    constexpr size_t smem = (main_bytes > epi_bytes ? main_bytes : epi_bytes) + BC * sizeof(float);
     static_assert(smem <= 80 * 1024, "two blocks must fit the 160 KB LDS of a CU");
     const long long npix = (long long)g.N * g.Ho * g.Wo;
     const int tiles_p = (int)((npix + BP - 1) / BP), tiles_c = (g.Co + BC - 1) / BC;
@@ -695,6 +695,7 @@ bool conv_gather_mfma_supported(const GatherConv &g)
 
 size_t conv_gather_mfma_workspace(const GatherConv &g)
 {
+    if (conv3x3_halo_supported(g)) return 0;
     GatherPlan p = gather_plan(g);
     return p.splits > 1 ? (size_t)p.splits * g.N * g.Ho * g.Wo * g.Co * sizeof(float) : 0;
 }
@@ -704,6 +705,7 @@ hipError_t conv_gather_mfma(const void *in, const void *wt, const float *bias, v
 {
     if (!conv_gather_mfma_supported(g)) return hipErrorInvalidValue;
     if ((long long)g.N * g.Ho * g.Wo == 0) return hipSuccess;
+    if (conv3x3_halo_supported(g)) return conv3x3_halo_mfma(in, wt, bias, out, relu, epi, g, s);
     const GatherPlan p = gather_plan(g);
     if (p.bp == 64) return launch_gather<64, 128, 1, 4, 32, 3>(in, wt, bias, out, relu, epi, g, p, workspace, s);
     if (p.bc == 64) return launch_gather<256, 64, 4, 1, 32, 3>(in, wt, bias, out, relu, epi, g, p, workspace, s);

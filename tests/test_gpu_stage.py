@@ -39,6 +39,9 @@ def test_conv_layer(dtype, k, stride, cin, cout, hw, relu):
     (1, 1, 128, 256, (9, 7), 5),      # 1x1
     (1, 2, 72, 40, (15, 15), 2),      # 1x1 stride 2
     (3, 1, 8, 8, (5, 4), 1),          # smaller than one tile in every dimension
+    (3, 1, 64, 64, (32, 48), 2),      # sides multiple of 16: halo-in-LDS kernel, 64-channel tile
+    (3, 1, 128, 128, (16, 32), 3),    # halo kernel, two 64-channel input slices, 128-channel tile
+    (3, 1, 128, 192, (32, 16), 1),    # halo kernel, 192 = 3 x 64 output channels
 ])
 def test_conv_mfma_tiling(k, stride, cin, cout, hw, mb):
     st = single(lambda b: b.conv(cin, cout, k, stride=stride, relu=1, src=-1), cin, hw, C.BF16, micro_batch=mb)
