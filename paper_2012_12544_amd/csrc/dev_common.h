@@ -53,6 +53,28 @@ __device__ __forceinline__ T grad_out(float v, bool accum, T old, bool masked, T
     return from_f32<T>(r);
 }
 
+// grad_out() on two bf16 values packed in a 32-bit word whose contribution `v` is already rounded
+// to bf16.  Without accumulation the result is v where the gate is positive and +0 elsewhere; a
+// positive finite bf16 is exactly a positive 16-bit integer, so the gate is an integer compare.
+__device__ __forceinline__ uint32_t grad_epilogue_pair(uint32_t v, uint32_t old, uint32_t gate, bool accum, bool masked)
+{
+    if (!accum) {
+        if (!masked) return v;
+        const uint32_t m = ((int32_t)(gate << 16) > 0 ? 0x0000FFFFu : 0u) | ((int32_t)(gate & 0xFFFF0000u) > 0 ? 0xFFFF0000u : 0u);
+        return v & m;
+    }
+    uint32_t packed = 0;
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        bf16_t a, o, g;
+        a.v = (uint16_t)(v >> (16 * h));
+        o.v = (uint16_t)(old >> (16 * h));
+        g.v = (uint16_t)(gate >> (16 * h));
+        packed |= (uint32_t)grad_out<bf16_t>(to_f32(a), true, o, masked, g).v << (16 * h);
+    }
+    return packed;
+}
+
 __device__ __forceinline__ float wave_sum(float v)
 {
 #pragma unroll

@@ -191,7 +191,7 @@ __global__ __launch_bounds__(256, 2) void k_conv3x3_halo(const bf16_t *__restric
     __syncthreads();
     constexpr int CH8 = BC / 8;
     constexpr int UNITS = 256 * CH8 / 256;
-#pragma unroll 4
+#pragma unroll
     for (int it = 0; it < UNITS; ++it) {
         const int u = tid + it * 256;
         const int pj = u / CH8, c8i = u % CH8;
@@ -206,19 +206,7 @@ __global__ __launch_bounds__(256, 2) void k_conv3x3_halo(const bf16_t *__restric
             if (accum) old = *reinterpret_cast<const chunk16 *>(dst);
             if (gate) gt = *reinterpret_cast<const chunk16 *>(gate + p * Co + co);
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                uint32_t packed = 0;
-#pragma unroll
-                for (int hsel = 0; hsel < 2; ++hsel) {
-                    bf16_t a, o, gg;
-                    a.v = (uint16_t)(v[j] >> (16 * hsel));
-                    o.v = (uint16_t)(old[j] >> (16 * hsel));
-                    gg.v = (uint16_t)(gt[j] >> (16 * hsel));
-                    bf16_t res = grad_out<bf16_t>(to_f32(a), accum != 0, o, gate != nullptr, gg);
-                    packed |= (uint32_t)res.v << (16 * hsel);
-                }
-                rr[j] = packed;
-            }
+            for (int j = 0; j < 4; ++j) rr[j] = grad_epilogue_pair(v[j], old[j], gt[j], accum != 0, gate != nullptr);
             *reinterpret_cast<chunk16 *>(dst) = rr;
         } else {
             *reinterpret_cast<chunk16 *>(dst) = v;

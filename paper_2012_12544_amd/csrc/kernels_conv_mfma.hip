@@ -302,7 +302,7 @@ __global__ __launch_bounds__(WP *WC * 64, 2) void k_gather_mfma(
     __syncthreads();
     constexpr int CH8 = BC / 8;                 // 16-byte units per pixel row
     constexpr int UNITS = BP * CH8 / NT;        // per thread
-#pragma unroll 4
+#pragma unroll
     for (int it = 0; it < UNITS; ++it) {
         const int u = tid + it * NT;
         const int prow = u / CH8, c8i = u % CH8;
@@ -318,19 +318,7 @@ __global__ __launch_bounds__(WP *WC * 64, 2) void k_gather_mfma(
                 if (accum) old = *reinterpret_cast<const chunk16 *>(dst);
                 if (gate) gt = *reinterpret_cast<const chunk16 *>(gate + (size_t)p * g.Co + co);
 #pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    uint32_t packed = 0;
-#pragma unroll
-                    for (int hsel = 0; hsel < 2; ++hsel) {
-                        bf16_t a, o, gg;
-                        a.v = (uint16_t)(v[j] >> (16 * hsel));
-                        o.v = (uint16_t)(old[j] >> (16 * hsel));
-                        gg.v = (uint16_t)(gt[j] >> (16 * hsel));
-                        bf16_t res = grad_out<bf16_t>(to_f32(a), accum != 0, o, gate != nullptr, gg);
-                        packed |= (uint32_t)res.v << (16 * hsel);
-                    }
-                    r[j] = packed;
-                }
+                for (int j = 0; j < 4; ++j) r[j] = grad_epilogue_pair(v[j], old[j], gt[j], accum != 0, gate != nullptr);
                 *reinterpret_cast<chunk16 *>(dst) = r;
             } else {
                 *reinterpret_cast<chunk16 *>(dst) = v;
@@ -632,25 +620,32 @@ __global__ __launch_bounds__(WKO *WCI * 64, 2) void k_wgrad_mfma(const bf16_t *_
         }
 }
 
+// dw[i] += sum_k part[k][i].  A block owns 64 float4 columns; its 4 split-lanes walk the partials
+// with stride 4 and are combined through LDS in lane order (the result does not depend on timing).
+// total is a multiple of 4 (channel counts are multiples of 8).
 __global__ void k_splitk_reduce(const float *__restrict__ part, float *dw, size_t total, int splits)
 {
-    size_t i = ((size_t)blockIdx.x * 256 + threadIdx.x) * 4;
-    if (i >= total) return;
-    if (i + 4 <= total) {
-        float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-        for (int k = 0; k < splits; ++k) {
+    __shared__ float4 red[4][64];
+    const int col = threadIdx.x & 63, sl = threadIdx.x >> 6;
+    const size_t i = ((size_t)blockIdx.x * 64 + col) * 4;
+    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (i < total) {
+#pragma unroll 4
+        for (int k = sl; k < splits; k += 4) {
             float4 v = *reinterpret_cast<const float4 *>(part + (size_t)k * total + i);
             acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
         }
+    }
+    red[sl][col] = acc;
+    __syncthreads();
+    if (sl == 0 && i < total) {
         float4 d = *reinterpret_cast<float4 *>(dw + i);
-        d.x += acc.x; d.y += acc.y; d.z += acc.z; d.w += acc.w;
-        *reinterpret_cast<float4 *>(dw + i) = d;
-    } else {
-        for (size_t j = i; j < total; ++j) {
-            float acc = 0.f;
-            for (int k = 0; k < splits; ++k) acc += part[(size_t)k * total + j];
-            dw[j] += acc;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            float4 v = red[k][col];
+            d.x += v.x; d.y += v.y; d.z += v.z; d.w += v.w;
         }
+        *reinterpret_cast<float4 *>(dw + i) = d;
     }
 }
 
@@ -762,7 +757,7 @@ hipError_t conv_wgrad_mfma(const void *x, const void *dy, float *dw, void *works
 #undef WG_LAUNCH
     size_t total = (size_t)c.K * c.R * c.S * c.C;
     if (!direct)
-        hipLaunchKernelGGL(k_splitk_reduce, dim3((unsigned)((total / 4 + 255) / 256 + 1)), dim3(256), 0, s, part,
+        hipLaunchKernelGGL(k_splitk_reduce, dim3((unsigned)((total / 4 + 63) / 64)), dim3(256), 0, s, part,
                            dw, total, p.splits);
     return hipGetLastError();
 }
