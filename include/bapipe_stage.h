@@ -127,7 +127,10 @@ int bapipe_stage_create(const bapipe_layer_desc_t *layers, int n_layers, int mic
 int bapipe_stage_forward(bapipe_stage_t *st, int mb_id, const void *x_dev, void *y_dev);
 
 /* Backward pass of micro-batch mb_id: consumes its stashed features, adds its weight
- * gradients into the fp32 accumulators and releases its stash slot.
+ * gradients into the fp32 accumulators and releases its stash slot.  (For LINEAR layers the
+ * library may keep the micro-batch's layer input and output gradient instead and form the
+ * weight gradient of all micro-batches with one GEMM inside bapipe_stage_step /
+ * bapipe_stage_get_grads: same sums, different summation order.)
  * dy_dev_or_labels: device; gradient w.r.t. the stage output (layout/type as y), or, when
  * the last layer is SOFTMAX_XENT, micro_batch int32 class labels.
  * dx_dev: device, receives the gradient w.r.t. the stage input (layout/type as x); may be

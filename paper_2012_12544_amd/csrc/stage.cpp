@@ -55,6 +55,12 @@ struct Layer {
     void *w_work = nullptr, *w_t = nullptr;
     size_t aux_off = 0, aux_bytes = 0;   // pool indices / BN statistics inside the slot
     int cin_p = 0;                       // input channels as laid out in HBM (conv / linear)
+    // deferred weight gradient (linear layers): the layer's input and gated output gradient of every
+    // micro-batch are kept and ONE wgrad GEMM over all of them runs at step time, so that dW
+    // (hundreds of MB for the VGG classifier) is touched once per mini-batch instead of M times
+    bool deferred = false;
+    char *def_x = nullptr, *def_g = nullptr;
+    size_t def_x_bytes = 0, def_g_bytes = 0;     // per micro-batch
     bool permute_in = false;             // LINEAR fed by a flattened (C,H,W) tensor
     int pc = 0, ph = 0, pw = 0;
 };
@@ -71,6 +77,9 @@ struct bapipe_stage {
     hipStream_t stream = nullptr;
     // arenas
     char *params = nullptr, *stash = nullptr, *transient = nullptr, *grads = nullptr, *work = nullptr;
+    char *deferred = nullptr;
+    size_t deferred_bytes = 0;
+    int flushed = 0;                         // micro-batches whose deferred weight gradients are already in dw
     float *losses = nullptr;
     size_t params_bytes = 0, slot_bytes = 0, transient_bytes = 0, grads_bytes = 0, work_bytes = 0;
     size_t accum_off = 0, accum_bytes = 0;   // the dw/db region inside params (zeroed together)
@@ -355,6 +364,7 @@ struct BwdCtx {
     void *dx_direct;               // caller's NHWC buffer used in place of grads[0]
     const int32_t *labels;
     std::vector<char> written;
+    bool profiling = false;        // profiler: run every kernel of the layer now (no deferral)
 };
 
 void *grad_ptr(bapipe_stage *st, int t, BwdCtx &c)
@@ -392,7 +402,10 @@ int layer_backward(bapipe_stage *st, int li, BwdCtx &c)
         const void *x = st->tptr(L.a, c.mbid);
         ConvShape cs = conv_shape(st, L);
         const double flop = conv_flop(fwd_geom(st, L), L.d.cin);
-        {
+        if (L.deferred && !c.profiling) {
+            HIPCHK(hipMemcpyAsync(L.def_x + (size_t)c.mbid * L.def_x_bytes, x, L.def_x_bytes, hipMemcpyDeviceToDevice, s));
+            HIPCHK(hipMemcpyAsync(L.def_g + (size_t)c.mbid * L.def_g_bytes, g, L.def_g_bytes, hipMemcpyDeviceToDevice, s));
+        } else {
             const bool mf = use_mfma_wgrad(st, cs);
             const bool tp = st->tap_begin(mf ? BAPIPE_KC_CONV_WGRAD_MFMA : BAPIPE_KC_CONV_DIRECT);
             if (mf)
@@ -483,6 +496,25 @@ int layer_backward(bapipe_stage *st, int li, BwdCtx &c)
     return BAPIPE_OK;
 }
 
+// weight gradients of the deferred layers for micro-batches [flushed, n_bwd): one GEMM per layer
+int flush_deferred(bapipe_stage *st)
+{
+    const int n = st->n_bwd - st->flushed;
+    if (n <= 0) return BAPIPE_OK;
+    for (auto &L : st->layers) {
+        if (!L.deferred) continue;
+        ConvShape cs = conv_shape(st, L);
+        cs.N = st->mb * n;
+        const char *x = L.def_x + (size_t)st->flushed * L.def_x_bytes;
+        const char *g = L.def_g + (size_t)st->flushed * L.def_g_bytes;
+        const bool tp = st->tap_begin(BAPIPE_KC_CONV_WGRAD_MFMA);
+        HIPCHK(conv_wgrad_mfma(x, g, L.dw, st->work, cs, st->stream));
+        st->tap_end(tp, conv_flop(fwd_geom(st, L), L.d.cin) * n, 0.0);
+    }
+    st->flushed = st->n_bwd;
+    return BAPIPE_OK;
+}
+
 }  // namespace
 
 // ======================================================================== C ABI
@@ -500,6 +532,7 @@ void bapipe_stage_destroy(bapipe_stage_t *st)
     st->dev_free(st->grads);
     st->dev_free(st->work);
     st->dev_free(st->losses);
+    st->dev_free(st->deferred);
     for (hipEvent_t e : st->tap_events) (void)hipEventDestroy(e);
     delete st;
 }
@@ -716,6 +749,17 @@ int bapipe_stage_create(const bapipe_layer_desc_t *layers, int n_layers, int mic
         }
         if (L.d.kind == BAPIPE_CONV2D || L.d.kind == BAPIPE_LINEAR) {
             ConvShape cs = conv_shape(st, L);
+            if (L.d.kind == BAPIPE_LINEAR && n_micro > 1 && use_mfma_wgrad(st, cs)) {
+                ConvShape all = cs;
+                all.N = micro_batch * n_micro;
+                if (use_mfma_wgrad(st, all)) {
+                    L.deferred = true;
+                    L.def_x_bytes = st->tensors[st->tensors[L.a].root].bytes();
+                    L.def_g_bytes = st->tensors[L.o].bytes();
+                    size_t wd = conv_wgrad_mfma_workspace(all);
+                    work = wd > work ? wd : work;
+                }
+            }
             size_t w = use_mfma_wgrad(st, cs) ? conv_wgrad_mfma_workspace(cs) : conv_wgrad_direct_workspace(cs);
             work = w > work ? w : work;
             w = colsum_workspace(cs.N * cs.P * cs.Q, cs.K);
@@ -744,6 +788,10 @@ int bapipe_stage_create(const bapipe_layer_desc_t *layers, int n_layers, int mic
     }
     st->params_bytes = pb;
 
+    size_t defb = 0;
+    for (auto &L : st->layers)
+        if (L.deferred) defb += align_up(L.def_x_bytes * n_micro) + align_up(L.def_g_bytes * n_micro);
+    st->deferred_bytes = defb;
     if (hipSuccess != hipGetLastError()) { /* clear stale error state */ }
     st->params = (char *)st->dev_alloc(st->params_bytes);
     st->stash = (char *)st->dev_alloc(st->slot_bytes * st->depth);
@@ -751,9 +799,18 @@ int bapipe_stage_create(const bapipe_layer_desc_t *layers, int n_layers, int mic
     st->grads = (char *)st->dev_alloc(st->grads_bytes);
     st->work = (char *)st->dev_alloc(st->work_bytes);
     st->losses = (float *)st->dev_alloc(sizeof(float) * n_micro);
-    if (!st->params || !st->stash || !st->transient || !st->grads || !st->work || !st->losses)
+    if (defb) st->deferred = (char *)st->dev_alloc(defb);
+    if (!st->params || !st->stash || !st->transient || !st->grads || !st->work || !st->losses || (defb && !st->deferred))
         return create_fail(BAPIPE_E_OOM, "device allocation failed (params %zu, stash %zu x %d, transient %zu, grads %zu, work %zu bytes)",
                            st->params_bytes, st->slot_bytes, st->depth, st->transient_bytes, st->grads_bytes, st->work_bytes);
+    {
+        size_t off = 0;
+        for (auto &L : st->layers)
+            if (L.deferred) {
+                L.def_x = st->deferred + off; off += align_up(L.def_x_bytes * n_micro);
+                L.def_g = st->deferred + off; off += align_up(L.def_g_bytes * n_micro);
+            }
+    }
     for (int i = 0; i < n_layers; ++i) {
         Layer &L = st->layers[i];
         if (!L.w_elems) continue;
@@ -867,6 +924,10 @@ int bapipe_stage_step(bapipe_stage_t *st, float lr)
     if (!st) return BAPIPE_E_INVALID;
     if (st->n_bwd != st->M)
         return st->fail(BAPIPE_E_ORDER, "step: %d of %d backward passes done", st->n_bwd, st->M);
+    {
+        int rc = flush_deferred(st);
+        if (rc != BAPIPE_OK) return rc;
+    }
     for (auto &L : st->layers) {
         if (!L.w_elems) continue;
         const bool mat = L.d.kind != BAPIPE_BATCHNORM2D;
@@ -878,6 +939,7 @@ int bapipe_stage_step(bapipe_stage_t *st, float lr)
         }
     }
     st->n_fwd = st->n_bwd = 0;
+    st->flushed = 0;
     return BAPIPE_OK;
 }
 
@@ -912,6 +974,10 @@ static int get_vectors(bapipe_stage_t *st, int layer, float *w_host, float *b_ho
     if (layer < 0 || layer >= (int)st->layers.size() || !st->layers[layer].w_elems)
         return st->fail(BAPIPE_E_INVALID, "%s: layer %d has no parameters", what, layer);
     Layer &L = st->layers[layer];
+    if (grads) {
+        int rc = flush_deferred(st);
+        if (rc != BAPIPE_OK) return rc;
+    }
     HIPCHK(hipStreamSynchronize(st->stream));
     if (w_host) {
         const float *src = grads ? L.dw : L.w;
@@ -1049,6 +1115,7 @@ int bapipe_profile_layers(bapipe_stage_t *st, int warmup, int iters, bapipe_laye
 
         BwdCtx bc;
         bc.mbid = 0; bc.x_direct = bc.dy_direct = nullptr; bc.dx_direct = nullptr; bc.labels = nullptr;
+        bc.profiling = true;
         if (L.d.kind == BAPIPE_SOFTMAX_XENT) {
             if (hipMemcpyAsync(labels_dev, zero_labels.data(), sizeof(int32_t) * st->mb, hipMemcpyHostToDevice, s) != hipSuccess) { rc = st->fail(BAPIPE_E_DEVICE, "profile: label upload"); break; }
             (void)hipStreamSynchronize(s);
