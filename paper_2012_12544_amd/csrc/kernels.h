@@ -49,6 +49,10 @@ hipError_t conv_gather_mfma(const void *in, const void *wt, const float *bias, v
 bool conv3x3_halo_supported(const GatherConv &g);
 hipError_t conv3x3_halo_mfma(const void *in, const void *wt, const float *bias, void *out, int relu,
                              GradEpi epi, const GatherConv &g, hipStream_t s);
+bool wgrad3x3_halo_supported(const ConvShape &c);
+size_t wgrad3x3_halo_workspace(const ConvShape &c);
+hipError_t wgrad3x3_halo_mfma(const void *x, const void *dy, float *dw, void *workspace, const ConvShape &c,
+                              hipStream_t s);
 bool conv_wgrad_mfma_supported(const ConvShape &c);
 size_t conv_wgrad_mfma_workspace(const ConvShape &c);
 hipError_t conv_wgrad_mfma(const void *x, const void *dy, float *dw, void *workspace,

@@ -238,6 +238,201 @@ hipError_t launch_halo(const void *in, const void *wt, const float *bias, void *
     return hipGetLastError();
 }
 
+
+// ------------------------------------------------------------------------------------------
+// wgrad with the input halo in LDS
+// ------------------------------------------------------------------------------------------
+// dw[ko][r][s][c] += sum over pixels of dy[pixel][ko] * x[pixel shifted by tap (r,s)][c] for 3x3 /
+// stride 1 / pad 1 on 16-aligned maps.  A block owns 64 output channels x 64 input channels x ALL 9
+// taps (a 64 x 576 fp32 tile, 144 accumulator registers per lane) and walks over units of 8x16
+// pixels: the unit's dy rows and the 10x18 halo of x land in LDS once (buffer_load ... lds, two
+// stages) and the nine taps read shifted views of the same halo through the transposing LDS read,
+// so x is fetched 1.4 times instead of 9.  Units are split over blockIdx.y; partial tiles are
+// reduced by k_wg_halo_reduce in a fixed order.
+typedef short s16x4_t __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ int wg_swz64(int row) { return 2 * ((row >> 1) & 1); }      // rows of 64 bf16
+
+// lane -> channel ch0 + (lane & 31), pixels (tile rows) k0 + 8*(lane >> 5) .. +7
+__device__ __forceinline__ bf16x8_t tr_frag64(const uint16_t *tile, int ch0, int k0, int lane)
+{
+    const int blk = lane >> 4, sl = lane & 15;
+    const int row = k0 + 8 * (blk >> 1) + (sl >> 2);
+    const int col = ch0 + 16 * (blk & 1) + 4 * (sl & 3);
+    const int chunk = col >> 3;
+    const int sw = (((chunk >> 1) ^ wg_swz64(row)) << 1) | (chunk & 1);
+    const uint16_t *p = tile + row * 64 + (sw << 3) + (col & 7);
+    typedef __attribute__((address_space(3))) s16x4_t lds_v4;
+    s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4 *)(p));
+    s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4 *)(p + 4 * 64));      // rows +4: same swizzle
+    typedef short s16x8_t __attribute__((ext_vector_type(8)));
+    s16x8_t both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    return __builtin_bit_cast(bf16x8_t, both);
+}
+
+constexpr int UH = 8, UW = 16, UPIX = UH * UW;                 // unit of 8 x 16 pixels
+constexpr int WH_ROWS = UH + 2, WH_COLS = UW + 2, WH_PIX = WH_ROWS * WH_COLS;      // 10 x 18 halo = 180 pixels
+constexpr int WG_DY_ELEMS = UPIX * 64;                         // 16 KB
+constexpr int WG_HALO_ELEMS = WH_PIX * 64 + 256;               // 1440 slots + 32 slots the last wave-load overruns
+constexpr int WG_STAGE_ELEMS = WG_DY_ELEMS + WG_HALO_ELEMS;
+constexpr int WG_HL = 6, WG_DL = 4;                            // wave-loads per wave: halo (24 >= 22.5), dy (16)
+
+__global__ __launch_bounds__(256, 2) void k_wgrad3x3_halo(const bf16_t *__restrict__ x, const bf16_t *__restrict__ dy,
+                                                          float *__restrict__ part, int N, int H, int W, int C,
+                                                          int K, int units_per_split, unsigned x_bytes,
+                                                          unsigned dy_bytes)
+{
+    constexpr unsigned OOB = 0x80000000u;
+    constexpr int NW = 4;
+    extern __shared__ __align__(16) unsigned char smem[];
+    uint16_t *stage0 = reinterpret_cast<uint16_t *>(smem);
+    uint16_t *dump = stage0 + 2 * WG_STAGE_ELEMS;              // 64 slots for the one all-out-of-range wave-load
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wk = wave & 1, wn = wave >> 1;                   // 32 output channels x 9 column tiles per wave
+    const int cslices = C / 64;
+    const int cs = blockIdx.x % cslices, kt = blockIdx.x / cslices;
+    const int ko0 = kt * 64, ci0 = cs * 64;
+    const int ux = W / UW, uy = H / UH, upi = ux * uy;
+    const int U = N * upi;
+    const int u0 = blockIdx.y * units_per_split;
+    const int u1 = u0 + units_per_split < U ? u0 + units_per_split : U;
+
+    __amdgpu_buffer_rsrc_t xrsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t *>(x), 0, (int)x_bytes, 0x00020000);
+    __amdgpu_buffer_rsrc_t grsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t *>(dy), 0, (int)dy_bytes, 0x00020000);
+
+    // halo slots of this lane (fixed relative to the unit origin)
+    int hdy[WG_HL], hdx[WG_HL];
+    unsigned hco[WG_HL];
+#pragma unroll
+    for (int i = 0; i < WG_HL; ++i) {
+        const int slot = (i * NW + wave) * 64 + lane;
+        const int hr = slot >> 3, cq = slot & 7;
+        const int c = ((((cq >> 1) ^ wg_swz64(hr)) << 1) | (cq & 1));
+        const int hy = hr / WH_COLS, hx = hr - hy * WH_COLS;
+        hdy[i] = hr < WH_PIX ? hy - 1 : -(1 << 20);
+        hdx[i] = hx - 1;
+        hco[i] = (unsigned)(ci0 + c * 8) * 2u;
+    }
+    unsigned dco[WG_DL];
+    int ddy[WG_DL], ddx[WG_DL];
+#pragma unroll
+    for (int i = 0; i < WG_DL; ++i) {
+        const int slot = (i * NW + wave) * 64 + lane;
+        const int px = slot >> 3, cq = slot & 7;
+        const int c = ((((cq >> 1) ^ wg_swz64(px)) << 1) | (cq & 1));
+        ddy[i] = px >> 4;
+        ddx[i] = px & 15;
+        dco[i] = (unsigned)(ko0 + c * 8) * 2u;
+    }
+    auto issue_unit = [&](int u, int st) {
+        uint16_t *sd = stage0 + st * WG_STAGE_ELEMS, *sh = sd + WG_DY_ELEMS;
+        const bool live = u < u1;
+        const int n = u / upi, rem = u - n * upi;
+        const int Y0 = (rem / ux) * UH, X0 = (rem % ux) * UW;
+#pragma unroll
+        for (int i = 0; i < WG_DL; ++i) {
+            unsigned vo = live ? (unsigned)(((n * H + Y0 + ddy[i]) * W + X0 + ddx[i]) * K) * 2u + dco[i] : OOB;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(grsrc, (lds_void_t *)(sd + (i * NW + wave) * 512), 16, (int)vo, 0, 0, 0);
+        }
+#pragma unroll
+        for (int i = 0; i < WG_HL; ++i) {
+            const int y = Y0 + hdy[i], xx = X0 + hdx[i];
+            const bool ok = live && (unsigned)y < (unsigned)H && (unsigned)xx < (unsigned)W;
+            unsigned vo = ok ? (unsigned)(((n * H + y) * W + xx) * C) * 2u + hco[i] : OOB;
+            const int q = i * NW + wave;                             // wave-load 23 lies wholly past the halo
+            uint16_t *dst = q * 64 < WH_PIX * 8 ? sh + q * 512 : dump;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(xrsrc, (lds_void_t *)dst, 16, (int)vo, 0, 0, 0);
+        }
+    };
+
+    f32x16_t acc[9];
+#pragma unroll
+    for (int b = 0; b < 9; ++b)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[b][v] = 0.0f;
+
+    issue_unit(u0, 0);
+    for (int u = u0; u < u1; ++u) {
+        const int st = (u - u0) & 1;
+        WAIT_VMCNT(0);
+        __builtin_amdgcn_s_barrier();
+        issue_unit(u + 1, st ^ 1);
+        const uint16_t *sd = stage0 + st * WG_STAGE_ELEMS, *sh = sd + WG_DY_ELEMS;
+#pragma unroll 2
+        for (int y = 0; y < UH; ++y) {                               // one k16 step = one row of 16 pixels
+            const bf16x8_t fa = tr_frag64(sd, wk * 32, y * 16, lane);
+#pragma unroll
+            for (int b = 0; b < 9; ++b) {
+                const int ct = wn * 9 + b, tap = ct >> 1;
+                const int r = tap / 3, s = tap - r * 3;
+                const bf16x8_t fb = tr_frag64(sh, (ct & 1) * 32, (y + r) * WH_COLS + s, lane);
+                acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa, fb, acc[b], 0, 0, 0);
+            }
+        }
+    }
+    WAIT_VMCNT(0);
+
+    // partial[split][ko][tap][c]: a wave writes 32 consecutive c (128 bytes) per row
+    const size_t total = (size_t)K * 9 * C;
+    float *dst = part + (size_t)blockIdx.y * total;
+    const int col = lane & 31, half = lane >> 5;
+#pragma unroll
+    for (int b = 0; b < 9; ++b) {
+        const int ct = wn * 9 + b, tap = ct >> 1;
+        const int c = ci0 + (ct & 1) * 32 + col;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int ko = ko0 + wk * 32 + 8 * (v >> 2) + 4 * half + (v & 3);
+            dst[((size_t)ko * 9 + tap) * C + c] = acc[b][v];
+        }
+    }
+}
+
+__global__ void k_wg_halo_reduce(const float *__restrict__ part, float *dw, size_t total, int splits)
+{
+    __shared__ float4 red[4][64];
+    const int col = threadIdx.x & 63, sl = threadIdx.x >> 6;
+    const size_t i = ((size_t)blockIdx.x * 64 + col) * 4;
+    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (i < total) {
+#pragma unroll 4
+        for (int k = sl; k < splits; k += 4) {
+            float4 v = *reinterpret_cast<const float4 *>(part + (size_t)k * total + i);
+            acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
+        }
+    }
+    red[sl][col] = acc;
+    __syncthreads();
+    if (sl == 0 && i < total) {
+        float4 d = *reinterpret_cast<float4 *>(dw + i);
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            float4 v = red[k][col];
+            d.x += v.x; d.y += v.y; d.z += v.z; d.w += v.w;
+        }
+        *reinterpret_cast<float4 *>(dw + i) = d;
+    }
+}
+
+struct WgHaloPlan {
+    int tiles, splits, units_per_split;
+};
+
+WgHaloPlan wg_halo_plan(const ConvShape &c)
+{
+    WgHaloPlan p;
+    p.tiles = (c.K / 64) * (c.C / 64);
+    const int U = c.N * (c.H / UH) * (c.W / UW);
+    int want = (512 + p.tiles - 1) / p.tiles;
+    if (want > U) want = U;
+    if (want < 1) want = 1;
+    p.units_per_split = (U + want - 1) / want;
+    p.splits = (U + p.units_per_split - 1) / p.units_per_split;
+    return p;
+}
+
 }  // namespace
 
 bool conv3x3_halo_supported(const GatherConv &g)
@@ -254,6 +449,47 @@ hipError_t conv3x3_halo_mfma(const void *in, const void *wt, const float *bias, 
     if (!conv3x3_halo_supported(g)) return hipErrorInvalidValue;
     if (g.Co % 128 == 0) return launch_halo<128, 2>(in, wt, bias, out, relu, epi, g, s);
     return launch_halo<64, 3>(in, wt, bias, out, relu, epi, g, s);
+}
+
+}  // namespace bapipe
+
+namespace bapipe {
+
+bool wgrad3x3_halo_supported(const ConvShape &c)
+{
+    return c.R == 3 && c.S == 3 && c.stride == 1 && c.pad == 1 && c.H == c.P && c.W == c.Q && c.H % UH == 0 &&
+           c.W % UW == 0 && c.C % 64 == 0 && c.K % 64 == 0 &&
+           (long long)c.N * c.H * c.W * c.C * 2 < (1ll << 31) && (long long)c.N * c.H * c.W * c.K * 2 < (1ll << 31);
+}
+
+size_t wgrad3x3_halo_workspace(const ConvShape &c)
+{
+    return (size_t)wg_halo_plan(c).splits * c.K * 9 * c.C * sizeof(float);
+}
+
+hipError_t wgrad3x3_halo_mfma(const void *x, const void *dy, float *dw, void *workspace, const ConvShape &c,
+                              hipStream_t s)
+{
+    if (!wgrad3x3_halo_supported(c)) return hipErrorInvalidValue;
+    const WgHaloPlan p = wg_halo_plan(c);
+    constexpr size_t smem = (size_t)(2 * WG_STAGE_ELEMS + 512) * 2;
+    static_assert(smem <= 80 * 1024, "two blocks per CU");
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute((const void *)k_wgrad3x3_halo, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    const unsigned x_bytes = (unsigned)((size_t)c.N * c.H * c.W * c.C * 2);
+    const unsigned dy_bytes = (unsigned)((size_t)c.N * c.H * c.W * c.K * 2);
+    float *part = (float *)workspace;
+    hipLaunchKernelGGL(k_wgrad3x3_halo, dim3((unsigned)p.tiles, (unsigned)p.splits), dim3(256), smem, s,
+                       (const bf16_t *)x, (const bf16_t *)dy, part, c.N, c.H, c.W, c.C, c.K, p.units_per_split,
+                       x_bytes, dy_bytes);
+    const size_t total = (size_t)c.K * 9 * c.C;
+    hipLaunchKernelGGL(k_wg_halo_reduce, dim3((unsigned)((total / 4 + 63) / 64)), dim3(256), 0, s, part, dw, total,
+                       p.splits);
+    return hipGetLastError();
 }
 
 }  // namespace bapipe
