@@ -51,11 +51,12 @@ hipError_t conv3x3_halo_mfma(const void *in, const void *wt, const float *bias, 
                              GradEpi epi, const GatherConv &g, hipStream_t s);
 bool wgrad3x3_halo_supported(const ConvShape &c);
 size_t wgrad3x3_halo_workspace(const ConvShape &c);
-hipError_t wgrad3x3_halo_mfma(const void *x, const void *dy, float *dw, void *workspace, const ConvShape &c,
-                              hipStream_t s);
+hipError_t wgrad3x3_halo_mfma(const void *x, const void *dy, float *dw, float *db, void *workspace,
+                              const ConvShape &c, hipStream_t s);
 bool conv_wgrad_mfma_supported(const ConvShape &c);
 size_t conv_wgrad_mfma_workspace(const ConvShape &c);
-hipError_t conv_wgrad_mfma(const void *x, const void *dy, float *dw, void *workspace,
+// dw += dy^T x over all pixels; db (may be null) += column sums of dy
+hipError_t conv_wgrad_mfma(const void *x, const void *dy, float *dw, float *db, void *workspace,
                            const ConvShape &c, hipStream_t s);
 
 // ---- column sums over a [rows][C] matrix: out[c] += sum_r a[r][c]  (bias gradient)

@@ -10,27 +10,11 @@
 // small LDS ring.  HBM/L2 traffic per output drops from 9 input reads to (18*18)/(16*16) = 1.27.
 // MFMA mapping, swizzles and the epilogue are those of the gather kernel (A = filter rows, B = pixels,
 // v_mfma_f32_32x32x16_bf16, staging through LDS to 16-byte coalesced rows).
-#include "dev_common.h"
 #include "kernels.h"
+#include "mfma_common.h"
 
 namespace bapipe {
 namespace {
-
-typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
-typedef float f32x16_t __attribute__((ext_vector_type(16)));
-typedef uint32_t chunk16 __attribute__((ext_vector_type(4)));
-typedef uint32_t chunk8 __attribute__((ext_vector_type(2)));
-typedef __attribute__((address_space(3))) void lds_void_t;
-
-#define WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(0x0F70 | ((n) & 15) | (((n) >> 4) << 14))
-
-__device__ __forceinline__ bf16x8_t as_frag(chunk16 c) { return __builtin_bit_cast(bf16x8_t, c); }
-
-__device__ __forceinline__ int xcd_remap(int id, int nb)
-{
-    const int x = id & 7, q = nb >> 3, rem = nb & 7;
-    return x * q + (x < rem ? x : rem) + (id >> 3);
-}
 
 // rows of 64 bf16 (8 chunks of 16 bytes): 16 consecutive rows read the same chunk column without
 // bank conflicts when the chunk index is XORed with bits 1..3 of the row
@@ -249,27 +233,6 @@ hipError_t launch_halo(const void *in, const void *wt, const float *bias, void *
 // stages) and the nine taps read shifted views of the same halo through the transposing LDS read,
 // so x is fetched 1.4 times instead of 9.  Units are split over blockIdx.y; partial tiles are
 // reduced by k_wg_halo_reduce in a fixed order.
-typedef short s16x4_t __attribute__((ext_vector_type(4)));
-
-__device__ __forceinline__ int wg_swz64(int row) { return 2 * ((row >> 1) & 1); }      // rows of 64 bf16
-
-// lane -> channel ch0 + (lane & 31), pixels (tile rows) k0 + 8*(lane >> 5) .. +7
-__device__ __forceinline__ bf16x8_t tr_frag64(const uint16_t *tile, int ch0, int k0, int lane)
-{
-    const int blk = lane >> 4, sl = lane & 15;
-    const int row = k0 + 8 * (blk >> 1) + (sl >> 2);
-    const int col = ch0 + 16 * (blk & 1) + 4 * (sl & 3);
-    const int chunk = col >> 3;
-    const int sw = (((chunk >> 1) ^ wg_swz64(row)) << 1) | (chunk & 1);
-    const uint16_t *p = tile + row * 64 + (sw << 3) + (col & 7);
-    typedef __attribute__((address_space(3))) s16x4_t lds_v4;
-    s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4 *)(p));
-    s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4 *)(p + 4 * 64));      // rows +4: same swizzle
-    typedef short s16x8_t __attribute__((ext_vector_type(8)));
-    s16x8_t both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-    return __builtin_bit_cast(bf16x8_t, both);
-}
-
 constexpr int UH = 8, UW = 16, UPIX = UH * UW;                 // unit of 8 x 16 pixels
 constexpr int WH_ROWS = UH + 2, WH_COLS = UW + 2, WH_PIX = WH_ROWS * WH_COLS;      // 10 x 18 halo = 180 pixels
 constexpr int WG_DY_ELEMS = UPIX * 64;                         // 16 KB
@@ -280,7 +243,7 @@ constexpr int WG_HL = 6, WG_DL = 4;                            // wave-loads per
 __global__ __launch_bounds__(256, 2) void k_wgrad3x3_halo(const bf16_t *__restrict__ x, const bf16_t *__restrict__ dy,
                                                           float *__restrict__ part, int N, int H, int W, int C,
                                                           int K, int units_per_split, unsigned x_bytes,
-                                                          unsigned dy_bytes)
+                                                          unsigned dy_bytes, int with_bias)
 {
     constexpr unsigned OOB = 0x80000000u;
     constexpr int NW = 4;
@@ -309,7 +272,7 @@ __global__ __launch_bounds__(256, 2) void k_wgrad3x3_halo(const bf16_t *__restri
     for (int i = 0; i < WG_HL; ++i) {
         const int slot = (i * NW + wave) * 64 + lane;
         const int hr = slot >> 3, cq = slot & 7;
-        const int c = ((((cq >> 1) ^ wg_swz64(hr)) << 1) | (cq & 1));
+        const int c = ((((cq >> 1) ^ wg_swz<64>(hr)) << 1) | (cq & 1));
         const int hy = hr / WH_COLS, hx = hr - hy * WH_COLS;
         hdy[i] = hr < WH_PIX ? hy - 1 : -(1 << 20);
         hdx[i] = hx - 1;
@@ -321,7 +284,7 @@ __global__ __launch_bounds__(256, 2) void k_wgrad3x3_halo(const bf16_t *__restri
     for (int i = 0; i < WG_DL; ++i) {
         const int slot = (i * NW + wave) * 64 + lane;
         const int px = slot >> 3, cq = slot & 7;
-        const int c = ((((cq >> 1) ^ wg_swz64(px)) << 1) | (cq & 1));
+        const int c = ((((cq >> 1) ^ wg_swz<64>(px)) << 1) | (cq & 1));
         ddy[i] = px >> 4;
         ddx[i] = px & 15;
         dco[i] = (unsigned)(ko0 + c * 8) * 2u;
@@ -353,6 +316,11 @@ __global__ __launch_bounds__(256, 2) void k_wgrad3x3_halo(const bf16_t *__restri
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[b][v] = 0.0f;
 
+    // bias gradient = column sums of dy: the waves that hold the dy fragments of input-channel slice 0
+    // add up their fragment values on the side (lane -> output channel, 8 pixels per step)
+    const bool do_bias = with_bias && cs == 0 && wn == 0;
+    float bsum = 0.0f;
+
     issue_unit(u0, 0);
     for (int u = u0; u < u1; ++u) {
         const int st = (u - u0) & 1;
@@ -362,22 +330,28 @@ __global__ __launch_bounds__(256, 2) void k_wgrad3x3_halo(const bf16_t *__restri
         const uint16_t *sd = stage0 + st * WG_STAGE_ELEMS, *sh = sd + WG_DY_ELEMS;
 #pragma unroll 2
         for (int y = 0; y < UH; ++y) {                               // one k16 step = one row of 16 pixels
-            const bf16x8_t fa = tr_frag64(sd, wk * 32, y * 16, lane);
+            const bf16x8_t fa = tr_frag<64>(sd, wk * 32, y * 16, lane);
+            if (do_bias) bsum = frag_sum(fa, bsum);
 #pragma unroll
             for (int b = 0; b < 9; ++b) {
                 const int ct = wn * 9 + b, tap = ct >> 1;
                 const int r = tap / 3, s = tap - r * 3;
-                const bf16x8_t fb = tr_frag64(sh, (ct & 1) * 32, (y + r) * WH_COLS + s, lane);
+                const bf16x8_t fb = tr_frag<64>(sh, (ct & 1) * 32, (y + r) * WH_COLS + s, lane);
                 acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa, fb, acc[b], 0, 0, 0);
             }
         }
     }
     WAIT_VMCNT(0);
 
-    // partial[split][ko][tap][c]: a wave writes 32 consecutive c (128 bytes) per row
-    const size_t total = (size_t)K * 9 * C;
-    float *dst = part + (size_t)blockIdx.y * total;
+    // partial[split][ko][tap][c] followed by the bias partial [split][ko]: a wave writes 32 consecutive
+    // c (128 bytes) per row
+    const size_t total_w = (size_t)K * 9 * C;
+    float *dst = part + (size_t)blockIdx.y * (total_w + (with_bias ? K : 0));
     const int col = lane & 31, half = lane >> 5;
+    if (do_bias) {
+        bsum += __shfl_xor(bsum, 32, 64);
+        if (half == 0) dst[total_w + ko0 + wk * 32 + col] = bsum;
+    }
 #pragma unroll
     for (int b = 0; b < 9; ++b) {
         const int ct = wn * 9 + b, tap = ct >> 1;
@@ -390,7 +364,10 @@ __global__ __launch_bounds__(256, 2) void k_wgrad3x3_halo(const bf16_t *__restri
     }
 }
 
-__global__ void k_wg_halo_reduce(const float *__restrict__ part, float *dw, size_t total, int splits)
+// dw[i] += sum_k part[k][i] for i < total_w, db[i - total_w] += ... for the bias tail (total_w and
+// total are multiples of 4); split lanes are combined through LDS in a fixed order.
+__global__ void k_wg_halo_reduce(const float *__restrict__ part, float *dw, float *db, size_t total_w, size_t total,
+                                 int splits)
 {
     __shared__ float4 red[4][64];
     const int col = threadIdx.x & 63, sl = threadIdx.x >> 6;
@@ -406,13 +383,14 @@ __global__ void k_wg_halo_reduce(const float *__restrict__ part, float *dw, size
     red[sl][col] = acc;
     __syncthreads();
     if (sl == 0 && i < total) {
-        float4 d = *reinterpret_cast<float4 *>(dw + i);
+        float *out = i < total_w ? dw + i : db + (i - total_w);
+        float4 d = *reinterpret_cast<float4 *>(out);
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
             float4 v = red[k][col];
             d.x += v.x; d.y += v.y; d.z += v.z; d.w += v.w;
         }
-        *reinterpret_cast<float4 *>(dw + i) = d;
+        *reinterpret_cast<float4 *>(out) = d;
     }
 }
 
@@ -464,11 +442,11 @@ bool wgrad3x3_halo_supported(const ConvShape &c)
 
 size_t wgrad3x3_halo_workspace(const ConvShape &c)
 {
-    return (size_t)wg_halo_plan(c).splits * c.K * 9 * c.C * sizeof(float);
+    return (size_t)wg_halo_plan(c).splits * ((size_t)c.K * 9 * c.C + c.K) * sizeof(float);
 }
 
-hipError_t wgrad3x3_halo_mfma(const void *x, const void *dy, float *dw, void *workspace, const ConvShape &c,
-                              hipStream_t s)
+hipError_t wgrad3x3_halo_mfma(const void *x, const void *dy, float *dw, float *db, void *workspace,
+                              const ConvShape &c, hipStream_t s)
 {
     if (!wgrad3x3_halo_supported(c)) return hipErrorInvalidValue;
     const WgHaloPlan p = wg_halo_plan(c);
@@ -485,10 +463,10 @@ hipError_t wgrad3x3_halo_mfma(const void *x, const void *dy, float *dw, void *wo
     float *part = (float *)workspace;
     hipLaunchKernelGGL(k_wgrad3x3_halo, dim3((unsigned)p.tiles, (unsigned)p.splits), dim3(256), smem, s,
                        (const bf16_t *)x, (const bf16_t *)dy, part, c.N, c.H, c.W, c.C, c.K, p.units_per_split,
-                       x_bytes, dy_bytes);
-    const size_t total = (size_t)c.K * 9 * c.C;
-    hipLaunchKernelGGL(k_wg_halo_reduce, dim3((unsigned)((total / 4 + 63) / 64)), dim3(256), 0, s, part, dw, total,
-                       p.splits);
+                       x_bytes, dy_bytes, db ? 1 : 0);
+    const size_t total_w = (size_t)c.K * 9 * c.C, total = total_w + (db ? c.K : 0);
+    hipLaunchKernelGGL(k_wg_halo_reduce, dim3((unsigned)((total / 4 + 63) / 64)), dim3(256), 0, s, part, dw, db,
+                       total_w, total, p.splits);
     return hipGetLastError();
 }
 

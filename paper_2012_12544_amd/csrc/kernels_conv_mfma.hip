@@ -20,29 +20,11 @@
 // CDNA4 transposing LDS read (ds_read_b64_tr_b16), which hands each lane 4 consecutive
 // pixels of one channel.  The pixel range is split over blocks (split-K); partial sums go to
 // a workspace and a second kernel adds them in a fixed order into the fp32 accumulators.
-#include "dev_common.h"
 #include "kernels.h"
+#include "mfma_common.h"
 
 namespace bapipe {
 namespace {
-
-typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
-typedef short s16x4_t __attribute__((ext_vector_type(4)));
-typedef float f32x16_t __attribute__((ext_vector_type(16)));
-
-typedef uint32_t chunk16 __attribute__((ext_vector_type(4)));   // 8 bf16, one 16-byte access
-typedef uint32_t chunk8 __attribute__((ext_vector_type(2)));
-
-__device__ __forceinline__ bf16x8_t as_frag(chunk16 c) { return __builtin_bit_cast(bf16x8_t, c); }
-
-// XCD-aware block order: hardware deals consecutive block ids round-robin to the 8 XCDs
-// (each with its own L2).  Re-number so that every XCD walks one contiguous range of tiles
-// and the blocks that share an input tile run on the same L2.
-__device__ __forceinline__ int xcd_remap(int id, int nb)
-{
-    const int x = id & 7, q = nb >> 3, rem = nb & 7;
-    return x * q + (x < rem ? x : rem) + (id >> 3);
-}
 
 template <int BK> __device__ __forceinline__ int swz(int row)
 {
@@ -53,11 +35,6 @@ template <int BK> __device__ __forceinline__ int swz(int row)
 // ------------------------------------------------------------------------------------------
 // gather convolution
 // ------------------------------------------------------------------------------------------
-typedef __attribute__((address_space(3))) void lds_void_t;
-
-// s_waitcnt with only the vector-memory counter set: wait until at most n loads are in flight
-#define WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(0x0F70 | ((n) & 15) | (((n) >> 4) << 14))
-
 // The operand tiles travel HBM/L2 -> LDS without touching registers: buffer_load_dwordx4 ... lds
 // writes the 64 lanes' 16-byte chunks to 64 consecutive LDS slots starting at a wave-uniform
 // address, and a lane whose offset is outside the buffer gets zeros (that is the zero padding of
@@ -432,36 +409,6 @@ hipError_t launch_gather(const void *in, const void *wt, const float *bias, void
 // ------------------------------------------------------------------------------------------
 // wgrad
 // ------------------------------------------------------------------------------------------
-// LDS tile [32 pixels][CH channels], rows unpadded (they are filled by buffer_load ... lds, whose
-// lanes land in consecutive 16-byte slots).  One 16-lane group of a transposing read touches 4
-// consecutive pixel rows x 32 bytes; the 32-byte pair index inside a row is XORed with a function of
-// the row so that the 32 lanes served together hit 8 different 32-byte bank groups.
-template <int CH> __device__ __forceinline__ int wg_swz(int row)
-{
-    constexpr int PPR = CH / 16;                      // 32-byte pairs per row
-    constexpr int RPS = PPR >= 8 ? 1 : 8 / PPR;       // rows per 256-byte bank sweep
-    return (2 * ((row / RPS) & 3)) & (PPR - 1);
-}
-
-// fragment for v_mfma_f32_32x32x16_bf16 out of a [pixel][channel] LDS tile:
-// lane -> channel ch0 + (lane & 31), pixels k0 + 8*(lane >> 5) .. +7  (two transposing reads)
-template <int CH>
-__device__ __forceinline__ bf16x8_t tr_frag(const uint16_t *tile, int ch0, int k0, int lane)
-{
-    const int blk = lane >> 4, sl = lane & 15;
-    const int row = k0 + 8 * (blk >> 1) + (sl >> 2);
-    const int col = ch0 + 16 * (blk & 1) + 4 * (sl & 3);
-    const int chunk = col >> 3;
-    const int sw = (((chunk >> 1) ^ wg_swz<CH>(row)) << 1) | (chunk & 1);
-    const uint16_t *p = tile + row * CH + (sw << 3) + (col & 7);
-    typedef __attribute__((address_space(3))) s16x4_t lds_v4;
-    s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4 *)(p));
-    s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4 *)(p + 4 * CH));     // rows +4: same swizzle
-    typedef short s16x8_t __attribute__((ext_vector_type(8)));
-    s16x8_t both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-    return __builtin_bit_cast(bf16x8_t, both);
-}
-
 // The GEMM's N index is the flattened (r, s, c) filter position n = (r*S + s)*C + c, so a tile
 // of BCI columns covers one tap (or part of it) when C >= BCI and several taps when C is small.
 // grid: x = (ko tile, n tile) ; y = split over pixel chunks.  Same HBM -> LDS ring as the gather
@@ -469,9 +416,10 @@ __device__ __forceinline__ bf16x8_t tr_frag(const uint16_t *tile, int ch0, int k
 template <int BKO, int BCI, int WKO, int WCI, int STAGES>
 __global__ __launch_bounds__(WKO *WCI * 64, 2) void k_wgrad_mfma(const bf16_t *__restrict__ x,
                                                                   const bf16_t *__restrict__ dy,
-                                                                  float *part, ConvShape c, int tiles_n,
-                                                                  int pix_per_split, int add_to_dst,
-                                                                  unsigned x_bytes, unsigned dy_bytes)
+                                                                  float *part, float *bpart, size_t split_stride,
+                                                                  ConvShape c, int tiles_n, int pix_per_split,
+                                                                  int add_to_dst, unsigned x_bytes,
+                                                                  unsigned dy_bytes)
 {
     constexpr int BKP = 32;
     constexpr int NW = WKO * WCI;
@@ -569,6 +517,13 @@ __global__ __launch_bounds__(WKO *WCI * 64, 2) void k_wgrad_mfma(const bf16_t *_
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.0f;
 
+    // bias gradient = column sums of dy: the waves holding the dy fragments of filter-column tile 0
+    // add up their fragment values on the side (lane -> output channel, 8 pixels per step)
+    const bool do_bias = bpart != nullptr && tn == 0 && wi == 0;
+    float bsum[TA];
+#pragma unroll
+    for (int a = 0; a < TA; ++a) bsum[a] = 0.0f;
+
     auto compute_tile = [&](int stage) {
         const uint16_t *sa = ring + stage * STAGE_ELEMS, *sb = sa + BKP * BKO;
 #pragma unroll
@@ -576,6 +531,10 @@ __global__ __launch_bounds__(WKO *WCI * 64, 2) void k_wgrad_mfma(const bf16_t *_
             bf16x8_t fa[TA], fb[TB];
 #pragma unroll
             for (int a = 0; a < TA; ++a) fa[a] = tr_frag<BKO>(sa, wk * WT_KO + a * 32, k0, lane);
+            if (do_bias) {
+#pragma unroll
+                for (int a = 0; a < TA; ++a) bsum[a] = frag_sum(fa[a], bsum[a]);
+            }
 #pragma unroll
             for (int b = 0; b < TB; ++b) fb[b] = tr_frag<BCI>(sb, wi * WT_CI + b * 32, k0, lane);
 #pragma unroll
@@ -601,9 +560,17 @@ __global__ __launch_bounds__(WKO *WCI * 64, 2) void k_wgrad_mfma(const bf16_t *_
     WAIT_VMCNT(0);
 
     // partial[split][ko][n]: lanes of a wave write 32 consecutive n (128 bytes)
-    const size_t total = (size_t)c.K * Ntot;
-    float *dst = part + (size_t)blockIdx.y * total;
+    float *dst = part + (size_t)blockIdx.y * split_stride;
     const int col = lane & 31, half = lane >> 5;
+    if (do_bias) {
+        float *bdst = bpart + (size_t)blockIdx.y * split_stride;
+#pragma unroll
+        for (int a = 0; a < TA; ++a) {
+            const float t = bsum[a] + __shfl_xor(bsum[a], 32, 64);
+            const int ko = ko0 + wk * WT_KO + a * 32 + col;
+            if (half == 0 && ko < c.K) bdst[ko] = add_to_dst ? bdst[ko] + t : t;
+        }
+    }
 #pragma unroll
     for (int a = 0; a < TA; ++a)
 #pragma unroll
@@ -622,8 +589,10 @@ __global__ __launch_bounds__(WKO *WCI * 64, 2) void k_wgrad_mfma(const bf16_t *_
 
 // dw[i] += sum_k part[k][i].  A block owns 64 float4 columns; its 4 split-lanes walk the partials
 // with stride 4 and are combined through LDS in lane order (the result does not depend on timing).
-// total is a multiple of 4 (channel counts are multiples of 8).
-__global__ void k_splitk_reduce(const float *__restrict__ part, float *dw, size_t total, int splits)
+// Entries past total_w are the bias partials and go to db.  total_w and total are multiples of 4
+// (channel counts are multiples of 8).
+__global__ void k_splitk_reduce(const float *__restrict__ part, float *dw, float *db, size_t total_w, size_t total,
+                                int splits)
 {
     __shared__ float4 red[4][64];
     const int col = threadIdx.x & 63, sl = threadIdx.x >> 6;
@@ -639,13 +608,14 @@ __global__ void k_splitk_reduce(const float *__restrict__ part, float *dw, size_
     red[sl][col] = acc;
     __syncthreads();
     if (sl == 0 && i < total) {
-        float4 d = *reinterpret_cast<float4 *>(dw + i);
+        float *out = i < total_w ? dw + i : db + (i - total_w);
+        float4 d = *reinterpret_cast<float4 *>(out);
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
             float4 v = red[k][col];
             d.x += v.x; d.y += v.y; d.z += v.z; d.w += v.w;
         }
-        *reinterpret_cast<float4 *>(dw + i) = d;
+        *reinterpret_cast<float4 *>(out) = d;
     }
 }
 
@@ -718,19 +688,21 @@ size_t conv_wgrad_mfma_workspace(const ConvShape &c)
 {
     if (wgrad3x3_halo_supported(c)) return wgrad3x3_halo_workspace(c);
     WgradPlan p = wgrad_plan(c);
-    return p.splits == 1 ? 0 : (size_t)p.splits * c.K * c.R * c.S * c.C * sizeof(float);
+    return p.splits == 1 ? 0 : (size_t)p.splits * ((size_t)c.K * c.R * c.S * c.C + c.K) * sizeof(float);
 }
 
-hipError_t conv_wgrad_mfma(const void *x, const void *dy, float *dw, void *workspace, const ConvShape &c,
-                           hipStream_t s)
+hipError_t conv_wgrad_mfma(const void *x, const void *dy, float *dw, float *db, void *workspace,
+                           const ConvShape &c, hipStream_t s)
 {
     if (!conv_wgrad_mfma_supported(c)) return hipErrorInvalidValue;
     if ((long long)c.N * c.P * c.Q == 0) return hipSuccess;
-    if (wgrad3x3_halo_supported(c)) return wgrad3x3_halo_mfma(x, dy, dw, workspace, c, s);
+    if (wgrad3x3_halo_supported(c)) return wgrad3x3_halo_mfma(x, dy, dw, db, workspace, c, s);
     WgradPlan p = wgrad_plan(c);
     dim3 grid((unsigned)(p.tiles_ko * p.tiles_n), (unsigned)p.splits);
     const int direct = p.splits == 1;
+    const size_t total_w = (size_t)c.K * c.R * c.S * c.C, total = total_w + (db ? c.K : 0);
     float *part = direct ? dw : (float *)workspace;
+    float *bpart = !db ? nullptr : (direct ? db : part + total_w);
 #define WG_LAUNCH(BKO_, BCI_, WKO_, WCI_)                                                                  \
     do {                                                                                                   \
         constexpr size_t smem = (size_t)3 * 32 * (BKO_ + BCI_) * 2;                                        \
@@ -741,8 +713,8 @@ hipError_t conv_wgrad_mfma(const void *x, const void *dy, float *dw, void *works
             if (e != hipSuccess) return e;                                                                 \
             attr_set = true;                                                                               \
         }                                                                                                  \
-        hipLaunchKernelGGL(kfn, grid, dim3(WKO_ * WCI_ * 64), smem, s, (const bf16_t *)x, (const bf16_t *)dy, part, c, \
-                           p.tiles_n, p.pix_per_split, direct, x_bytes, dy_bytes);                         \
+        hipLaunchKernelGGL(kfn, grid, dim3(WKO_ * WCI_ * 64), smem, s, (const bf16_t *)x, (const bf16_t *)dy, part, bpart, \
+                           total, c, p.tiles_n, p.pix_per_split, direct, x_bytes, dy_bytes);               \
     } while (0)
     const unsigned x_bytes = (unsigned)((size_t)c.N * c.H * c.W * c.C * 2);
     const unsigned dy_bytes = (unsigned)((size_t)c.N * c.P * c.Q * c.K * 2);
@@ -757,10 +729,9 @@ hipError_t conv_wgrad_mfma(const void *x, const void *dy, float *dw, void *works
     else
         WG_LAUNCH(64, 64, 2, 2);
 #undef WG_LAUNCH
-    size_t total = (size_t)c.K * c.R * c.S * c.C;
     if (!direct)
         hipLaunchKernelGGL(k_splitk_reduce, dim3((unsigned)((total / 4 + 63) / 64)), dim3(256), 0, s, part,
-                           dw, total, p.splits);
+                           dw, db, total_w, total, p.splits);
     return hipGetLastError();
 }
 

@@ -402,6 +402,7 @@ int layer_backward(bapipe_stage *st, int li, BwdCtx &c)
         const void *x = st->tptr(L.a, c.mbid);
         ConvShape cs = conv_shape(st, L);
         const double flop = conv_flop(fwd_geom(st, L), L.d.cin);
+        bool bias_done = false;
         if (L.deferred && !c.profiling) {
             HIPCHK(hipMemcpyAsync(L.def_x + (size_t)c.mbid * L.def_x_bytes, x, L.def_x_bytes, hipMemcpyDeviceToDevice, s));
             HIPCHK(hipMemcpyAsync(L.def_g + (size_t)c.mbid * L.def_g_bytes, g, L.def_g_bytes, hipMemcpyDeviceToDevice, s));
@@ -409,12 +410,13 @@ int layer_backward(bapipe_stage *st, int li, BwdCtx &c)
             const bool mf = use_mfma_wgrad(st, cs);
             const bool tp = st->tap_begin(mf ? BAPIPE_KC_CONV_WGRAD_MFMA : BAPIPE_KC_CONV_DIRECT);
             if (mf)
-                HIPCHK(conv_wgrad_mfma(x, g, L.dw, st->work, cs, s));
+                HIPCHK(conv_wgrad_mfma(x, g, L.dw, L.db, st->work, cs, s));      // bias gradient rides along
             else
                 HIPCHK(conv_wgrad_direct(dt, x, g, L.dw, st->work, cs, s));
             st->tap_end(tp, flop, 0.0);
+            bias_done = mf;
         }
-        if (L.db) {
+        if (L.db && !bias_done) {
             const bool tp = st->tap_begin(BAPIPE_KC_ELEMENTWISE);
             HIPCHK(colsum_accumulate(dt, g, cs.N * cs.P * cs.Q, cs.K, L.db, st->work, s));
             st->tap_end(tp, 0.0, (double)O.bytes());
@@ -508,7 +510,7 @@ int flush_deferred(bapipe_stage *st)
         const char *x = L.def_x + (size_t)st->flushed * L.def_x_bytes;
         const char *g = L.def_g + (size_t)st->flushed * L.def_g_bytes;
         const bool tp = st->tap_begin(BAPIPE_KC_CONV_WGRAD_MFMA);
-        HIPCHK(conv_wgrad_mfma(x, g, L.dw, st->work, cs, st->stream));
+        HIPCHK(conv_wgrad_mfma(x, g, L.dw, nullptr, st->work, cs, st->stream));
         st->tap_end(tp, conv_flop(fwd_geom(st, L), L.d.cin) * n, 0.0);
     }
     st->flushed = st->n_bwd;
