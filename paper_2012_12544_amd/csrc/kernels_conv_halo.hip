@@ -107,6 +107,24 @@ __global__ __launch_bounds__(256, 2) void k_conv3x3_halo(const bf16_t *__restric
     const int py = 4 * wave + (frow >> 4), px = frow & 15;       // patch pixel of B tile 0 (tile 1: py + 2)
 
     if (tid < BC) sBias[tid] = bias ? bias[co0 + tid] : 0.0f;          // read after the main loop's barriers
+
+    // gradient epilogue: the ReLU gate of the first GPRE output rows of this thread is requested now, so
+    // the loads complete under the halo wait instead of after the last MFMA
+    constexpr int CH8 = BC / 8;
+    constexpr int UNITS = 256 * CH8 / 256;
+    constexpr int GPRE = 8;
+    const chunk16 zero16 = {0u, 0u, 0u, 0u};
+    chunk16 gpre[GPRE];
+#pragma unroll
+    for (int it = 0; it < GPRE; ++it) {
+        gpre[it] = zero16;
+        if (gate) {
+            const int u = tid + it * 256;
+            const int pj = u / CH8, c8i = u % CH8;
+            const size_t p = (size_t)(n * H + Y0 + (pj >> 4)) * W + X0 + (pj & 15);
+            gpre[it] = *reinterpret_cast<const chunk16 *>(gate + p * Co + co0 + c8i * 8);
+        }
+    }
     issue_halo(0);
 #pragma unroll
     for (int st = 0; st < WSTAGES - 1; ++st) issue_w(st);
@@ -147,7 +165,6 @@ __global__ __launch_bounds__(256, 2) void k_conv3x3_halo(const bf16_t *__restric
 
     // ---- epilogue: every wave parks its 64 pixels x BC channels in LDS (bf16, bias / ReLU applied),
     // one barrier, then the block streams the patch out as 16-byte coalesced rows
-    const chunk16 zero16 = {0u, 0u, 0u, 0u};
 #pragma unroll
     for (int a = 0; a < TC; ++a) {
 #pragma unroll
@@ -173,8 +190,6 @@ __global__ __launch_bounds__(256, 2) void k_conv3x3_halo(const bf16_t *__restric
         }
     }
     __syncthreads();
-    constexpr int CH8 = BC / 8;
-    constexpr int UNITS = 256 * CH8 / 256;
 #pragma unroll
     for (int it = 0; it < UNITS; ++it) {
         const int u = tid + it * 256;
@@ -188,7 +203,10 @@ __global__ __launch_bounds__(256, 2) void k_conv3x3_halo(const bf16_t *__restric
         if (is_grad) {
             chunk16 old = zero16, gt = zero16, rr;
             if (accum) old = *reinterpret_cast<const chunk16 *>(dst);
-            if (gate) gt = *reinterpret_cast<const chunk16 *>(gate + p * Co + co);
+            if (it < GPRE)
+                gt = gpre[it];
+            else if (gate)
+                gt = *reinterpret_cast<const chunk16 *>(gate + p * Co + co);
 #pragma unroll
             for (int j = 0; j < 4; ++j) rr[j] = grad_epilogue_pair(v[j], old[j], gt[j], accum != 0, gate != nullptr);
             *reinterpret_cast<chunk16 *>(dst) = rr;
