@@ -88,11 +88,18 @@ __global__ __launch_bounds__(WP *WC * 64, 2) void k_gather_mfma(
     __amdgpu_buffer_rsrc_t wrsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t *>(wt), 0, (int)wt_bytes, 0x00020000);
 
     // ---- per-lane gather state: the pixel rows this lane fetches (row = (i*NW + wave)*RPW + lrow)
+    // FAST (stride 1, taps innermost, at most 32 taps): everything that depends on the lane is
+    // computed once - the byte offset of the lane's chunk at tap (0,0) and a bit mask of the taps
+    // that fall inside the image - so that a K-tile costs one scalar offset, one mask test and one
+    // add per load.
+    constexpr bool FAST = S1 && TAPS_INNER;
     int hb[XL], wb[XL];
-    unsigned xoff[XL];                       // byte offset of pixel (n, 0, 0), channel 0
+    unsigned xoff[XL];                       // generic: byte offset of pixel (n, 0, 0), channel 0; FAST: see above
+    unsigned tapmask[XL];
 #pragma unroll
     for (int i = 0; i < XL; ++i) {
         int p = pix0 + (i * NW + wave) * RPW + lrow;
+        tapmask[i] = 0;
         if (p < npix) {
             int ow = p % g.Wo;
             int t = p / g.Wo;
@@ -101,6 +108,13 @@ __global__ __launch_bounds__(WP *WC * 64, 2) void k_gather_mfma(
             hb[i] = oh * g.s_out - g.pad_h;
             wb[i] = ow * g.s_out - g.pad_w;
             xoff[i] = (unsigned)n * (unsigned)(g.Hi * g.Wi * g.Ci) * 2u;
+            if (FAST) {
+                for (int r = 0; r < g.R; ++r)
+                    for (int q = 0; q < g.S; ++q)
+                        if ((unsigned)(hb[i] + r) < (unsigned)g.Hi && (unsigned)(wb[i] + q) < (unsigned)g.Wi)
+                            tapmask[i] |= 1u << (r * g.S + q);
+                xoff[i] += (unsigned)((hb[i] * g.Wi + wb[i]) * g.Ci + 8 * lc) * 2u;     // may wrap; the tap offset undoes it
+            }
         } else {
             hb[i] = -(1 << 28);          // fails every bounds check below
             wb[i] = 0;
@@ -112,6 +126,7 @@ __global__ __launch_bounds__(WP *WC * 64, 2) void k_gather_mfma(
     for (int i = 0; i < WL; ++i) {
         int co = co0 + (i * NW + wave) * RPW + lrow;
         woff[i] = co < g.Co ? (unsigned)co * (unsigned)K * 2u : OOB;
+        if (FAST && co < g.Co) woff[i] += 16u * lc;
     }
     // K order.  TAPS_INNER (Ci a multiple of BK): tile kt covers channels [cit*BK, +BK) of tap
     // (kt % RS), taps innermost, so that consecutive tiles re-read almost the same pixels (shifted
@@ -121,15 +136,36 @@ __global__ __launch_bounds__(WP *WC * 64, 2) void k_gather_mfma(
     const int kt1 = part ? (kt0 + kt_per_split < KT ? kt0 + kt_per_split : KT) : KT;
     int kk = kt0 * BK + 8 * lc;                        // flattened k of this lane's chunk (generic order)
     int kr = kk / (g.S * g.Ci), ks = (kk / g.Ci) % g.S, kc = kk % g.Ci;
+    int cb = 0;                                        // FAST: first channel of the tile (wave-uniform)
     if (TAPS_INNER) {
         const int tap = kt0 % (g.R * g.S);
         kr = tap / g.S;
         ks = tap % g.S;
-        kc = (kt0 / (g.R * g.S)) * BK + 8 * lc;        // channel offset; tap = (kr, ks)
+        cb = (kt0 / (g.R * g.S)) * BK;
+        kc = cb + 8 * lc;                              // channel offset; tap = (kr, ks)
     }
 
     auto issue_tile = [&](int stage) {
         uint16_t *sw = ring + stage * STAGE_ELEMS, *sx = sw + BC * BK;
+        if constexpr (FAST) {
+            const bool kin = cb < g.Ci;
+            const int tap = kr * g.S + ks;
+            const unsigned bit = kin ? 1u << tap : 0u;
+            const unsigned xo = (unsigned)((kr * g.Wi + ks) * g.Ci + cb) * 2u;
+            const unsigned wo = kin ? (unsigned)(tap * g.Ci + cb) * 2u : OOB;
+#pragma unroll
+            for (int i = 0; i < XL; ++i) {
+                unsigned vo = (tapmask[i] & bit) ? xoff[i] + xo : OOB;
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(xrsrc, (lds_void_t *)(sx + (i * NW + wave) * RPW * BK), 16, (int)vo, 0, 0, 0);
+            }
+#pragma unroll
+            for (int i = 0; i < WL; ++i) {
+                unsigned vo = (woff[i] + wo) | (woff[i] & OOB);       // rows past Co stay out of range
+                if (!kin) vo = OOB;                                   // and so do tiles past K
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(wrsrc, (lds_void_t *)(sw + (i * NW + wave) * RPW * BK), 16, (int)vo, 0, 0, 0);
+            }
+            return;                                   // the caller advances (kr, ks, cb) after its MFMAs
+        }
         const bool kin = TAPS_INNER ? (kc < g.Ci) : (kr < g.R);
         const unsigned koff = (unsigned)(TAPS_INNER ? (kr * g.S + ks) * g.Ci + kc : kk) * 2u;
 #pragma unroll
@@ -175,6 +211,19 @@ __global__ __launch_bounds__(WP *WC * 64, 2) void k_gather_mfma(
             }
         }
     };
+    // FAST path: step (kr, ks, cb) to the next K-tile.  Kept apart from issue_tile so that the branchy
+    // scalar code does not split the block in which the MFMAs and the address arithmetic interleave.
+    auto advance_tile = [&]() {
+        if (FAST) {
+            if (++ks == g.S) {
+                ks = 0;
+                if (++kr == g.R) {
+                    kr = 0;
+                    cb += BK;
+                }
+            }
+        }
+    };
 
     f32x16_t acc[TC][TP];
 #pragma unroll
@@ -185,46 +234,68 @@ __global__ __launch_bounds__(WP *WC * 64, 2) void k_gather_mfma(
             for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.0f;
 
     const int frow = lane & 31, fhalf = lane >> 5;
-    auto compute_tile = [&](int stage) {
+    // operand fragments of K-sub-step ks16 of the tile in ring slot `stage`
+    auto load_frags = [&](int stage, int ks16, bf16x8_t(&fa)[TC], bf16x8_t(&fb)[TP]) {
         const uint16_t *cw = ring + stage * STAGE_ELEMS, *cx = cw + BC * BK;
+        const int ch = 2 * ks16 + fhalf;
 #pragma unroll
-        for (int ks16 = 0; ks16 < KSUB; ++ks16) {
-            const int ch = 2 * ks16 + fhalf;
-            bf16x8_t fa[TC], fb[TP];
-#pragma unroll
-            for (int a = 0; a < TC; ++a) {
-                int row = wc * WT_C + a * 32 + frow;
-                fa[a] = as_frag(*reinterpret_cast<const chunk16 *>(cw + row * BK + ((ch ^ swz<BK>(row)) << 3)));
-            }
-#pragma unroll
-            for (int b = 0; b < TP; ++b) {
-                int row = wp * WT_P + b * 32 + frow;
-                fb[b] = as_frag(*reinterpret_cast<const chunk16 *>(cx + row * BK + ((ch ^ swz<BK>(row)) << 3)));
-            }
-#pragma unroll
-            for (int a = 0; a < TC; ++a)
-#pragma unroll
-                for (int b = 0; b < TP; ++b)
-                    acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[a], fb[b], acc[a][b], 0, 0, 0);
+        for (int a = 0; a < TC; ++a) {
+            int row = wc * WT_C + a * 32 + frow;
+            fa[a] = as_frag(*reinterpret_cast<const chunk16 *>(cw + row * BK + ((ch ^ swz<BK>(row)) << 3)));
         }
+#pragma unroll
+        for (int b = 0; b < TP; ++b) {
+            int row = wp * WT_P + b * 32 + frow;
+            fb[b] = as_frag(*reinterpret_cast<const chunk16 *>(cx + row * BK + ((ch ^ swz<BK>(row)) << 3)));
+        }
+    };
+    auto mfma_all = [&](const bf16x8_t(&fa)[TC], const bf16x8_t(&fb)[TP]) {
+#pragma unroll
+        for (int a = 0; a < TC; ++a)
+#pragma unroll
+            for (int b = 0; b < TP; ++b)
+                acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[a], fb[b], acc[a][b], 0, 0, 0);
     };
 
     // the block's bias slice goes to LDS now; it is read after the barriers of the main loop
     if (tid < BC) sBias[tid] = (bias && co0 + tid < g.Co) ? bias[co0 + tid] : 0.0f;
 
-    // every iteration requests exactly XL+WL loads per wave (tiles past the end fetch zeros into a
-    // stage nobody reads), so "at most (STAGES-2)*(XL+WL) in flight" means tile kt has landed
+    // Software pipeline.  The ring holds STAGES tiles in flight or in use; every iteration requests
+    // exactly XL+WL loads per wave (tiles past the end fetch zeros nobody multiplies), so "at most
+    // (STAGES-2)*(XL+WL) outstanding" means the next tile has landed.  Fragments are double-buffered
+    // in registers: the LDS reads of a sub-step are issued one sub-step (one group of MFMAs) before
+    // they are needed, and the barrier that publishes tile kt+1 sits between the two MFMA groups of
+    // tile kt.  By then every wave holds all of tile kt in registers, so its slot is refilled at once.
+    // sched_barrier pins that order: left alone the scheduler sinks the reads next to their MFMAs.
+    static_assert(KSUB == 2, "pipeline below is written for two sub-steps per tile");
     constexpr int NLOAD = XL + WL;
 #pragma unroll
-    for (int st = 0; st < STAGES - 1; ++st) issue_tile(st);
-    int rd = 0, wr = STAGES - 1;
+    for (int st = 0; st < STAGES; ++st) {
+        issue_tile(st);
+        advance_tile();
+    }
+    WAIT_VMCNT((STAGES - 1) * NLOAD);
+    WAIT_LGKMCNT(0);       // no scalar load may be pending at loop entry, or every LDS wait in the loop becomes a full drain
+    __builtin_amdgcn_s_barrier();
+    bf16x8_t fa0[TC], fb0[TP], fa1[TC], fb1[TP];
+    load_frags(0, 0, fa0, fb0);
+    int rd = 0;
     for (int kt = kt0; kt < kt1; ++kt) {
-        WAIT_VMCNT((STAGES - 2) * NLOAD);
+        const int nx = rd + 1 == STAGES ? 0 : rd + 1;
+        load_frags(rd, 1, fa1, fb1);
+        __builtin_amdgcn_sched_barrier(0);            // keep the reads ahead of the MFMAs that hide them
+        mfma_all(fa0, fb0);
+        __builtin_amdgcn_sched_barrier(0);
+        WAIT_LGKMCNT(0);                              // this wave has read all of tile kt
+        WAIT_VMCNT((STAGES - 2) * NLOAD);             // its share of tile kt+1 has landed
         __builtin_amdgcn_s_barrier();
-        issue_tile(wr);
-        compute_tile(rd);
-        rd = rd + 1 == STAGES ? 0 : rd + 1;
-        wr = wr + 1 == STAGES ? 0 : wr + 1;
+        load_frags(nx, 0, fa0, fb0);
+        __builtin_amdgcn_sched_barrier(0);
+        issue_tile(rd);                               // tile kt+STAGES into the slot just retired; its address
+        mfma_all(fa1, fb1);                           // arithmetic is free to mix with these MFMAs
+        __builtin_amdgcn_sched_barrier(0);
+        advance_tile();
+        rd = nx;
     }
     WAIT_VMCNT(0);
     __syncthreads();
@@ -388,7 +459,7 @@ hipError_t launch_gather(const void *in, const void *wt, const float *bias, void
                            (bf16_t *)out, (const bf16_t *)epi.gate, epi.accum, relu, is_grad, g, tiles_c, in_bytes, \
                            wt_bytes, part, plan.kt_per_split);                                                    \
     } while (0)
-    const bool taps_inner = g.Ci % BK == 0;
+    const bool taps_inner = g.Ci % BK == 0 && g.R * g.S <= 32;      // the stride-1 variant keeps a 32-bit tap mask
     if (g.s_in == 1) {
         if (taps_inner) GATHER_LAUNCH(true, true);
         else GATHER_LAUNCH(true, false);
@@ -634,11 +705,24 @@ WgradPlan wgrad_plan(const ConvShape &c)
     p.tiles_n = (Ntot + p.bci - 1) / p.bci;
     long long npix = (long long)c.N * c.P * c.Q;
     long long tiles = (long long)p.tiles_ko * p.tiles_n;
-    long long want = (1024 + tiles - 1) / tiles;          // ~4 blocks per CU
-    long long max_by_work = (npix + 511) / 512;             // at least 512 pixels per split
-    if (want > max_by_work) want = max_by_work;
-    if (want < 1) want = 1;
-    if (want > 256) want = 256;
+    // Split count: the chip holds 512 blocks at once (256 CUs x 2), and a launch whose block count is
+    // just above a multiple of that leaves most CUs idle during the last blocks.  Take the split count
+    // whose block count fills whole rounds best, less the relative cost of its partials (every split
+    // writes and re-reads a full fp32 copy of dw: about 500/npix of the MFMA time each); at least 512
+    // pixels per split.
+    long long max_by_work = (npix + 511) / 512;
+    if (max_by_work > 256) max_by_work = 256;
+    if (max_by_work < 1) max_by_work = 1;
+    long long want = 1;
+    double best = -1.0;
+    for (long long sp = 1; sp <= max_by_work; ++sp) {
+        const long long blocks = tiles * sp, rounds = (blocks + 511) / 512;
+        const double score = (double)blocks / (double)(rounds * 512) - 500.0 * (double)sp / (double)npix;
+        if (score > best) {
+            best = score;
+            want = sp;
+        }
+    }
     long long pps = (npix + want - 1) / want;
     pps = (pps + 31) / 32 * 32;
     if (pps < 32) pps = 32;

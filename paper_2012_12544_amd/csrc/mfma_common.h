@@ -14,6 +14,8 @@ typedef __attribute__((address_space(3))) void lds_void_t;
 
 // s_waitcnt with only the vector-memory counter set: wait until at most n loads are in flight
 #define WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(0x0F70 | ((n) & 15) | (((n) >> 4) << 14))
+// ... with only the LDS / scalar-memory counter set
+#define WAIT_LGKMCNT(n) __builtin_amdgcn_s_waitcnt(0xC07F | ((n) << 8))
 
 __device__ __forceinline__ bf16x8_t as_frag(chunk16 c) { return __builtin_bit_cast(bf16x8_t, c); }
 
