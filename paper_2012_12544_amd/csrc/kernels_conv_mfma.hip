@@ -560,7 +560,6 @@ __global__ __launch_bounds__(WKO *WCI * 64, 2) void k_wgrad_mfma(const bf16_t *_
         for (int i = 0; i < AL; ++i) {
             unsigned vo = (ap[i] < p_end && akoff[i] >= 0) ? ((unsigned)ap[i] * (unsigned)c.K + (unsigned)akoff[i]) * 2u : OOB;
             __builtin_amdgcn_raw_ptr_buffer_load_lds(grsrc, (lds_void_t *)(sa + (i * NW + wave) * 512), 16, (int)vo, 0, 0, 0);
-            ap[i] += BKP;
         }
 #pragma unroll
         for (int i = 0; i < BL; ++i) {
@@ -568,6 +567,15 @@ __global__ __launch_bounds__(WKO *WCI * 64, 2) void k_wgrad_mfma(const bf16_t *_
             const bool ok = bp[i] < p_end && bc[i] >= 0 && (unsigned)ih < (unsigned)c.H && (unsigned)iw < (unsigned)c.W;
             unsigned vo = ok ? (unsigned)(((bn[i] * c.H + ih) * c.W + iw) * c.C + bc[i]) * 2u : OOB;
             __builtin_amdgcn_raw_ptr_buffer_load_lds(xrsrc, (lds_void_t *)(sb + (i * NW + wave) * 512), 16, (int)vo, 0, 0, 0);
+        }
+    };
+    // step the per-lane pixel state to the next tile (kept out of issue_tile: its loops would split
+    // the block in which the loads' address arithmetic interleaves with the MFMAs)
+    auto advance_tile = [&]() {
+#pragma unroll
+        for (int i = 0; i < AL; ++i) ap[i] += BKP;
+#pragma unroll
+        for (int i = 0; i < BL; ++i) {
             bp[i] += BKP;
             bq[i] += BKP;
             while (bq[i] >= c.Q) {
@@ -595,38 +603,55 @@ __global__ __launch_bounds__(WKO *WCI * 64, 2) void k_wgrad_mfma(const bf16_t *_
 #pragma unroll
     for (int a = 0; a < TA; ++a) bsum[a] = 0.0f;
 
-    auto compute_tile = [&](int stage) {
+    auto load_frags = [&](int stage, int k0, bf16x8_t(&fa)[TA], bf16x8_t(&fb)[TB]) {
         const uint16_t *sa = ring + stage * STAGE_ELEMS, *sb = sa + BKP * BKO;
 #pragma unroll
-        for (int k0 = 0; k0 < BKP; k0 += 16) {
-            bf16x8_t fa[TA], fb[TB];
+        for (int a = 0; a < TA; ++a) fa[a] = tr_frag<BKO>(sa, wk * WT_KO + a * 32, k0, lane);
 #pragma unroll
-            for (int a = 0; a < TA; ++a) fa[a] = tr_frag<BKO>(sa, wk * WT_KO + a * 32, k0, lane);
-            if (do_bias) {
+        for (int b = 0; b < TB; ++b) fb[b] = tr_frag<BCI>(sb, wi * WT_CI + b * 32, k0, lane);
+    };
+    auto mfma_all = [&](const bf16x8_t(&fa)[TA], const bf16x8_t(&fb)[TB]) {
+        if (do_bias) {
 #pragma unroll
-                for (int a = 0; a < TA; ++a) bsum[a] = frag_sum(fa[a], bsum[a]);
-            }
-#pragma unroll
-            for (int b = 0; b < TB; ++b) fb[b] = tr_frag<BCI>(sb, wi * WT_CI + b * 32, k0, lane);
-#pragma unroll
-            for (int a = 0; a < TA; ++a)
-#pragma unroll
-                for (int b = 0; b < TB; ++b)
-                    acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[a], fb[b], acc[a][b], 0, 0, 0);
+            for (int a = 0; a < TA; ++a) bsum[a] = frag_sum(fa[a], bsum[a]);
         }
+#pragma unroll
+        for (int a = 0; a < TA; ++a)
+#pragma unroll
+            for (int b = 0; b < TB; ++b)
+                acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[a], fb[b], acc[a][b], 0, 0, 0);
     };
 
+    // Same software pipeline as the gather kernel: STAGES tiles in the ring, fragments double-buffered
+    // in registers, the barrier that publishes tile kt+1 between the two MFMA groups of tile kt.
     constexpr int NLOAD = AL + BL;
 #pragma unroll
-    for (int st = 0; st < STAGES - 1; ++st) issue_tile(st);
-    int rd = 0, wr = STAGES - 1;
+    for (int st = 0; st < STAGES; ++st) {
+        issue_tile(st);
+        advance_tile();
+    }
+    WAIT_VMCNT((STAGES - 1) * NLOAD);
+    WAIT_LGKMCNT(0);
+    __builtin_amdgcn_s_barrier();
+    bf16x8_t fa0[TA], fb0[TB], fa1[TA], fb1[TB];
+    load_frags(0, 0, fa0, fb0);
+    int rd = 0;
     for (int kt = 0; kt < KT; ++kt) {
+        const int nx = rd + 1 == STAGES ? 0 : rd + 1;
+        load_frags(rd, 16, fa1, fb1);
+        __builtin_amdgcn_sched_barrier(0);
+        mfma_all(fa0, fb0);
+        __builtin_amdgcn_sched_barrier(0);
+        WAIT_LGKMCNT(0);
         WAIT_VMCNT((STAGES - 2) * NLOAD);
         __builtin_amdgcn_s_barrier();
-        issue_tile(wr);
-        compute_tile(rd);
-        rd = rd + 1 == STAGES ? 0 : rd + 1;
-        wr = wr + 1 == STAGES ? 0 : wr + 1;
+        load_frags(nx, 0, fa0, fb0);
+        __builtin_amdgcn_sched_barrier(0);
+        issue_tile(rd);
+        mfma_all(fa1, fb1);
+        __builtin_amdgcn_sched_barrier(0);
+        advance_tile();
+        rd = nx;
     }
     WAIT_VMCNT(0);
 
