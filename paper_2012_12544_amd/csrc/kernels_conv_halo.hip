@@ -39,6 +39,7 @@ __global__ __launch_bounds__(256, 2) void k_conv3x3_halo(const bf16_t *__restric
     constexpr unsigned OOB = 0x80000000u;
 
     extern __shared__ __align__(16) unsigned char smem[];
+    const lds_addr_of lds_of(smem);
     uint16_t *halo = reinterpret_cast<uint16_t *>(smem);
     uint16_t *wring = halo + HALO_ELEMS;
     uint16_t *sO = reinterpret_cast<uint16_t *>(smem);                                   // [256][SROW] (epilogue)
@@ -82,7 +83,7 @@ __global__ __launch_bounds__(256, 2) void k_conv3x3_halo(const bf16_t *__restric
 #pragma unroll
         for (int i = 0; i < HL; ++i) {
             unsigned vo = hoff[i] == OOB ? OOB : hoff[i] + (unsigned)slice * 128u;
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(xrsrc, (lds_void_t *)(halo + (i * NW + wave) * 512), 16, (int)vo, 0, 0, 0);
+            dma16(xrsrc, lds_of(halo + (i * NW + wave) * 512), vo);
         }
     };
     auto issue_w = [&](int step) {              // step = slice*9 + tap
@@ -91,7 +92,7 @@ __global__ __launch_bounds__(256, 2) void k_conv3x3_halo(const bf16_t *__restric
 #pragma unroll
         for (int i = 0; i < WLD; ++i) {
             unsigned vo = step < T ? woff[i] + ((unsigned)tap * (unsigned)Ci + (unsigned)slice * 64u) * 2u : OOB;
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(wrsrc, (lds_void_t *)(dst + (i * NW + wave) * 512), 16, (int)vo, 0, 0, 0);
+            dma16(wrsrc, lds_of(dst + (i * NW + wave) * 512), vo);
         }
     };
 
@@ -266,6 +267,7 @@ __global__ __launch_bounds__(256, 2) void k_wgrad3x3_halo(const bf16_t *__restri
     constexpr unsigned OOB = 0x80000000u;
     constexpr int NW = 4;
     extern __shared__ __align__(16) unsigned char smem[];
+    const lds_addr_of lds_of(smem);
     uint16_t *stage0 = reinterpret_cast<uint16_t *>(smem);
     uint16_t *dump = stage0 + 2 * WG_STAGE_ELEMS;              // 64 slots for the one all-out-of-range wave-load
 
@@ -315,7 +317,7 @@ __global__ __launch_bounds__(256, 2) void k_wgrad3x3_halo(const bf16_t *__restri
 #pragma unroll
         for (int i = 0; i < WG_DL; ++i) {
             unsigned vo = live ? (unsigned)(((n * H + Y0 + ddy[i]) * W + X0 + ddx[i]) * K) * 2u + dco[i] : OOB;
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(grsrc, (lds_void_t *)(sd + (i * NW + wave) * 512), 16, (int)vo, 0, 0, 0);
+            dma16(grsrc, lds_of(sd + (i * NW + wave) * 512), vo);
         }
 #pragma unroll
         for (int i = 0; i < WG_HL; ++i) {
@@ -324,7 +326,7 @@ __global__ __launch_bounds__(256, 2) void k_wgrad3x3_halo(const bf16_t *__restri
             unsigned vo = ok ? (unsigned)(((n * H + y) * W + xx) * C) * 2u + hco[i] : OOB;
             const int q = i * NW + wave;                             // wave-load 23 lies wholly past the halo
             uint16_t *dst = q * 64 < WH_PIX * 8 ? sh + q * 512 : dump;
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(xrsrc, (lds_void_t *)dst, 16, (int)vo, 0, 0, 0);
+            dma16(xrsrc, lds_of(dst), vo);
         }
     };
 
@@ -339,24 +341,64 @@ __global__ __launch_bounds__(256, 2) void k_wgrad3x3_halo(const bf16_t *__restri
     const bool do_bias = with_bias && cs == 0 && wn == 0;
     float bsum = 0.0f;
 
+    // Fragment addresses (element offsets into a stage).  A fragment's swizzle depends on bit 1 of
+    // its pixel row, which moving down two halo rows (36 pixels) or one dy row (16 pixels) leaves
+    // alone, so one offset per column tile and row parity is enough; the row itself becomes the
+    // immediate offset of the read.
+    auto frag_off = [&](int ch0, int k0) {
+        const int blk = lane >> 4, sl = lane & 15;
+        const int row = k0 + 8 * (blk >> 1) + (sl >> 2);
+        const int col = ch0 + 16 * (blk & 1) + 4 * (sl & 3);
+        const int chunk = col >> 3;
+        const int sw = (((chunk >> 1) ^ wg_swz<64>(row)) << 1) | (chunk & 1);
+        return row * 64 + (sw << 3) + (col & 7);
+    };
+    auto frag_at = [&](const uint16_t *p) {
+        typedef __attribute__((address_space(3))) s16x4_t lds_v4;
+        typedef short s16x8_t __attribute__((ext_vector_type(8)));
+        s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4 *)(p));
+        s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4 *)(p + 4 * 64));
+        return __builtin_bit_cast(bf16x8_t, (s16x8_t)__builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+    };
+    const int offA = frag_off(wk * 32, 0);
+    int offB[9][2];
+#pragma unroll
+    for (int b = 0; b < 9; ++b) {
+        const int ct = wn * 9 + b, tap = ct >> 1;
+        const int r = tap / 3, q = tap - r * 3;
+        offB[b][0] = WG_DY_ELEMS + frag_off((ct & 1) * 32, r * WH_COLS + q);
+        offB[b][1] = WG_DY_ELEMS + frag_off((ct & 1) * 32, (r + 1) * WH_COLS + q);
+    }
+
+    // Main loop.  One unit = 8 pixel rows x 9 column tiles = 72 MFMAs per wave, fully unrolled; the
+    // x fragment of MFMA j+2 and the dy fragment of the next row are requested before MFMA j is
+    // issued (sched_barrier keeps that order), so the LDS latency hides behind two MFMAs.
     issue_unit(u0, 0);
+    WAIT_LGKMCNT(0);           // no scalar load pending at loop entry (else every LDS wait becomes a full drain)
     for (int u = u0; u < u1; ++u) {
         const int st = (u - u0) & 1;
         WAIT_VMCNT(0);
         __builtin_amdgcn_s_barrier();
         issue_unit(u + 1, st ^ 1);
-        const uint16_t *sd = stage0 + st * WG_STAGE_ELEMS, *sh = sd + WG_DY_ELEMS;
-#pragma unroll 2
-        for (int y = 0; y < UH; ++y) {                               // one k16 step = one row of 16 pixels
-            const bf16x8_t fa = tr_frag<64>(sd, wk * 32, y * 16, lane);
-            if (do_bias) bsum = frag_sum(fa, bsum);
+        const uint16_t *sd = stage0 + st * WG_STAGE_ELEMS;
+        auto ld_b = [&](int j) {                                   // x fragment of MFMA j = (row j/9, tile j%9)
+            const int y = j / 9, bb = j % 9;
+            return frag_at(sd + offB[bb][y & 1] + (y & ~1) * WH_COLS * 64);
+        };
+        bf16x8_t fa_cur = frag_at(sd + offA), fa_nxt = fa_cur;
+        bf16x8_t fbq[3];
+        fbq[0] = ld_b(0);
+        fbq[1] = ld_b(1);
 #pragma unroll
-            for (int b = 0; b < 9; ++b) {
-                const int ct = wn * 9 + b, tap = ct >> 1;
-                const int r = tap / 3, s = tap - r * 3;
-                const bf16x8_t fb = tr_frag<64>(sh, (ct & 1) * 32, (y + r) * WH_COLS + s, lane);
-                acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa, fb, acc[b], 0, 0, 0);
-            }
+        for (int j = 0; j < UH * 9; ++j) {
+            const int y = j / 9, bb = j % 9;
+            if (j + 2 < UH * 9) fbq[(j + 2) % 3] = ld_b(j + 2);
+            if (bb == 4 && y + 1 < UH) fa_nxt = frag_at(sd + offA + (y + 1) * 16 * 64);
+            __builtin_amdgcn_sched_barrier(0);
+            if (bb == 0 && do_bias) bsum = frag_sum(fa_cur, bsum);
+            acc[bb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa_cur, fbq[j % 3], acc[bb], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+            if (bb == 8) fa_cur = fa_nxt;
         }
     }
     WAIT_VMCNT(0);

@@ -62,6 +62,7 @@ __global__ __launch_bounds__(WP *WC * 64, 2) void k_gather_mfma(
     static_assert(BK == 32, "swizzle below assumes 4 chunks per row");
 
     extern __shared__ __align__(16) unsigned char smem[];
+    const lds_addr_of lds_of(smem);
     uint16_t *ring = reinterpret_cast<uint16_t *>(smem);               // [STAGES][ W tile | X tile ]
     uint16_t *sO = reinterpret_cast<uint16_t *>(smem);                 // [BP][SROW] (epilogue, reuses the ring)
     constexpr size_t RING_BYTES = (size_t)STAGES * STAGE_ELEMS * 2, EPI_BYTES = (size_t)BP * SROW * 2;
@@ -156,13 +157,13 @@ __global__ __launch_bounds__(WP *WC * 64, 2) void k_gather_mfma(
 #pragma unroll
             for (int i = 0; i < XL; ++i) {
                 unsigned vo = (tapmask[i] & bit) ? xoff[i] + xo : OOB;
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(xrsrc, (lds_void_t *)(sx + (i * NW + wave) * RPW * BK), 16, (int)vo, 0, 0, 0);
+                dma16(xrsrc, lds_of(sx + (i * NW + wave) * RPW * BK), vo);
             }
 #pragma unroll
             for (int i = 0; i < WL; ++i) {
                 unsigned vo = (woff[i] + wo) | (woff[i] & OOB);       // rows past Co stay out of range
                 if (!kin) vo = OOB;                                   // and so do tiles past K
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(wrsrc, (lds_void_t *)(sw + (i * NW + wave) * RPW * BK), 16, (int)vo, 0, 0, 0);
+                dma16(wrsrc, lds_of(sw + (i * NW + wave) * RPW * BK), vo);
             }
             return;                                   // the caller advances (kr, ks, cb) after its MFMAs
         }
@@ -183,12 +184,12 @@ __global__ __launch_bounds__(WP *WC * 64, 2) void k_gather_mfma(
                 ok = kin && hn >= 0 && wn >= 0 && ih * g.s_in == hn && iw * g.s_in == wn && ih < g.Hi && iw < g.Wi;
             }
             unsigned vo = ok ? xoff[i] + (unsigned)((ih * g.Wi + iw) * g.Ci + kc) * 2u : OOB;
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(xrsrc, (lds_void_t *)(sx + (i * NW + wave) * RPW * BK), 16, (int)vo, 0, 0, 0);
+            dma16(xrsrc, lds_of(sx + (i * NW + wave) * RPW * BK), vo);
         }
 #pragma unroll
         for (int i = 0; i < WL; ++i) {
             unsigned vo = (kin && woff[i] != OOB) ? woff[i] + koff : OOB;
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(wrsrc, (lds_void_t *)(sw + (i * NW + wave) * RPW * BK), 16, (int)vo, 0, 0, 0);
+            dma16(wrsrc, lds_of(sw + (i * NW + wave) * RPW * BK), vo);
         }
         // advance to the next K-tile
         if (TAPS_INNER) {
@@ -503,6 +504,7 @@ __global__ __launch_bounds__(WKO *WCI * 64, 2) void k_wgrad_mfma(const bf16_t *_
     static_assert(AL >= 1 && BL >= 1 && (BKP * CPA / 64) % NW == 0 && (BKP * CPB / 64) % NW == 0, "tile/thread mismatch");
 
     extern __shared__ __align__(16) unsigned char smem[];
+    const lds_addr_of lds_of(smem);
     uint16_t *ring = reinterpret_cast<uint16_t *>(smem);         // [STAGES][ A tile | B tile ]
 
     const int tid = threadIdx.x, lane = tid & 63;
@@ -519,70 +521,82 @@ __global__ __launch_bounds__(WKO *WCI * 64, 2) void k_wgrad_mfma(const bf16_t *_
     __amdgpu_buffer_rsrc_t xrsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t *>(x), 0, (int)x_bytes, 0x00020000);
     __amdgpu_buffer_rsrc_t grsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t *>(dy), 0, (int)dy_bytes, 0x00020000);
 
-    // ---- A (dy) loads: lane fills slot (row, c') of wave-load q = i*NW + wave and fetches chunk c
-    int ap[AL];                  // pixel of the lane's row in the current tile
-    int akoff[AL];               // element offset of its chunk inside a dy row, or -1
+    // ---- A (dy) loads: lane fills slot (row, c') of wave-load q = i*NW + wave and fetches chunk c.
+    // All addresses are kept as running byte offsets: a tile step adds a constant, so the loop body
+    // has no multiplications.
+    int ap[AL];                  // pixel of the lane's row in the current tile (huge if its chunk is past K)
+    unsigned aoff[AL];           // byte offset of its chunk
 #pragma unroll
     for (int i = 0; i < AL; ++i) {
         const int slot = (i * NW + wave) * 64 + lane;
         const int row = slot / CPA, cs = slot % CPA;
         const int ch = ((((cs >> 1) ^ wg_swz<BKO>(row)) << 1) | (cs & 1));
-        ap[i] = p_begin + row;
-        akoff[i] = ko0 + ch * 8 < c.K ? ko0 + ch * 8 : -1;
+        const bool kin = ko0 + ch * 8 < c.K;
+        ap[i] = kin ? p_begin + row : (1 << 30);
+        aoff[i] = ((unsigned)(p_begin + row) * (unsigned)c.K + (unsigned)(ko0 + ch * 8)) * 2u;
     }
-    // ---- B (x) loads: filter position of the lane's chunk column (fixed) and its pixel (advancing)
-    int bp[BL], bq[BL], bpp[BL], bn[BL], br[BL], bs[BL], bc[BL];
+    // ---- B (x) loads: filter position of the lane's chunk column (fixed) and its pixel (advancing):
+    // bp = output pixel index, (ph, pw) = stride * (output row, column), boff = byte offset of the
+    // input element under the lane's tap.  Moving one output column / row / image forward changes
+    // boff by a constant each.
+    int bp[BL], ph[BL], pw[BL], br[BL], bs[BL];
+    unsigned boff[BL];
+    const int Qs = c.Q * c.stride, Ps = c.P * c.stride;
+    const unsigned colstep = (unsigned)(c.stride * c.C) * 2u;
+    const unsigned rowstep = (unsigned)(c.stride * (c.W - c.Q) * c.C) * 2u;                 // extra, on top of Q columns
+    const unsigned imgstep = (unsigned)((c.H - c.P * c.stride) * c.W * c.C) * 2u;           // extra, on top of P rows
 #pragma unroll
     for (int i = 0; i < BL; ++i) {
         const int slot = (i * NW + wave) * 64 + lane;
         const int row = slot / CPB, cs = slot % CPB;
         const int ch = ((((cs >> 1) ^ wg_swz<BCI>(row)) << 1) | (cs & 1));
         const int n = n0 + ch * 8;
-        if (n < Ntot) {
-            const int tap = n / c.C;
-            bc[i] = n % c.C;
-            br[i] = tap / c.S - c.pad;
-            bs[i] = tap % c.S - c.pad;
-        } else {
-            bc[i] = -1;
-            br[i] = bs[i] = 0;
-        }
-        bp[i] = p_begin + row;
-        bq[i] = bp[i] % c.Q;
-        const int t = bp[i] / c.Q;
-        bpp[i] = t % c.P;
-        bn[i] = t / c.P;
+        const int tap = n / c.C, ci = n % c.C;
+        br[i] = tap / c.S - c.pad;
+        bs[i] = tap % c.S - c.pad;
+        const int p0 = p_begin + row;
+        bp[i] = n < Ntot ? p0 : (1 << 30);
+        const int q = p0 % c.Q, t = p0 / c.Q;
+        const int pr = t % c.P, img = t / c.P;
+        ph[i] = pr * c.stride;
+        pw[i] = q * c.stride;
+        boff[i] = (unsigned)(((img * c.H + ph[i] + br[i]) * c.W + pw[i] + bs[i]) * c.C + ci) * 2u;   // may wrap at the borders
     }
 
     auto issue_tile = [&](int stage) {
         uint16_t *sa = ring + stage * STAGE_ELEMS, *sb = sa + BKP * BKO;
 #pragma unroll
         for (int i = 0; i < AL; ++i) {
-            unsigned vo = (ap[i] < p_end && akoff[i] >= 0) ? ((unsigned)ap[i] * (unsigned)c.K + (unsigned)akoff[i]) * 2u : OOB;
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(grsrc, (lds_void_t *)(sa + (i * NW + wave) * 512), 16, (int)vo, 0, 0, 0);
+            unsigned vo = ap[i] < p_end ? aoff[i] : OOB;
+            dma16(grsrc, lds_of(sa + (i * NW + wave) * 512), vo);
         }
 #pragma unroll
         for (int i = 0; i < BL; ++i) {
-            const int ih = bpp[i] * c.stride + br[i], iw = bq[i] * c.stride + bs[i];
-            const bool ok = bp[i] < p_end && bc[i] >= 0 && (unsigned)ih < (unsigned)c.H && (unsigned)iw < (unsigned)c.W;
-            unsigned vo = ok ? (unsigned)(((bn[i] * c.H + ih) * c.W + iw) * c.C + bc[i]) * 2u : OOB;
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(xrsrc, (lds_void_t *)(sb + (i * NW + wave) * 512), 16, (int)vo, 0, 0, 0);
+            const bool ok = bp[i] < p_end && (unsigned)(ph[i] + br[i]) < (unsigned)c.H && (unsigned)(pw[i] + bs[i]) < (unsigned)c.W;
+            unsigned vo = ok ? boff[i] : OOB;
+            dma16(xrsrc, lds_of(sb + (i * NW + wave) * 512), vo);
         }
     };
     // step the per-lane pixel state to the next tile (kept out of issue_tile: its loops would split
     // the block in which the loads' address arithmetic interleaves with the MFMAs)
     auto advance_tile = [&]() {
 #pragma unroll
-        for (int i = 0; i < AL; ++i) ap[i] += BKP;
+        for (int i = 0; i < AL; ++i) {
+            ap[i] += BKP;
+            aoff[i] += (unsigned)(BKP * c.K) * 2u;
+        }
 #pragma unroll
         for (int i = 0; i < BL; ++i) {
             bp[i] += BKP;
-            bq[i] += BKP;
-            while (bq[i] >= c.Q) {
-                bq[i] -= c.Q;
-                if (++bpp[i] == c.P) {
-                    bpp[i] = 0;
-                    ++bn[i];
+            pw[i] += BKP * c.stride;
+            boff[i] += BKP * colstep;
+            while (pw[i] >= Qs) {
+                pw[i] -= Qs;
+                boff[i] += rowstep;
+                ph[i] += c.stride;
+                if (ph[i] == Ps) {
+                    ph[i] = 0;
+                    boff[i] += imgstep;
                 }
             }
         }
@@ -732,19 +746,19 @@ WgradPlan wgrad_plan(const ConvShape &c)
     long long tiles = (long long)p.tiles_ko * p.tiles_n;
     // Split count: the chip holds 512 blocks at once (256 CUs x 2), and a launch whose block count is
     // just above a multiple of that leaves most CUs idle during the last blocks.  Take the split count
-    // whose block count fills whole rounds best, less the relative cost of its partials (every split
-    // writes and re-reads a full fp32 copy of dw: about 500/npix of the MFMA time each); at least 512
-    // pixels per split.
+    // that minimises (time relative to perfectly filled rounds) + (relative cost of the partials: every
+    // split writes and re-reads a full fp32 copy of dw, about 500/npix of the MFMA time each); at least
+    // 512 pixels per split.
     long long max_by_work = (npix + 511) / 512;
     if (max_by_work > 256) max_by_work = 256;
     if (max_by_work < 1) max_by_work = 1;
     long long want = 1;
-    double best = -1.0;
+    double best = 1e30;
     for (long long sp = 1; sp <= max_by_work; ++sp) {
         const long long blocks = tiles * sp, rounds = (blocks + 511) / 512;
-        const double score = (double)blocks / (double)(rounds * 512) - 500.0 * (double)sp / (double)npix;
-        if (score > best) {
-            best = score;
+        const double cost = (double)(rounds * 512) / (double)blocks + 500.0 * (double)sp / (double)npix;
+        if (cost < best) {
+            best = cost;
             want = sp;
         }
     }

@@ -17,6 +17,32 @@ typedef __attribute__((address_space(3))) void lds_void_t;
 // ... with only the LDS / scalar-memory counter set
 #define WAIT_LGKMCNT(n) __builtin_amdgcn_s_waitcnt(0xC07F | ((n) << 8))
 
+// One wave-wide 16-byte-per-lane load HBM/L2 -> LDS (buffer_load_dwordx4 ... lds): lane l's chunk lands
+// at LDS byte address lds_addr + 16*l (wave-uniform); a lane whose voffset is outside the buffer gets
+// zeros.  Written as inline assembly on purpose: when the compiler knows of an LDS-DMA in flight it
+// puts s_waitcnt vmcnt(0) in front of every transposing LDS read (it cannot tell which bytes the DMA
+// writes), which would drain the prefetch ring once per K-step.  Completion is tracked by hand with
+// WAIT_VMCNT in every kernel that uses this; loads the compiler does track only wait longer for it.
+// No "memory" clobber: the s_barrier / s_waitcnt builtins around it already pin the LDS accesses,
+// and with one the LDS reads could no longer be scheduled around the issue slots.
+__device__ __forceinline__ void dma16(__amdgpu_buffer_rsrc_t rsrc, unsigned lds_addr, unsigned voffset)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds" ::"s"(lds_addr), "v"(voffset), "s"(rsrc));
+}
+
+// LDS byte address of a pointer into the kernel's dynamic shared memory, for dma16: base address taken
+// once, the rest is integer arithmetic (a generic pointer cast per load would cost a null check each)
+struct lds_addr_of {
+    const unsigned char *base;
+    unsigned addr0;
+    __device__ __forceinline__ explicit lds_addr_of(const unsigned char *smem)
+        : base(smem), addr0((unsigned)(uintptr_t)(lds_void_t *)smem) {}
+    __device__ __forceinline__ unsigned operator()(const void *p) const
+    {
+        return __builtin_amdgcn_readfirstlane(addr0 + (unsigned)((const unsigned char *)p - base));
+    }
+};
+
 __device__ __forceinline__ bf16x8_t as_frag(chunk16 c) { return __builtin_bit_cast(bf16x8_t, c); }
 
 // XCD-aware block order: hardware deals consecutive block ids round-robin to the 8 XCDs
