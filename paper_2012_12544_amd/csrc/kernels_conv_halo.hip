@@ -6,8 +6,8 @@
 // A block owns a 16x16 patch of output pixels x BC output channels.  The 18x18 input halo of one
 // 64-channel slice is brought into LDS ONCE (buffer_load ... lds, zero fill outside the image) and
 // all 9 taps read their shifted views of it: the B fragment of tap (r,s) for patch pixel (y,x) is
-// simply halo pixel (y+r, x+s).  Only the 64x(BC) filter tile of the current tap streams through a
-// small LDS ring.  HBM/L2 traffic per output drops from 9 input reads to (18*18)/(16*16) = 1.27.
+// simply halo pixel (y+r, x+s).  Only the filter tile of the current tap streams through a small
+// LDS ring.  HBM/L2 traffic per output drops from 9 input reads to (18*18)/(16*16) = 1.27.
 // MFMA mapping, swizzles and the epilogue are those of the gather kernel (A = filter rows, B = pixels,
 // v_mfma_f32_32x32x16_bf16, staging through LDS to 16-byte coalesced rows).
 #include "kernels.h"
@@ -24,7 +24,12 @@ constexpr int PATCH = 16, HALO = 18, HPIX = HALO * HALO;       // 324 halo pixel
 constexpr int HL = 11;                                          // halo wave-loads per wave (44 x 64 slots >= 2592)
 constexpr int HALO_ELEMS = HL * 4 * 64 * 8;                     // bf16 elements reserved for the halo tile
 
-template <int BC, int WSTAGES>
+// Filter tiles stream through a ring of three 8 KB stages: one "step" is one tap x KS input channels
+// (KS = 64 for BC = 64, 32 for BC = 128), i.e. NSUB = KS/16 MFMA sub-steps.  The taps of a slice are
+// unrolled, so ring slots, halo rows and swizzles are compile-time or precomputed per tap: a fragment
+// read costs at most one XOR.  Fragments are double-buffered in registers and the barrier that
+// publishes the next filter tile sits before the last sub-step of a step, as in the gather kernel.
+template <int BC>
 __global__ __launch_bounds__(256, 2) void k_conv3x3_halo(const bf16_t *__restrict__ in, const bf16_t *__restrict__ wt,
                                                          const float *__restrict__ bias, bf16_t *out,
                                                          const bf16_t *__restrict__ gate, int accum, int relu,
@@ -32,18 +37,25 @@ __global__ __launch_bounds__(256, 2) void k_conv3x3_halo(const bf16_t *__restric
                                                          unsigned in_bytes, unsigned wt_bytes)
 {
     constexpr int NW = 4;
-    constexpr int WLD = BC / 32;               // filter-tile wave-loads per wave (BC rows x 8 chunks / 64 / 4)
+    constexpr int KS = BC == 64 ? 64 : 32;     // input channels per filter step tile
+    constexpr int NSUB = KS / 16;              // MFMA sub-steps per step
+    constexpr int SPT = 64 / KS;               // steps per tap and 64-channel slice
+    constexpr int SPS = 9 * SPT;               // steps per slice (a multiple of WS)
+    constexpr int WS = 3;                      // ring stages
+    constexpr int WT_ELEMS = BC * KS;          // 4096 elements = 8 KB
+    constexpr int CPR = KS / 8;                // 16-byte chunks per filter-tile row
+    constexpr int WLD = 2;                     // filter wave-loads per wave and step (512 slots / 64 / 4)
     constexpr int TC = BC / 32, TP = 2;        // wave tile: BC channels x 64 pixels
-    constexpr int WT_ELEMS = BC * 64;
     constexpr int SROW = BC + 4;
     constexpr unsigned OOB = 0x80000000u;
+    static_assert(WT_ELEMS == 4096 && SPS % WS == 0, "ring layout");
 
     extern __shared__ __align__(16) unsigned char smem[];
     const lds_addr_of lds_of(smem);
     uint16_t *halo = reinterpret_cast<uint16_t *>(smem);
     uint16_t *wring = halo + HALO_ELEMS;
     uint16_t *sO = reinterpret_cast<uint16_t *>(smem);                                   // [256][SROW] (epilogue)
-    float *sBias = reinterpret_cast<float *>(smem + (size_t)(HALO_ELEMS + WSTAGES * WT_ELEMS) * 2);   // [BC]
+    float *sBias = reinterpret_cast<float *>(smem + (size_t)(HALO_ELEMS + WS * WT_ELEMS) * 2);   // [BC]
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -56,44 +68,42 @@ __global__ __launch_bounds__(256, 2) void k_conv3x3_halo(const bf16_t *__restric
     const int Y0 = (t % py_tiles) * PATCH;
     const int n = t / py_tiles;
     const int co0 = tile_c * BC;
-    const int NS = Ci / 64, T = NS * 9;
+    const int NS = Ci / 64;
 
     __amdgpu_buffer_rsrc_t xrsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t *>(in), 0, (int)in_bytes, 0x00020000);
     __amdgpu_buffer_rsrc_t wrsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t *>(wt), 0, (int)wt_bytes, 0x00020000);
 
-    // halo slots of this lane: slot = hr*8 + c', it fetches chunk c = c' ^ swz8(hr) of halo pixel hr
-    unsigned hoff[HL];
+    // halo slot of a lane: slot = hr*8 + c', it fetches chunk c = c' ^ swz8(hr) of halo pixel hr (offsets
+    // are recomputed per slice: keeping 11 of them alive through the main loop costs more than that)
+    auto issue_halo = [&](int slice) {
 #pragma unroll
-    for (int i = 0; i < HL; ++i) {
-        const int slot = (i * NW + wave) * 64 + lane;
-        const int hr = slot >> 3, c = (slot & 7) ^ swz8(hr);
-        const int hy = hr / HALO, hx = hr - hy * HALO;
-        const int y = Y0 - 1 + hy, x = X0 - 1 + hx;
-        const bool ok = hr < HPIX && (unsigned)y < (unsigned)H && (unsigned)x < (unsigned)W;
-        hoff[i] = ok ? ((unsigned)((n * H + y) * W + x) * (unsigned)Ci + (unsigned)c * 8u) * 2u : OOB;
-    }
+        for (int i = 0; i < HL; ++i) {
+            const int slot = (i * NW + wave) * 64 + lane;
+            const int hr = slot >> 3, c = (slot & 7) ^ swz8(hr);
+            const int hy = hr / HALO, hx = hr - hy * HALO;
+            const int y = Y0 - 1 + hy, x = X0 - 1 + hx;
+            const bool ok = hr < HPIX && (unsigned)y < (unsigned)H && (unsigned)x < (unsigned)W;
+            unsigned vo = ok ? ((unsigned)((n * H + y) * W + x) * (unsigned)Ci + (unsigned)(slice * 64 + c * 8)) * 2u : OOB;
+            dma16(xrsrc, lds_of(halo + (i * NW + wave) * 512), vo);
+        }
+    };
+    // filter tile rows are KS elements long; chunk index XORed with swz8(row) (KS = 64) or bits 2..3 of
+    // the row (KS = 32) so that the fragment reads are conflict free
+    auto wswz = [](int row) { return KS == 64 ? ((row >> 1) & 7) : ((row >> 2) & 3); };
     unsigned woff[WLD];
 #pragma unroll
     for (int i = 0; i < WLD; ++i) {
         const int slot = (i * NW + wave) * 64 + lane;
-        const int row = slot >> 3, c = (slot & 7) ^ swz8(row);
+        const int row = slot / CPR, c = (slot % CPR) ^ wswz(row);
         woff[i] = ((unsigned)(co0 + row) * 9u * (unsigned)Ci + (unsigned)c * 8u) * 2u;
     }
-    auto issue_halo = [&](int slice) {
+    const unsigned wring_addr = lds_of(wring);
+    auto issue_w = [&](int slice, int pos) {        // step `pos` (= tap*SPT + half) of a slice
+        const int tap = pos / SPT, half = pos % SPT;
+        const unsigned ko = slice < NS ? (unsigned)(tap * Ci + slice * 64 + half * KS) * 2u : OOB;
 #pragma unroll
-        for (int i = 0; i < HL; ++i) {
-            unsigned vo = hoff[i] == OOB ? OOB : hoff[i] + (unsigned)slice * 128u;
-            dma16(xrsrc, lds_of(halo + (i * NW + wave) * 512), vo);
-        }
-    };
-    auto issue_w = [&](int step) {              // step = slice*9 + tap
-        const int slice = step / 9, tap = step - slice * 9;
-        uint16_t *dst = wring + (step % WSTAGES) * WT_ELEMS;
-#pragma unroll
-        for (int i = 0; i < WLD; ++i) {
-            unsigned vo = step < T ? woff[i] + ((unsigned)tap * (unsigned)Ci + (unsigned)slice * 64u) * 2u : OOB;
-            dma16(wrsrc, lds_of(dst + (i * NW + wave) * 512), vo);
-        }
+        for (int i = 0; i < WLD; ++i)
+            dma16(wrsrc, wring_addr + (unsigned)((pos % WS) * WT_ELEMS * 2 + (i * NW + wave) * 1024), (woff[i] + ko) | (ko & OOB));
     };
 
     f32x16_t acc[TC][TP];
@@ -107,15 +117,48 @@ __global__ __launch_bounds__(256, 2) void k_conv3x3_halo(const bf16_t *__restric
     const int frow = lane & 31, fhalf = lane >> 5;
     const int py = 4 * wave + (frow >> 4), px = frow & 15;       // patch pixel of B tile 0 (tile 1: py + 2)
 
+    // fragment addresses (bytes).  The K position of a sub-step only flips bits 5..6 (the chunk pair),
+    // which commutes with the swizzle XOR: address(kk) = base ^ (kk << 5).
+    unsigned hbase[9][TP];
+#pragma unroll
+    for (int tap = 0; tap < 9; ++tap)
+#pragma unroll
+        for (int b = 0; b < TP; ++b) {
+            const int hr = (py + tap / 3 + 2 * b) * HALO + px + tap % 3;
+            hbase[tap][b] = (unsigned)(hr * 128 + ((fhalf ^ swz8(hr)) << 4));
+        }
+    unsigned wbase[TC];
+#pragma unroll
+    for (int a = 0; a < TC; ++a) {
+        const int row = a * 32 + frow;
+        wbase[a] = (unsigned)(HALO_ELEMS * 2 + row * KS * 2 + ((fhalf ^ wswz(row)) << 4));
+    }
+    auto load_frags = [&](int pos, int ks, bf16x8_t(&fa)[TC], bf16x8_t(&fb)[TP]) {
+        const int tap = pos / SPT, half = pos % SPT;
+#pragma unroll
+        for (int a = 0; a < TC; ++a)
+            fa[a] = as_frag(*reinterpret_cast<const chunk16 *>(smem + (wbase[a] ^ (unsigned)(ks << 5)) + (pos % WS) * WT_ELEMS * 2));
+#pragma unroll
+        for (int b = 0; b < TP; ++b)
+            fb[b] = as_frag(*reinterpret_cast<const chunk16 *>(smem + (hbase[tap][b] ^ (unsigned)((half * NSUB + ks) << 5))));
+    };
+    auto mfma_all = [&](const bf16x8_t(&fa)[TC], const bf16x8_t(&fb)[TP]) {
+#pragma unroll
+        for (int a = 0; a < TC; ++a)
+#pragma unroll
+            for (int b = 0; b < TP; ++b)
+                acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[a], fb[b], acc[a][b], 0, 0, 0);
+    };
+
     if (tid < BC) sBias[tid] = bias ? bias[co0 + tid] : 0.0f;          // read after the main loop's barriers
 
     // gradient epilogue: the ReLU gate of the first GPRE output rows of this thread is requested now, so
     // the loads complete under the halo wait instead of after the last MFMA
     constexpr int CH8 = BC / 8;
     constexpr int UNITS = 256 * CH8 / 256;
-    constexpr int GPRE = 8;
+    constexpr int GPRE = BC == 64 ? 8 : 0;        // BC = 128 has no registers to spare for it
     const chunk16 zero16 = {0u, 0u, 0u, 0u};
-    chunk16 gpre[GPRE];
+    chunk16 gpre[GPRE > 0 ? GPRE : 1];
 #pragma unroll
     for (int it = 0; it < GPRE; ++it) {
         gpre[it] = zero16;
@@ -126,39 +169,63 @@ __global__ __launch_bounds__(256, 2) void k_conv3x3_halo(const bf16_t *__restric
             gpre[it] = *reinterpret_cast<const chunk16 *>(gate + p * Co + co0 + c8i * 8);
         }
     }
+
     issue_halo(0);
 #pragma unroll
-    for (int st = 0; st < WSTAGES - 1; ++st) issue_w(st);
-    for (int step = 0; step < T; ++step) {
-        const int slice = step / 9, tap = step - slice * 9;
-        if (tap == 0 && step > 0) {
-            __builtin_amdgcn_s_barrier();                        // everyone has left the old halo slice
-            issue_halo(slice);
-            WAIT_VMCNT(0);
-        } else {
-            WAIT_VMCNT((WSTAGES - 2) * WLD);
-        }
-        __builtin_amdgcn_s_barrier();
-        issue_w(step + WSTAGES - 1);
-        const uint16_t *cw = wring + (step % WSTAGES) * WT_ELEMS;
-        const int r = tap / 3, s = tap - r * 3;
-        const int hr0 = (py + r) * HALO + px + s, hr1 = hr0 + 2 * HALO;
+    for (int st = 0; st < WS; ++st) issue_w(0, st);
+    WAIT_VMCNT((WS - 1) * WLD);                  // gate rows, halo and filter tile 0 have landed
+    WAIT_LGKMCNT(0);                             // no scalar load pending at loop entry (else every LDS wait is a full drain)
+    __builtin_amdgcn_s_barrier();
+    bf16x8_t fa0[TC], fb0[TP], fa1[TC], fb1[TP];
+    load_frags(0, 0, fa0, fb0);
+    for (int slice = 0; slice < NS; ++slice) {
+        // keep the 26 base addresses opaque per slice: otherwise all 80 XORed fragment addresses are
+        // hoisted out of this loop and spill
 #pragma unroll
-        for (int ks16 = 0; ks16 < 4; ++ks16) {
-            const int ch = 2 * ks16 + fhalf;
-            bf16x8_t fa[TC], fb[TP];
+        for (int tap = 0; tap < 9; ++tap)
 #pragma unroll
-            for (int a = 0; a < TC; ++a) {
-                const int row = a * 32 + frow;
-                fa[a] = as_frag(*reinterpret_cast<const chunk16 *>(cw + row * 64 + ((ch ^ swz8(row)) << 3)));
+            for (int b = 0; b < TP; ++b) asm volatile("" : "+v"(hbase[tap][b]));
+#pragma unroll
+        for (int a = 0; a < TC; ++a) asm volatile("" : "+v"(wbase[a]));
+#pragma unroll
+        for (int pos = 0; pos < SPS; ++pos) {
+            // sub-steps 0 .. NSUB-2: fetch the next sub-step's fragments, multiply the current ones
+#pragma unroll
+            for (int ks = 0; ks + 1 < NSUB; ++ks) {
+                if (ks % 2 == 0) {
+                    load_frags(pos, ks + 1, fa1, fb1);
+                    __builtin_amdgcn_sched_barrier(0);
+                    mfma_all(fa0, fb0);
+                } else {
+                    load_frags(pos, ks + 1, fa0, fb0);
+                    __builtin_amdgcn_sched_barrier(0);
+                    mfma_all(fa1, fb1);
+                }
+                __builtin_amdgcn_sched_barrier(0);
             }
-            fb[0] = as_frag(*reinterpret_cast<const chunk16 *>(halo + hr0 * 64 + ((ch ^ swz8(hr0)) << 3)));
-            fb[1] = as_frag(*reinterpret_cast<const chunk16 *>(halo + hr1 * 64 + ((ch ^ swz8(hr1)) << 3)));
-#pragma unroll
-            for (int a = 0; a < TC; ++a)
-#pragma unroll
-                for (int b = 0; b < TP; ++b)
-                    acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[a], fb[b], acc[a][b], 0, 0, 0);
+            // last sub-step (its fragments are in fa1/fb1: NSUB is even): publish the next filter tile first
+            WAIT_LGKMCNT(0);                          // this wave has read everything it needs from this step's tile
+            WAIT_VMCNT((WS - 2) * WLD);
+            __builtin_amdgcn_s_barrier();
+            if (pos + 1 < SPS) {
+                load_frags(pos + 1, 0, fa0, fb0);
+                __builtin_amdgcn_sched_barrier(0);
+                if (pos + WS < SPS)
+                    issue_w(slice, pos + WS);
+                else
+                    issue_w(slice + 1, pos + WS - SPS);
+                mfma_all(fa1, fb1);
+                __builtin_amdgcn_sched_barrier(0);
+            } else {
+                // slice boundary: every wave has left the halo, bring in the next 64 input channels
+                if (slice + 1 < NS) issue_halo(slice + 1);
+                issue_w(slice + 1, pos + WS - SPS);
+                mfma_all(fa1, fb1);
+                __builtin_amdgcn_sched_barrier(0);
+                WAIT_VMCNT(0);
+                __builtin_amdgcn_s_barrier();
+                load_frags(0, 0, fa0, fb0);
+            }
         }
     }
     WAIT_VMCNT(0);
@@ -217,14 +284,15 @@ __global__ __launch_bounds__(256, 2) void k_conv3x3_halo(const bf16_t *__restric
     }
 }
 
-template <int BC, int WSTAGES>
+template <int BC>
 hipError_t launch_halo(const void *in, const void *wt, const float *bias, void *out, int relu, GradEpi epi,
                        const GatherConv &g, hipStream_t s)
 {
-    constexpr size_t smem = (size_t)HALO_ELEMS * 2 + (size_t)WSTAGES * BC * 64 * 2 + BC * sizeof(float);
-    static_assert((size_t)256 * (BC + 4) * 2 <= (size_t)HALO_ELEMS * 2 + (size_t)WSTAGES * BC * 64 * 2, "epilogue staging fits");
+    constexpr size_t ring_bytes = (size_t)HALO_ELEMS * 2 + 3 * 8192;
+    constexpr size_t smem = ring_bytes + BC * sizeof(float);
+    static_assert((size_t)256 * (BC + 4) * 2 <= ring_bytes, "epilogue staging fits");
     static_assert(smem <= 80 * 1024, "two blocks per CU");
-    auto kfn = k_conv3x3_halo<BC, WSTAGES>;
+    auto kfn = k_conv3x3_halo<BC>;
     static bool attr_set = false;
     if (!attr_set && smem > 64 * 1024) {
         hipError_t e = hipFuncSetAttribute((const void *)kfn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
@@ -485,8 +553,8 @@ hipError_t conv3x3_halo_mfma(const void *in, const void *wt, const float *bias, 
                              const GatherConv &g, hipStream_t s)
 {
     if (!conv3x3_halo_supported(g)) return hipErrorInvalidValue;
-    if (g.Co % 128 == 0) return launch_halo<128, 2>(in, wt, bias, out, relu, epi, g, s);
-    return launch_halo<64, 3>(in, wt, bias, out, relu, epi, g, s);
+    if (g.Co % 128 == 0) return launch_halo<128>(in, wt, bias, out, relu, epi, g, s);
+    return launch_halo<64>(in, wt, bias, out, relu, epi, g, s);
 }
 
 }  // namespace bapipe
