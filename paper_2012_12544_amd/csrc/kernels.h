@@ -49,6 +49,10 @@ hipError_t conv_gather_mfma(const void *in, const void *wt, const float *bias, v
 bool conv3x3_halo_supported(const GatherConv &g);
 hipError_t conv3x3_halo_mfma(const void *in, const void *wt, const float *bias, void *out, int relu,
                              GradEpi epi, const GatherConv &g, hipStream_t s);
+// same convolution with a 2x2 stride-2 max-pool fused into the epilogue: writes the pooled output
+// [N][H/2][W/2][Co] and the arg-max indices (one byte each, same layout); the conv output is not stored
+hipError_t conv3x3_halo_pool_mfma(const void *in, const void *wt, const float *bias, int relu, void *pool_out,
+                                  uint8_t *pool_idx, const GatherConv &g, hipStream_t s);
 bool wgrad3x3_halo_supported(const ConvShape &c);
 size_t wgrad3x3_halo_workspace(const ConvShape &c);
 hipError_t wgrad3x3_halo_mfma(const void *x, const void *dy, float *dw, float *db, void *workspace,

@@ -34,7 +34,8 @@ __global__ __launch_bounds__(256, 2) void k_conv3x3_halo(const bf16_t *__restric
                                                          const float *__restrict__ bias, bf16_t *out,
                                                          const bf16_t *__restrict__ gate, int accum, int relu,
                                                          int is_grad, int N, int H, int W, int Ci, int Co,
-                                                         unsigned in_bytes, unsigned wt_bytes)
+                                                         unsigned in_bytes, unsigned wt_bytes,
+                                                         bf16_t *__restrict__ pool_out, uint8_t *__restrict__ pool_idx)
 {
     constexpr int NW = 4;
     constexpr int KS = BC == 64 ? 64 : 32;     // input channels per filter step tile
@@ -258,6 +259,51 @@ __global__ __launch_bounds__(256, 2) void k_conv3x3_halo(const bf16_t *__restric
         }
     }
     __syncthreads();
+    if (pool_out) {
+        // fused 2x2 stride-2 max-pool: the patch holds 8x8 complete windows; the conv output itself
+        // never reaches memory.  Window scan order and tie rule (first maximum) are those of the
+        // stand-alone pooling kernel.
+        const int Hq = H / 2, Wq = W / 2;
+#pragma unroll
+        for (int it = 0; it < 64 * CH8 / 256; ++it) {
+            const int u = tid + it * 256;
+            const int qp = u / CH8, c8i = u % CH8;
+            const int qy = qp >> 3, qx = qp & 7;
+            uint32_t w[4][4];
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const int pj = (2 * qy + (k >> 1)) * 16 + 2 * qx + (k & 1);
+                const chunk8 lo = *reinterpret_cast<const chunk8 *>(sO + pj * SROW + c8i * 8);
+                const chunk8 hi = *reinterpret_cast<const chunk8 *>(sO + pj * SROW + c8i * 8 + 4);
+                w[k][0] = lo[0]; w[k][1] = lo[1]; w[k][2] = hi[0]; w[k][3] = hi[1];
+            }
+            chunk16 best;
+            chunk8 bidx = {0u, 0u};
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const int sh = 16 * (j & 1);
+                uint32_t bv = (w[0][j >> 1] >> sh) & 0xFFFFu;
+                uint32_t bi = 0;
+#pragma unroll
+                for (int k = 1; k < 4; ++k) {
+                    const uint32_t v = (w[k][j >> 1] >> sh) & 0xFFFFu;
+                    if (__uint_as_float(v << 16) > __uint_as_float(bv << 16)) {       // strictly greater: the first maximum wins
+                        bv = v;
+                        bi = (uint32_t)k;
+                    }
+                }
+                if (j & 1)
+                    best[j >> 1] |= bv << 16;
+                else
+                    best[j >> 1] = bv;
+                bidx[j >> 2] |= bi << (8 * (j & 3));
+            }
+            const size_t q = ((size_t)(n * Hq + Y0 / 2 + qy) * Wq + X0 / 2 + qx) * Co + co0 + c8i * 8;
+            *reinterpret_cast<chunk16 *>(pool_out + q) = best;
+            *reinterpret_cast<chunk8 *>(pool_idx + q) = bidx;
+        }
+        return;
+    }
 #pragma unroll
     for (int it = 0; it < UNITS; ++it) {
         const int u = tid + it * 256;
@@ -286,7 +332,7 @@ __global__ __launch_bounds__(256, 2) void k_conv3x3_halo(const bf16_t *__restric
 
 template <int BC>
 hipError_t launch_halo(const void *in, const void *wt, const float *bias, void *out, int relu, GradEpi epi,
-                       const GatherConv &g, hipStream_t s)
+                       const GatherConv &g, void *pool_out, uint8_t *pool_idx, hipStream_t s)
 {
     constexpr size_t ring_bytes = (size_t)HALO_ELEMS * 2 + 3 * 8192;
     constexpr size_t smem = ring_bytes + BC * sizeof(float);
@@ -305,7 +351,7 @@ hipError_t launch_halo(const void *in, const void *wt, const float *bias, void *
     dim3 grid((unsigned)(g.N * (g.Ho / PATCH) * (g.Wo / PATCH) * (g.Co / BC)));
     hipLaunchKernelGGL(kfn, grid, dim3(256), smem, s, (const bf16_t *)in, (const bf16_t *)wt, bias, (bf16_t *)out,
                        (const bf16_t *)epi.gate, epi.accum, relu, is_grad, g.N, g.Hi, g.Wi, g.Ci, g.Co, in_bytes,
-                       wt_bytes);
+                       wt_bytes, (bf16_t *)pool_out, pool_idx);
     return hipGetLastError();
 }
 
@@ -549,12 +595,21 @@ bool conv3x3_halo_supported(const GatherConv &g)
            (long long)g.N * g.Ho * g.Wo * g.Co < (1ll << 40);
 }
 
-hipError_t conv3x3_halo_mfma(const void *in, const void *wt, const float *bias, void *out, int relu, GradEpi epi,
-                             const GatherConv &g, hipStream_t s)
+hipError_t conv3x3_halo_mfma(const void *in, const void *wt, const float *bias, void *out, int relu,
+                             GradEpi epi, const GatherConv &g, hipStream_t s)
 {
     if (!conv3x3_halo_supported(g)) return hipErrorInvalidValue;
-    if (g.Co % 128 == 0) return launch_halo<128>(in, wt, bias, out, relu, epi, g, s);
-    return launch_halo<64>(in, wt, bias, out, relu, epi, g, s);
+    if (g.Co % 128 == 0) return launch_halo<128>(in, wt, bias, out, relu, epi, g, nullptr, nullptr, s);
+    return launch_halo<64>(in, wt, bias, out, relu, epi, g, nullptr, nullptr, s);
+}
+
+hipError_t conv3x3_halo_pool_mfma(const void *in, const void *wt, const float *bias, int relu, void *pool_out,
+                                  uint8_t *pool_idx, const GatherConv &g, hipStream_t s)
+{
+    if (!conv3x3_halo_supported(g) || !pool_out || !pool_idx || ((uintptr_t)pool_idx & 7)) return hipErrorInvalidValue;
+    GradEpi none{nullptr, 0};
+    if (g.Co % 128 == 0) return launch_halo<128>(in, wt, bias, nullptr, relu, none, g, pool_out, pool_idx, s);
+    return launch_halo<64>(in, wt, bias, nullptr, relu, none, g, pool_out, pool_idx, s);
 }
 
 }  // namespace bapipe

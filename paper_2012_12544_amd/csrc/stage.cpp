@@ -61,6 +61,10 @@ struct Layer {
     bool deferred = false;
     char *def_x = nullptr, *def_g = nullptr;
     size_t def_x_bytes = 0, def_g_bytes = 0;     // per micro-batch
+    // conv whose output only feeds a 2x2 max-pool: the pool runs in the conv kernel's epilogue and
+    // the conv output is never stored (fuse_pool = index of that pool layer; fused marks the pool)
+    int fuse_pool = -1;
+    bool fused = false;
     bool permute_in = false;             // LINEAR fed by a flattened (C,H,W) tensor
     int pc = 0, ph = 0, pw = 0;
 };
@@ -311,7 +315,11 @@ int layer_forward(bapipe_stage *st, int li, const FwdCtx &c)
         GradEpi none{nullptr, 0};
         const bool mf = use_mfma_gather(st, g);
         const bool tp = st->tap_begin(mf ? BAPIPE_KC_CONV_GATHER_MFMA : BAPIPE_KC_CONV_DIRECT);
-        if (mf)
+        if (L.fuse_pool >= 0) {
+            const Layer &P = st->layers[L.fuse_pool];
+            HIPCHK(conv3x3_halo_pool_mfma(a, L.w_work, L.bias, L.d.fuse_relu, st->tptr(P.o, c.mbid),
+                                          (uint8_t *)(st->slot(c.mbid) + P.aux_off), g, s));
+        } else if (mf)
             HIPCHK(conv_gather_mfma(a, L.w_work, L.bias, o, L.d.fuse_relu, none, g, st->work, s));
         else
             HIPCHK(conv_gather_direct(dt, a, L.w_work, L.bias, o, L.d.fuse_relu, none, g, s));
@@ -325,6 +333,7 @@ int layer_forward(bapipe_stage *st, int li, const FwdCtx &c)
         break;
     }
     case BAPIPE_MAXPOOL2D: {
+        if (L.fused) break;                       // done in the producing conv's epilogue
         const Tensor &A = st->tensors[L.a];
         const bool tp = st->tap_begin(BAPIPE_KC_POOL);
         HIPCHK(maxpool2x2_fwd(dt, a, o, (uint8_t *)(st->slot(c.mbid) + L.aux_off), st->mb, A.H, A.W, A.C, s));
@@ -738,6 +747,18 @@ int bapipe_stage_create(const bapipe_layer_desc_t *layers, int n_layers, int mic
     {   // gradient of the stage output (ingest target when the caller's dy cannot be used in place)
         Tensor &T = st->tensors[root_of(last_t)];
         if (st->layers[n_layers - 1].d.kind != BAPIPE_SOFTMAX_XENT && root_of(last_t) == last_t) { T.goff = gr; gr += align_up(T.bytes()); }
+    }
+    // conv -> max-pool fusion (bf16, halo kernel shapes): the conv output must be a transient tensor
+    // read by that pool only
+    for (int i = 0; i < n_layers; ++i) {
+        Layer &L = st->layers[i];
+        const Tensor &O = st->tensors[L.o];
+        if (L.d.kind != BAPIPE_CONV2D || st->dt != DT_BF16 || L.o == last_t || O.stashed || O.consumers.size() != 1) continue;
+        Layer &P = st->layers[O.consumers[0]];
+        if (P.d.kind != BAPIPE_MAXPOOL2D || P.a != L.o) continue;
+        if (!conv3x3_halo_supported(fwd_geom(st, L)) || (O.H & 1) || (O.W & 1)) continue;
+        L.fuse_pool = O.consumers[0];
+        P.fused = true;
     }
     size_t work = 256;
     for (int i = 0; i < n_layers; ++i) {

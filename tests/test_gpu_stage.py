@@ -78,6 +78,14 @@ def test_pool_only_stage_indices_bit_exact(dtype, c, hw, mb):
     g.close()
 
 
+@pytest.mark.parametrize("cin,cout,hw,mb", [(64, 64, (32, 16), 2), (64, 128, (16, 48), 2), (128, 64, (16, 16), 3)])
+def test_conv_with_pool_in_its_epilogue(cin, cout, hw, mb):
+    """16-aligned 3x3 conv (+ReLU) whose output only feeds a 2x2 max-pool: pooled values and arg-max
+    indices come out of the conv kernel's epilogue and the conv output is never stored."""
+    st = single(lambda b: (b.conv(cin, cout, 3, relu=1, src=-1), b.pool()), cin, hw, C.BF16, micro_batch=mb)
+    compare_minibatch(st, verbose="conv+pool fused %d->%d %s" % (cin, cout, hw))
+
+
 @pytest.mark.parametrize("dtype", DT)
 def test_pool_odd_size_and_vector_tail(dtype):
     st = single(lambda b: (b.conv(6, 6, 1, relu=1, src=-1), b.pool()), 6, (9, 7), dtype)
