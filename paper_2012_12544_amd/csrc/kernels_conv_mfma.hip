@@ -409,8 +409,8 @@ struct GatherPlan {
     int bp, bc, splits, kt_per_split;
 };
 
-// Tile shape and split-K factor.  K is split when the output tiles alone cannot occupy the chip
-// (256 CUs x 2 resident blocks), e.g. the linear layers (one pixel tile) and the 14x14 layers.
+// Tile shape and split-K factor.  K is split only when there are very few output tiles (the linear
+// layers: one pixel tile).
 GatherPlan gather_plan(const GatherConv &g)
 {
     GatherPlan p;
@@ -418,10 +418,15 @@ GatherPlan gather_plan(const GatherConv &g)
     p.bp = npix <= 64 ? 64 : 256;
     p.bc = g.Co <= 64 ? 64 : 128;
     if (p.bp == 64) p.bc = 128;
-    const long long tiles = ((npix + p.bp - 1) / p.bp) * ((g.Co + p.bc - 1) / p.bc);
+    auto tiles_of = [&](int bp) { return ((npix + bp - 1) / bp) * ((g.Co + p.bc - 1) / p.bc); };
+    // 256-pixel tiles that cannot even fill 400 of the 512 block slots (14x14 layers, the 1x1 convs of
+    // the bottleneck blocks): halve the pixel tile rather than split K, whose fp32 partials cost more
+    // than the smaller tile loses (measured on 512-channel 14x14 layers: 73 us against 100 us)
+    if (p.bp == 256 && p.bc == 128 && tiles_of(256) < 400) p.bp = 128;
+    const long long tiles = tiles_of(p.bp);
     const int BK = 32;
     const int KT = g.Ci % BK == 0 ? (g.Ci / BK) * g.R * g.S : (g.R * g.S * g.Ci + BK - 1) / BK;
-    long long want = tiles >= 384 ? 1 : (512 + tiles - 1) / tiles;
+    long long want = tiles >= 128 ? 1 : (512 + tiles - 1) / tiles;
     long long most = KT / 16;                       // at least 16 K-tiles per split
     if (want > most) want = most;
     if (want > 32) want = 32;
@@ -797,6 +802,7 @@ hipError_t conv_gather_mfma(const void *in, const void *wt, const float *bias, v
     const GatherPlan p = gather_plan(g);
     if (p.bp == 64) return launch_gather<64, 128, 1, 4, 32, 3>(in, wt, bias, out, relu, epi, g, p, workspace, s);
     if (p.bc == 64) return launch_gather<256, 64, 4, 1, 32, 3>(in, wt, bias, out, relu, epi, g, p, workspace, s);
+    if (p.bp == 128) return launch_gather<128, 128, 2, 2, 32, 3>(in, wt, bias, out, relu, epi, g, p, workspace, s);
     return launch_gather<256, 128, 2, 2, 32, 3>(in, wt, bias, out, relu, epi, g, p, workspace, s);
 }
 
