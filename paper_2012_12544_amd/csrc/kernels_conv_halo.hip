@@ -153,28 +153,32 @@ __global__ __launch_bounds__(256, 2) void k_conv3x3_halo(const bf16_t *__restric
 
     if (tid < BC) sBias[tid] = bias ? bias[co0 + tid] : 0.0f;          // read after the main loop's barriers
 
-    // gradient epilogue: the ReLU gate of the first GPRE output rows of this thread is requested now, so
-    // the loads complete under the halo wait instead of after the last MFMA
+    issue_halo(0);
+#pragma unroll
+    for (int st = 0; st < WS; ++st) issue_w(0, st);
+
+    // gradient epilogue: the ReLU gate of the first GPRE output rows of this thread is requested now
+    // (behind the halo and the first filter tiles, which the MFMAs need first), so the loads complete
+    // under the main loop instead of after the last MFMA
     constexpr int CH8 = BC / 8;
     constexpr int UNITS = 256 * CH8 / 256;
     constexpr int GPRE = BC == 64 ? 8 : 0;        // BC = 128 has no registers to spare for it
     const chunk16 zero16 = {0u, 0u, 0u, 0u};
     chunk16 gpre[GPRE > 0 ? GPRE : 1];
 #pragma unroll
-    for (int it = 0; it < GPRE; ++it) {
-        gpre[it] = zero16;
-        if (gate) {
+    for (int it = 0; it < GPRE; ++it) gpre[it] = zero16;
+    if (GPRE > 0 && gate) {
+#pragma unroll
+        for (int it = 0; it < GPRE; ++it) {
             const int u = tid + it * 256;
             const int pj = u / CH8, c8i = u % CH8;
             const size_t p = (size_t)(n * H + Y0 + (pj >> 4)) * W + X0 + (pj & 15);
             gpre[it] = *reinterpret_cast<const chunk16 *>(gate + p * Co + co0 + c8i * 8);
         }
+        WAIT_VMCNT(GPRE + (WS - 1) * WLD);       // halo and filter tile 0 have landed (gate rows may still fly)
+    } else {
+        WAIT_VMCNT((WS - 1) * WLD);
     }
-
-    issue_halo(0);
-#pragma unroll
-    for (int st = 0; st < WS; ++st) issue_w(0, st);
-    WAIT_VMCNT((WS - 1) * WLD);                  // gate rows, halo and filter tile 0 have landed
     WAIT_LGKMCNT(0);                             // no scalar load pending at loop entry (else every LDS wait is a full drain)
     __builtin_amdgcn_s_barrier();
     bf16x8_t fa0[TC], fb0[TP], fa1[TC], fb1[TP];
