@@ -49,6 +49,10 @@ hipError_t conv_gather_mfma(const void *in, const void *wt, const float *bias, v
 bool conv3x3_halo_supported(const GatherConv &g);
 hipError_t conv3x3_halo_mfma(const void *in, const void *wt, const float *bias, void *out, int relu,
                              GradEpi epi, const GatherConv &g, hipStream_t s);
+// forward of a 3x3 / stride 1 / pad 1 conv whose input has 8 channels in memory (the padded RGB stage input)
+bool conv3x3_c8_supported(const GatherConv &g);
+hipError_t conv3x3_c8_mfma(const void *in, const void *wt, const float *bias, void *out, int relu,
+                           const GatherConv &g, hipStream_t s);
 // same convolution with a 2x2 stride-2 max-pool fused into the epilogue: writes the pooled output
 // [N][H/2][W/2][Co] and the arg-max indices (one byte each, same layout); the conv output is not stored
 hipError_t conv3x3_halo_pool_mfma(const void *in, const void *wt, const float *bias, int relu, void *pool_out,

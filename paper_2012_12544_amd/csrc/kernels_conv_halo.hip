@@ -361,6 +361,130 @@ hipError_t launch_halo(const void *in, const void *wt, const float *bias, void *
 
 
 // ------------------------------------------------------------------------------------------
+// first layer: 8 (padded) input channels
+// ------------------------------------------------------------------------------------------
+// 3x3 / stride 1 / pad 1 convolution of an input with 8 channels in memory (RGB zero-padded to 8) to
+// 64-channel tiles on 16-aligned maps.  There is almost no arithmetic (K = 72): the layer is bound by
+// writing its output, so a block is kept small - one 16x16 patch, a 5 KB halo, the whole 64x72 filter
+// in registers straight from L2 - and four of them share a CU.  One pixel of the halo is exactly one
+// 16-byte MFMA operand chunk: sub-step kk multiplies taps 2kk and 2kk+1 (the 10th tap is a zero filter).
+__global__ __launch_bounds__(256, 4) void k_conv3x3_c8(const bf16_t *__restrict__ in, const bf16_t *__restrict__ wt,
+                                                       const float *__restrict__ bias, bf16_t *__restrict__ out,
+                                                       int relu, int N, int H, int W, int Co, unsigned in_bytes)
+{
+    constexpr int NW = 4, BC = 64, SROW = BC + 4;
+    constexpr unsigned OOB = 0x80000000u;
+    extern __shared__ __align__(16) unsigned char smem[];
+    const lds_addr_of lds_of(smem);
+    uint16_t *sO = reinterpret_cast<uint16_t *>(smem);                        // [256][SROW] (epilogue)
+    uint16_t *halo = sO;                                                      // [324 (+60)][8], dead before sO is written
+    float *sBias = reinterpret_cast<float *>(sO + 256 * SROW);                // [64]
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int tiles_c = Co / BC, px_tiles = W / PATCH, py_tiles = H / PATCH;
+    const int bid = xcd_remap(blockIdx.x, gridDim.x);
+    const int tile_c = bid % tiles_c;
+    int t = bid / tiles_c;
+    const int X0 = (t % px_tiles) * PATCH;
+    t /= px_tiles;
+    const int Y0 = (t % py_tiles) * PATCH;
+    const int n = t / py_tiles;
+    const int co0 = tile_c * BC;
+
+    __amdgpu_buffer_rsrc_t xrsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t *>(in), 0, (int)in_bytes, 0x00020000);
+    // halo: 324 pixels of 16 bytes = 6 wave-loads (waves 0 and 1 take two, waves 2 and 3 one)
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const int q = i * NW + wave;
+        if (q < 6) {
+            const int hr = q * 64 + lane;
+            const int hy = hr / HALO, hx = hr - hy * HALO;
+            const int y = Y0 - 1 + hy, x = X0 - 1 + hx;
+            const bool ok = hr < HPIX && (unsigned)y < (unsigned)H && (unsigned)x < (unsigned)W;
+            dma16(xrsrc, lds_of(halo + q * 512), ok ? (unsigned)((n * H + y) * W + x) * 16u : OOB);
+        }
+    }
+    if (tid < BC) sBias[tid] = bias ? bias[co0 + tid] : 0.0f;
+
+    // the filter, as MFMA operand fragments: lane -> output channel a*32 + (lane & 31), tap 2kk + (lane >> 5)
+    const int frow = lane & 31, fhalf = lane >> 5;
+    const chunk16 zero16 = {0u, 0u, 0u, 0u};
+    chunk16 fw[2][5];
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int kk = 0; kk < 5; ++kk) {
+            const int tap = 2 * kk + fhalf;
+            fw[a][kk] = tap < 9 ? *reinterpret_cast<const chunk16 *>(wt + ((size_t)(co0 + a * 32 + frow) * 9 + tap) * 8) : zero16;
+        }
+
+    f32x16_t acc[2][2];
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int b = 0; b < 2; ++b)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.0f;
+
+    const int py = 4 * wave + (frow >> 4), px = frow & 15;       // patch pixel of B tile 0 (tile 1: py + 2)
+    __builtin_amdgcn_s_waitcnt(0x0070);                           // halo, filter and bias: everything has landed
+    __syncthreads();
+#pragma unroll
+    for (int kk = 0; kk < 5; ++kk) {
+        const int tap = 2 * kk + fhalf < 9 ? 2 * kk + fhalf : 8;  // the 10th tap multiplies a zero filter
+        const int r = tap / 3, q = tap - r * 3;
+        bf16x8_t fb[2];
+#pragma unroll
+        for (int b = 0; b < 2; ++b)
+            fb[b] = as_frag(*reinterpret_cast<const chunk16 *>(halo + ((py + r + 2 * b) * HALO + px + q) * 8));
+#pragma unroll
+        for (int a = 0; a < 2; ++a)
+#pragma unroll
+            for (int b = 0; b < 2; ++b)
+                acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_frag(fw[a][kk]), fb[b], acc[a][b], 0, 0, 0);
+    }
+
+    // epilogue: as in the halo kernel (stage [pixel][channel] in LDS, leave as 16-byte rows)
+    __syncthreads();                                              // every wave has read its halo pixels
+#pragma unroll
+    for (int a = 0; a < 2; ++a) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int col = a * 32 + 8 * q + 4 * fhalf;
+            const float4 bv = *reinterpret_cast<const float4 *>(sBias + col);
+#pragma unroll
+            for (int b = 0; b < 2; ++b) {
+                const int prow = wave * 64 + b * 32 + frow;
+                float v0 = acc[a][b][4 * q] + bv.x, v1 = acc[a][b][4 * q + 1] + bv.y;
+                float v2 = acc[a][b][4 * q + 2] + bv.z, v3 = acc[a][b][4 * q + 3] + bv.w;
+                if (relu) {
+                    v0 = fmaxf(v0, 0.0f);
+                    v1 = fmaxf(v1, 0.0f);
+                    v2 = fmaxf(v2, 0.0f);
+                    v3 = fmaxf(v3, 0.0f);
+                }
+                chunk8 c8;
+                c8[0] = (uint32_t)f32_to_bf16_bits(v0) | ((uint32_t)f32_to_bf16_bits(v1) << 16);
+                c8[1] = (uint32_t)f32_to_bf16_bits(v2) | ((uint32_t)f32_to_bf16_bits(v3) << 16);
+                *reinterpret_cast<chunk8 *>(sO + prow * SROW + col) = c8;
+            }
+        }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int it = 0; it < 8; ++it) {
+        const int u = tid + it * 256;
+        const int pj = u >> 3, c8i = u & 7;
+        const size_t p = (size_t)(n * H + Y0 + (pj >> 4)) * W + X0 + (pj & 15);
+        const chunk8 lo = *reinterpret_cast<const chunk8 *>(sO + pj * SROW + c8i * 8);
+        const chunk8 hi = *reinterpret_cast<const chunk8 *>(sO + pj * SROW + c8i * 8 + 4);
+        const chunk16 v = {lo[0], lo[1], hi[0], hi[1]};
+        *reinterpret_cast<chunk16 *>(out + p * Co + co0 + c8i * 8) = v;
+    }
+}
+
+// ------------------------------------------------------------------------------------------
 // wgrad with the input halo in LDS
 // ------------------------------------------------------------------------------------------
 // dw[ko][r][s][c] += sum over pixels of dy[pixel][ko] * x[pixel shifted by tap (r,s)][c] for 3x3 /
@@ -605,6 +729,26 @@ hipError_t conv3x3_halo_mfma(const void *in, const void *wt, const float *bias, 
     if (!conv3x3_halo_supported(g)) return hipErrorInvalidValue;
     if (g.Co % 128 == 0) return launch_halo<128>(in, wt, bias, out, relu, epi, g, nullptr, nullptr, s);
     return launch_halo<64>(in, wt, bias, out, relu, epi, g, nullptr, nullptr, s);
+}
+
+bool conv3x3_c8_supported(const GatherConv &g)
+{
+    return g.R == 3 && g.S == 3 && g.s_out == 1 && g.s_in == 1 && g.pad_h == 1 && g.pad_w == 1 && g.Hi == g.Ho &&
+           g.Wi == g.Wo && g.Ho % PATCH == 0 && g.Wo % PATCH == 0 && g.Ci == 8 && g.Co % 64 == 0 &&
+           (long long)g.N * g.Hi * g.Wi * 16 < (1ll << 31) && (long long)g.N * g.Ho * g.Wo * g.Co < (1ll << 40);
+}
+
+hipError_t conv3x3_c8_mfma(const void *in, const void *wt, const float *bias, void *out, int relu,
+                           const GatherConv &g, hipStream_t s)
+{
+    if (!conv3x3_c8_supported(g)) return hipErrorInvalidValue;
+    constexpr size_t smem = (size_t)256 * 68 * 2 + 64 * sizeof(float);
+    static_assert(smem <= 40 * 1024, "four blocks per CU");
+    const unsigned in_bytes = (unsigned)((size_t)g.N * g.Hi * g.Wi * 16);
+    dim3 grid((unsigned)(g.N * (g.Ho / PATCH) * (g.Wo / PATCH) * (g.Co / 64)));
+    hipLaunchKernelGGL(k_conv3x3_c8, grid, dim3(256), smem, s, (const bf16_t *)in, (const bf16_t *)wt, bias,
+                       (bf16_t *)out, relu, g.N, g.Hi, g.Wi, g.Co, in_bytes);
+    return hipGetLastError();
 }
 
 hipError_t conv3x3_halo_pool_mfma(const void *in, const void *wt, const float *bias, int relu, void *pool_out,

@@ -788,7 +788,7 @@ bool conv_gather_mfma_supported(const GatherConv &g)
 
 size_t conv_gather_mfma_workspace(const GatherConv &g)
 {
-    if (conv3x3_halo_supported(g)) return 0;
+    if (conv3x3_halo_supported(g) || conv3x3_c8_supported(g)) return 0;
     GatherPlan p = gather_plan(g);
     return p.splits > 1 ? (size_t)p.splits * g.N * g.Ho * g.Wo * g.Co * sizeof(float) : 0;
 }
@@ -799,6 +799,7 @@ hipError_t conv_gather_mfma(const void *in, const void *wt, const float *bias, v
     if (!conv_gather_mfma_supported(g)) return hipErrorInvalidValue;
     if ((long long)g.N * g.Ho * g.Wo == 0) return hipSuccess;
     if (conv3x3_halo_supported(g)) return conv3x3_halo_mfma(in, wt, bias, out, relu, epi, g, s);
+    if (!epi.gate && !epi.accum && conv3x3_c8_supported(g)) return conv3x3_c8_mfma(in, wt, bias, out, relu, g, s);
     const GatherPlan p = gather_plan(g);
     if (p.bp == 64) return launch_gather<64, 128, 1, 4, 32, 3>(in, wt, bias, out, relu, epi, g, p, workspace, s);
     if (p.bc == 64) return launch_gather<256, 64, 4, 1, 32, 3>(in, wt, bias, out, relu, epi, g, p, workspace, s);

@@ -42,6 +42,8 @@ def test_conv_layer(dtype, k, stride, cin, cout, hw, relu):
     (3, 1, 64, 64, (32, 48), 2),      # sides multiple of 16: halo-in-LDS kernel, 64-channel tile
     (3, 1, 128, 128, (16, 32), 3),    # halo kernel, two 64-channel input slices, 128-channel tile
     (3, 1, 128, 192, (32, 16), 1),    # halo kernel, 192 = 3 x 64 output channels
+    (3, 1, 3, 64, (16, 32), 3),       # RGB input padded to 8 channels: first-layer kernel
+    (3, 1, 3, 128, (32, 16), 2),      # ... two 64-channel output tiles
 ])
 def test_conv_mfma_tiling(k, stride, cin, cout, hw, mb):
     st = single(lambda b: b.conv(cin, cout, k, stride=stride, relu=1, src=-1), cin, hw, C.BF16, micro_batch=mb)
