@@ -14,8 +14,9 @@ import os
 import sys
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-CLASSES = {"gather": "k_gather_mfma", "wgrad": "k_wgrad_mfma", "direct": "k_conv_", "pool": "k_pool_",
-           "bn": "k_bn_", "eltwise": "k_grad_copy"}
+# kernel class of the library's timing tap -> kernel name fragments
+CLASSES = {"gather": ("k_gather_mfma", "k_conv3x3_halo", "k_conv3x3_c8"), "wgrad": ("k_wgrad_mfma", "k_wgrad3x3_halo"),
+           "direct": ("k_conv_",), "pool": ("k_pool_",), "bn": ("k_bn_",), "eltwise": ("k_grad_copy",)}
 COPY_BYTES = float(1 << 30)
 
 
@@ -72,8 +73,8 @@ def main():
             fv, wv = F.get(k, [0.0]), W.get(k, [0.0])
             lines.append("| `%s` | %d | %.1f | %.1f |" % (k[:70], len(fv), sum(fv) / len(fv) / ff / 1e6, sum(wv) / len(wv) / wf / 1e6))
         for cls, pat in CLASSES.items():
-            fv = [v for k, vs in F.items() if pat in k for v in vs]
-            wv = [v for k, vs in W.items() if pat in k for v in vs]
+            fv = [v for k, vs in F.items() if any(x in k for x in pat) for v in vs]
+            wv = [v for k, vs in W.items() if any(x in k for x in pat) for v in vs]
             if fv or wv:
                 n = max(len(fv), len(wv))
                 traffic[cls] = (sum(fv) / ff + sum(wv) / wf) / n
