@@ -24,7 +24,9 @@ EXPORTS = [
     "bapipe_stage_get_grads", "bapipe_stage_get_pool_indices", "bapipe_stage_get_loss",
     "bapipe_stage_stash_bytes", "bapipe_last_error", "bapipe_stage_destroy",
     "bapipe_stage_kernel_timing", "bapipe_stage_kernel_timing_read",
+    "bapipe_schedule_cost", "bapipe_partition",
 ]
+PLAN_1F1B_AS, PLAN_FBP_AS, PLAN_1F1B_SNO, PLAN_1F1B_SO = range(4)
 KC_CONV_GATHER_MFMA, KC_CONV_WGRAD_MFMA, KC_CONV_DIRECT, KC_POOL, KC_BATCHNORM, KC_ELEMENTWISE = range(6)
 
 
@@ -247,3 +249,55 @@ def make_opts(stage, io_layout=NHWC, stream=0, allocator=None, loss_scale=0.0, s
     if allocator is not None:
         o.mem = allocator.struct()
     return o
+
+
+# ---------------------------------------------------------------- planner (include/bapipe_plan.h)
+class ScheduleCost(ct.Structure):
+    _fields_ = [("minibatch_time", ct.c_double), ("bubble_fraction", ct.c_double), ("features_memory", ct.c_double),
+                ("weights_memory", ct.c_double), ("bandwidth_demand", ct.c_double), ("in_flight", ct.c_int)]
+
+
+class PlanInput(ct.Structure):
+    _fields_ = [("n_layers", ct.c_int), ("n_acc", ct.c_int), ("fwd_ms", ct.POINTER(ct.c_double)),
+                ("bwd_ms", ct.POINTER(ct.c_double)), ("out_bytes", ct.POINTER(ct.c_double)),
+                ("weight_bytes", ct.POINTER(ct.c_double)), ("stash_bytes", ct.POINTER(ct.c_double)),
+                ("mem_capacity", ct.POINTER(ct.c_double)), ("link_bytes_per_ms", ct.c_double),
+                ("n_micro", ct.c_int), ("schedule", ct.c_int)]
+
+
+class PlanReport(ct.Structure):
+    _fields_ = [("ideal_stage_ms", ct.c_double), ("seed_bottleneck_ms", ct.c_double), ("bottleneck_ms", ct.c_double),
+                ("a_th_bytes", ct.c_double), ("comm_bottleneck", ct.c_int), ("memory_tuned", ct.c_int)]
+
+
+def bapipe_schedule_cost(schedule, M, N, i, F, B, SR, a, w):
+    out = ScheduleCost()
+    _check(load().bapipe_schedule_cost(int(schedule), int(M), int(N), int(i), ct.c_double(F), ct.c_double(B),
+                                       ct.c_double(SR), ct.c_double(a), ct.c_double(w), ct.byref(out)))
+    return {k: getattr(out, k) for k, _ in ScheduleCost._fields_}
+
+
+def _darr(values):
+    values = [float(v) for v in values]
+    return (ct.c_double * len(values))(*values)
+
+
+def bapipe_partition(fwd_ms, bwd_ms, out_bytes, weight_bytes, stash_bytes, mem_capacity=None, link_bytes_per_ms=0.0,
+                     n_micro=1, schedule=PLAN_1F1B_SO):
+    """fwd_ms / bwd_ms: one row of per-layer times per accelerator.  Returns (stage_begin, report);
+    raises BapipeError (status E_UNSUPPORTED: nothing satisfies the constraints)."""
+    n_acc, n_layers = len(fwd_ms), len(fwd_ms[0])
+    keep = [_darr([v for row in fwd_ms for v in row]), _darr([v for row in bwd_ms for v in row]), _darr(out_bytes),
+            _darr(weight_bytes), _darr(stash_bytes), _darr(mem_capacity) if mem_capacity is not None else None]
+    inp = PlanInput(n_layers, n_acc, keep[0], keep[1], keep[2], keep[3], keep[4],
+                    keep[5] if keep[5] is not None else ct.POINTER(ct.c_double)(), float(link_bytes_per_ms),
+                    int(n_micro), int(schedule))
+    sb = (ct.c_int * (n_acc + 1))()
+    rep = PlanReport()
+    status = load().bapipe_partition(ct.byref(inp), sb, ct.byref(rep))
+    report = {k: getattr(rep, k) for k, _ in PlanReport._fields_}
+    if status != OK:
+        err = BapipeError(status, "no partition satisfies the constraints" if status == E_UNSUPPORTED else "bad planner input")
+        err.report = report
+        raise err
+    return list(sb), report

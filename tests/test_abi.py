@@ -13,15 +13,18 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
 def header_functions():
-    src = open(os.path.join(ROOT, "include", "bapipe_stage.h")).read()
-    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
-    return sorted(set(re.findall(r"\b(bapipe_[a-z_]+)\s*\(", src)))
+    names = set()
+    for h in ("bapipe_stage.h", "bapipe_plan.h"):
+        src = open(os.path.join(ROOT, "include", h)).read()
+        src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+        names |= set(re.findall(r"\b(bapipe_[a-z0-9_]+)\s*\(", src))
+    return sorted(names)
 
 
 def test_library_exports_every_declared_function():
     lib = B.load()
     names = header_functions()
-    assert len(names) >= 13
+    assert len(names) >= 15
     for n in names:
         assert hasattr(lib, n), n
     assert sorted(B.EXPORTS) == names

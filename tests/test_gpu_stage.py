@@ -1,5 +1,7 @@
 """GPU parity: the HIP library (through its C ABI) against the CPU oracle, element by element,
 on seeded workloads small enough for the oracle yet spanning several tiles with ragged tails."""
+import math
+
 import numpy as np
 import pytest
 
@@ -129,6 +131,21 @@ def test_config1_tiny_fp32_full_size():
 ])
 def test_shrunken_workloads_bf16(name, stage):
     compare_minibatch(stage, verbose=name)
+
+
+def test_profile_feeds_the_partition_explorer():
+    """The per-layer profile measured on the device is what the host-side planner consumes."""
+    st = C.vgg16_stage1(c1=16, c2=24, hw=20, micro_batch=3, n_micro=5)
+    g = GpuStage(st, gen.all_params(st))
+    prof = B.bapipe_profile_layers(g.h, 1, 2, len(st["layers"]))
+    g.close()
+    assert all(p["fwd_ms"] >= 0 and p["bwd_ms"] >= 0 for p in prof) and sum(p["fwd_ms"] + p["bwd_ms"] for p in prof) > 0
+    f, b = [p["fwd_ms"] for p in prof], [p["bwd_ms"] for p in prof]
+    sb, rep = B.bapipe_partition([f, f], [b, b], [p["out_feature_bytes"] for p in prof], [p["weight_bytes"] for p in prof],
+                                 [p["stash_bytes"] for p in prof], n_micro=5, schedule=B.PLAN_1F1B_SO)
+    assert sb[0] == 0 and sb[-1] == len(prof) and 0 < sb[1] < len(prof)
+    total = sum(f) + sum(b)
+    assert total / 2 * (1 - 1e-9) <= rep["bottleneck_ms"] <= total and math.isclose(rep["ideal_stage_ms"], total / 2, rel_tol=1e-9)
 
 
 def test_schedule_violations_and_stash_depth():
