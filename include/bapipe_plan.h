@@ -45,6 +45,26 @@ typedef struct {
 int bapipe_schedule_cost(int schedule, int M, int N, int i, double F, double B, double SR,
                          double a, double w, bapipe_schedule_cost_t *out);
 
+/* One way of running a mini-batch that the planner may pick (Sec. III-A-2, last paragraph: the
+ * schedule is chosen from the hardware limits, the profile and the partition).  A candidate is
+ * a schedule together with the micro-batch split it would run at - doubling the warm-up
+ * (1F1B-SO) doubles the features memory, so it may only fit with smaller, hence more and
+ * possibly less efficient, micro-batches, whose F, B, SR and feature sizes come from a profile
+ * taken at that micro-batch size. */
+typedef struct {
+    int schedule;         /* bapipe_schedule_t                                            */
+    int n_micro;          /* M for this candidate                                         */
+    double F, B, SR;      /* per micro-batch of this candidate's size, slowest stage      */
+    const double *a;      /* [N] features bytes per in-flight micro-batch, per stage      */
+} bapipe_schedule_candidate_t;
+
+/* Among the candidates whose every stage i fits (in-flight x a[i] + 2 w[i] <= capacity[i];
+ * capacity[i] <= 0 or capacity == NULL: unlimited) pick the one with the smallest mini-batch
+ * time; ties go to the earlier candidate.  *best receives its index, *cost (optional) its cost
+ * evaluated for stage 1.  BAPIPE_E_UNSUPPORTED if none fits, E_INVALID on bad arguments. */
+int bapipe_schedule_choose(const bapipe_schedule_candidate_t *cand, int n_cand, int N, const double *w,
+                           const double *capacity, int *best, bapipe_schedule_cost_t *cost);
+
 /* Per-layer profile of the whole network as the explorer reads it (Sec. III-B-1: how many
  * accelerators there are and, for each kind of accelerator, every layer's forward and backward
  * time).  Arrays are indexed [acc * n_layers + layer] where marked per accelerator, else [layer]. */

@@ -154,6 +154,16 @@ int bapipe_stage_step(bapipe_stage_t *st, float lr);
 int bapipe_profile_layers(bapipe_stage_t *st, int warmup, int iters,
                           bapipe_layer_profile_t *out, int cap, int *n);
 
+/* The same profile taken at several micro-batch sizes (Sec. III-A-2: on GPUs small batches may
+ * not fill the device, so the profile has to treat the batch size as a variable).  For each of
+ * the n_sizes entries of micro_batches a temporary stage is created from the layer list
+ * (n_micro = 1, otherwise opts as given), profiled as above and destroyed.  out: host array of
+ * n_sizes x n_layers records, row k holding the profile at micro_batches[k].  Errors are those
+ * of bapipe_stage_create / bapipe_profile_layers; nothing is left allocated. */
+int bapipe_profile_sweep(const bapipe_layer_desc_t *layers, int n_layers, const int *micro_batches,
+                         int n_sizes, const bapipe_stage_opts_t *opts, int warmup, int iters,
+                         bapipe_layer_profile_t *out);
+
 /* Parameter / result access for checkpoints and parity checks (host buffers, float,
  * PyTorch layouts as described above).  w_host / b_host may be NULL to skip.  Layers
  * without parameters: E_INVALID.  These calls synchronise the stream. */

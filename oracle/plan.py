@@ -84,3 +84,17 @@ def best_bottleneck(p, a_th=None, use_memory=False):
         if best is None or t < best:
             best = t
     return best
+
+
+def choose_schedule(candidates, w, capacity=None):
+    """Index of the memory-feasible candidate with the smallest mini-batch time (first wins ties), or None."""
+    N = len(w)
+    best = None
+    for c, k in enumerate(candidates):
+        costs = [schedule_cost(k["schedule"], k["n_micro"], N, i, k["F"], k["B"], k["SR"], k["a"][i - 1], w[i - 1])
+                 for i in range(1, N + 1)]
+        fits = all(not (capacity and capacity[i] > 0) or costs[i]["in_flight"] * k["a"][i] + 2 * w[i] <= capacity[i]
+                   for i in range(N))
+        if fits and (best is None or costs[0]["minibatch_time"] < best[1]):
+            best = (c, costs[0]["minibatch_time"])
+    return None if best is None else best[0]

@@ -20,11 +20,11 @@ SCHED_1F1B, SCHED_1F1B_SO = 0, 1
 
 EXPORTS = [
     "bapipe_stage_create", "bapipe_stage_forward", "bapipe_stage_backward", "bapipe_stage_step",
-    "bapipe_profile_layers", "bapipe_stage_set_params", "bapipe_stage_get_params",
+    "bapipe_profile_layers", "bapipe_profile_sweep", "bapipe_stage_set_params", "bapipe_stage_get_params",
     "bapipe_stage_get_grads", "bapipe_stage_get_pool_indices", "bapipe_stage_get_loss",
     "bapipe_stage_stash_bytes", "bapipe_last_error", "bapipe_stage_destroy",
     "bapipe_stage_kernel_timing", "bapipe_stage_kernel_timing_read",
-    "bapipe_schedule_cost", "bapipe_partition",
+    "bapipe_schedule_cost", "bapipe_schedule_choose", "bapipe_partition",
 ]
 PLAN_1F1B_AS, PLAN_FBP_AS, PLAN_1F1B_SNO, PLAN_1F1B_SO = range(4)
 KC_CONV_GATHER_MFMA, KC_CONV_WGRAD_MFMA, KC_CONV_DIRECT, KC_POOL, KC_BATCHNORM, KC_ELEMENTWISE = range(6)
@@ -178,6 +178,18 @@ def bapipe_profile_layers(h, warmup, iters, n_layers):
             for i in range(n.value)]
 
 
+def bapipe_profile_sweep(layers, micro_batches, opts, warmup=1, iters=3):
+    """Per-layer profile at each micro-batch size: {size: [record per layer]}."""
+    descs = make_layer_array(layers)
+    sizes = (ct.c_int * len(micro_batches))(*[int(m) for m in micro_batches])
+    out = (LayerProfile * (len(layers) * len(micro_batches)))()
+    _check(load().bapipe_profile_sweep(descs, len(layers), sizes, len(micro_batches), ct.byref(opts), warmup, iters, out))
+    n = len(layers)
+    return {int(m): [dict(fwd_ms=out[k * n + i].fwd_ms, bwd_ms=out[k * n + i].bwd_ms, weight_bytes=out[k * n + i].weight_bytes,
+                          out_feature_bytes=out[k * n + i].out_feature_bytes, stash_bytes=out[k * n + i].stash_bytes)
+                     for i in range(n)] for k, m in enumerate(micro_batches)}
+
+
 def _fptr(a):
     return None if a is None else a.ctypes.data_as(ct.POINTER(ct.c_float))
 
@@ -275,6 +287,24 @@ def bapipe_schedule_cost(schedule, M, N, i, F, B, SR, a, w):
     _check(load().bapipe_schedule_cost(int(schedule), int(M), int(N), int(i), ct.c_double(F), ct.c_double(B),
                                        ct.c_double(SR), ct.c_double(a), ct.c_double(w), ct.byref(out)))
     return {k: getattr(out, k) for k, _ in ScheduleCost._fields_}
+
+
+class ScheduleCandidate(ct.Structure):
+    _fields_ = [("schedule", ct.c_int), ("n_micro", ct.c_int), ("F", ct.c_double), ("B", ct.c_double),
+                ("SR", ct.c_double), ("a", ct.POINTER(ct.c_double))]
+
+
+def bapipe_schedule_choose(candidates, w, capacity=None):
+    """candidates: dicts with schedule, n_micro, F, B, SR, a (per-stage list).  Returns (index, cost of stage 1)."""
+    N = len(w)
+    keep = [_darr(c["a"]) for c in candidates]
+    arr = (ScheduleCandidate * len(candidates))(*[
+        ScheduleCandidate(int(c["schedule"]), int(c["n_micro"]), float(c["F"]), float(c["B"]), float(c["SR"]), k)
+        for c, k in zip(candidates, keep)])
+    best, cost = ct.c_int(-1), ScheduleCost()
+    _check(load().bapipe_schedule_choose(arr, len(candidates), N, _darr(w), _darr(capacity) if capacity is not None else None,
+                                         ct.byref(best), ct.byref(cost)))
+    return best.value, {k: getattr(cost, k) for k, _ in ScheduleCost._fields_}
 
 
 def _darr(values):

@@ -223,6 +223,37 @@ extern "C" int bapipe_schedule_cost(int schedule, int M, int N, int i, double F,
     return BAPIPE_OK;
 }
 
+extern "C" int bapipe_schedule_choose(const bapipe_schedule_candidate_t *cand, int n_cand, int N, const double *w,
+                                      const double *capacity, int *best, bapipe_schedule_cost_t *cost)
+{
+    if (!cand || n_cand < 1 || N < 1 || !w || !best) return BAPIPE_E_INVALID;
+    int pick = -1;
+    bapipe_schedule_cost_t pick_cost{};
+    for (int c = 0; c < n_cand; ++c) {
+        const bapipe_schedule_candidate_t &k = cand[c];
+        if (!k.a) return BAPIPE_E_INVALID;
+        bool fits = true;
+        bapipe_schedule_cost_t first{};
+        for (int i = 1; i <= N; ++i) {
+            bapipe_schedule_cost_t sc;
+            const int st = bapipe_schedule_cost(k.schedule, k.n_micro, N, i, k.F, k.B, k.SR, k.a[i - 1], w[i - 1], &sc);
+            if (st != BAPIPE_OK) return st;
+            if (i == 1) first = sc;
+            const double cap = capacity ? capacity[i - 1] : 0.0;
+            // memory actually held: the in-flight count never exceeds the M micro-batches that exist
+            if (cap > 0.0 && (double)sc.in_flight * k.a[i - 1] + sc.weights_memory > cap) fits = false;
+        }
+        if (fits && (pick < 0 || first.minibatch_time < pick_cost.minibatch_time)) {
+            pick = c;
+            pick_cost = first;
+        }
+    }
+    if (pick < 0) return BAPIPE_E_UNSUPPORTED;
+    *best = pick;
+    if (cost) *cost = pick_cost;
+    return BAPIPE_OK;
+}
+
 extern "C" int bapipe_partition(const bapipe_plan_input_t *in, int *stage_begin, bapipe_plan_report_t *report)
 {
     if (!in || !stage_begin || !report || in->n_layers < 1 || in->n_acc < 1 || in->n_acc > in->n_layers ||

@@ -1171,4 +1171,22 @@ int bapipe_profile_layers(bapipe_stage_t *st, int warmup, int iters, bapipe_laye
     return rc;
 }
 
+int bapipe_profile_sweep(const bapipe_layer_desc_t *layers, int n_layers, const int *micro_batches, int n_sizes,
+                         const bapipe_stage_opts_t *opts, int warmup, int iters, bapipe_layer_profile_t *out)
+{
+    if (!layers || n_layers <= 0 || !micro_batches || n_sizes <= 0 || !opts || !out) return BAPIPE_E_INVALID;
+    std::vector<bapipe_layer_profile_t> all((size_t)n_sizes * n_layers);
+    for (int k = 0; k < n_sizes; ++k) {
+        bapipe_stage_t *st = nullptr;
+        int rc = bapipe_stage_create(layers, n_layers, micro_batches[k], 1, opts, &st);
+        if (rc != BAPIPE_OK) return rc;
+        int n = 0;
+        rc = bapipe_profile_layers(st, warmup, iters, all.data() + (size_t)k * n_layers, n_layers, &n);
+        bapipe_stage_destroy(st);
+        if (rc != BAPIPE_OK) return rc;
+    }
+    for (size_t i = 0; i < all.size(); ++i) out[i] = all[i];
+    return BAPIPE_OK;
+}
+
 }  // extern "C"

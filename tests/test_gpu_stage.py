@@ -148,6 +148,23 @@ def test_profile_feeds_the_partition_explorer():
     assert total / 2 * (1 - 1e-9) <= rep["bottleneck_ms"] <= total and math.isclose(rep["ideal_stage_ms"], total / 2, rel_tol=1e-9)
 
 
+def test_profile_sweep_over_micro_batch_sizes():
+    st = C.vgg16_stage1(c1=16, c2=24, hw=20, micro_batch=4, n_micro=2)
+    import torch
+    alloc = B.TorchAllocator("cuda:0")
+    opts = B.make_opts(st, io_layout=B.NHWC, stream=torch.cuda.current_stream().cuda_stream, allocator=alloc)
+    sweep = B.bapipe_profile_sweep(st["layers"], [2, 4, 8], opts, warmup=1, iters=2)
+    assert sorted(sweep) == [2, 4, 8]
+    for mb, prof in sweep.items():
+        assert len(prof) == len(st["layers"]) and all(p["fwd_ms"] >= 0 and p["bwd_ms"] >= 0 for p in prof)
+    for i in range(len(st["layers"])):                      # sizes scale with the micro-batch, weights do not
+        assert sweep[8][i]["out_feature_bytes"] == 4 * sweep[2][i]["out_feature_bytes"]
+        assert sweep[8][i]["weight_bytes"] == sweep[2][i]["weight_bytes"]
+    with pytest.raises(B.BapipeError) as e:
+        B.bapipe_profile_sweep(st["layers"], [2, 0], opts)
+    assert e.value.status == B.E_INVALID
+
+
 def test_schedule_violations_and_stash_depth():
     st = C.vgg16_deep(cin=8, c=8, hw=4, micro_batch=2, n_micro=4)        # stage 3 of 4: depth 2
     g = GpuStage(st, gen.all_params(st))

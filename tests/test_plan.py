@@ -90,6 +90,37 @@ def test_schedule_cost_rejects_bad_arguments():
         assert e.value.status == B.E_INVALID
 
 
+def test_schedule_choice():
+    # the paper's trade-off: overlap (SO) wins when its doubled features fit, otherwise it needs half-size
+    # micro-batches (twice as many, each a bit less efficient) and may lose to the naive schedule
+    w, a_full, a_half = [1e9, 1e9], [4e9, 4e9], [2e9, 2e9]
+    cands = [dict(schedule=B.PLAN_1F1B_SNO, n_micro=8, F=1.0, B=2.0, SR=0.5, a=a_full),
+             dict(schedule=B.PLAN_1F1B_SO, n_micro=8, F=1.0, B=2.0, SR=0.5, a=a_full),
+             dict(schedule=B.PLAN_1F1B_SO, n_micro=16, F=0.6, B=1.2, SR=0.25, a=a_half)]
+    assert B.bapipe_schedule_choose(cands, w)[0] == 1                                  # unlimited memory
+    assert B.bapipe_schedule_choose(cands, w, [2e9 + 2 * 4e9] * 2)[0] == 0              # SO at full size needs 4 x 4e9 on stage 1
+    slow_half = [cands[0], cands[1], dict(cands[2], F=0.9, B=1.8)]
+    assert B.bapipe_schedule_choose(slow_half, w, [2e9 + 2 * 4e9] * 2)[0] == 0
+    fast_half = [cands[0], cands[1], dict(cands[2], F=0.5, B=1.0)]
+    assert B.bapipe_schedule_choose(fast_half, w, [2e9 + 2 * 4e9] * 2)[0] == 2
+    with pytest.raises(B.BapipeError) as e:
+        B.bapipe_schedule_choose(cands, w, [1e9] * 2)
+    assert e.value.status == B.E_UNSUPPORTED
+    rng = random.Random(23)
+    for _ in range(200):
+        N = rng.randint(1, 5)
+        ww = [rng.uniform(0, 2e9) for _ in range(N)]
+        cs = [dict(schedule=rng.choice(SCHEDULES), n_micro=rng.randint(1, 32), F=rng.uniform(0.1, 3), B=rng.uniform(0.1, 6),
+                   SR=rng.uniform(0, 1), a=[rng.uniform(0, 4e9) for _ in range(N)]) for _ in range(rng.randint(1, 5))]
+        cap = [rng.choice([0.0, 4e9, 1.6e10, 6e10]) for _ in range(N)]
+        ref = O.choose_schedule(cs, ww, cap)
+        if ref is None:
+            with pytest.raises(B.BapipeError):
+                B.bapipe_schedule_choose(cs, ww, cap)
+        else:
+            assert B.bapipe_schedule_choose(cs, ww, cap)[0] == ref
+
+
 def random_profile(rng, L, N, hetero):
     speed = [rng.uniform(0.5, 2.0) if hetero else 1.0 for _ in range(N)]
     base_f = [rng.choice([0.05, 0.2, 1.0, 3.0]) * rng.uniform(0.5, 1.5) for _ in range(L)]
