@@ -674,7 +674,7 @@ __global__ __launch_bounds__(WKO *WCI * 64, 2) void k_wgrad_mfma(const bf16_t *_
     }
     WAIT_VMCNT(0);
 
-    // partial[split][ko][n]: lanes of a wave write 32 consecutive n (128 bytes)
+    // partial[split][ko][n]
     float *dst = part + (size_t)blockIdx.y * split_stride;
     const int col = lane & 31, half = lane >> 5;
     if (do_bias) {
@@ -686,20 +686,39 @@ __global__ __launch_bounds__(WKO *WCI * 64, 2) void k_wgrad_mfma(const bf16_t *_
             if (half == 0 && ko < c.K) bdst[ko] = add_to_dst ? bdst[ko] + t : t;
         }
     }
+    // The accumulators leave through LDS: each wave parks one 32-row slice of its sub-tile in a region
+    // of its own ([32][WT_CI] floats; the ring is free by now) and reads it back as float4 so that 16
+    // lanes cover 256 contiguous bytes of one dw row.  Straight from the registers a row segment would
+    // be 32 separate 4-byte read-modify-writes.
+    __syncthreads();                                          // every wave has left the ring
+    float *stg = reinterpret_cast<float *>(smem) + wave * (32 * WT_CI);
+    constexpr int F4R = WT_CI / 4;                            // float4 per staged row
+    constexpr int RPI = 64 / F4R;                             // rows one wave-wide access covers
 #pragma unroll
-    for (int a = 0; a < TA; ++a)
+    for (int a = 0; a < TA; ++a) {
 #pragma unroll
-        for (int b = 0; b < TB; ++b) {
-            const int n = n0 + wi * WT_CI + b * 32 + col;
+        for (int b = 0; b < TB; ++b)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int ko = ko0 + wk * WT_KO + a * 32 + 8 * (v >> 2) + 4 * half + (v & 3);
-                if (ko < c.K && n < Ntot) {
-                    float *d = dst + (size_t)ko * Ntot + n;
-                    *d = add_to_dst ? *d + acc[a][b][v] : acc[a][b][v];     // single split: straight into dw
+            for (int v = 0; v < 16; ++v) stg[(8 * (v >> 2) + 4 * half + (v & 3)) * WT_CI + b * 32 + col] = acc[a][b][v];
+        WAIT_LGKMCNT(0);
+        __builtin_amdgcn_wave_barrier();
+#pragma unroll
+        for (int it = 0; it < 32 / RPI; ++it) {
+            const int row = it * RPI + lane / F4R, c4 = (lane % F4R) * 4;
+            const int ko = ko0 + wk * WT_KO + a * 32 + row, n = n0 + wi * WT_CI + c4;
+            if (ko < c.K && n < Ntot) {
+                float4 t = *reinterpret_cast<const float4 *>(stg + row * WT_CI + c4);
+                float4 *d = reinterpret_cast<float4 *>(dst + (size_t)ko * Ntot + n);
+                if (add_to_dst) {                                 // single split: straight into dw
+                    const float4 o = *d;
+                    t.x += o.x; t.y += o.y; t.z += o.z; t.w += o.w;
                 }
+                *d = t;
             }
         }
+        WAIT_LGKMCNT(0);
+        __builtin_amdgcn_wave_barrier();
+    }
 }
 
 // dw[i] += sum_k part[k][i].  A block owns 64 float4 columns; its 4 split-lanes walk the partials

@@ -512,19 +512,28 @@ template <class T> __global__ void k_recast(const float *__restrict__ w, T *__re
     if (i < n) work[i] = from_f32<T>(w[i]);
 }
 
+// wt[c][r][s][k] = w[k][R-1-r][S-1-s][c] in storage type: per tap a K x C -> C x K transpose, done
+// on 64 x 64 tiles through LDS so that both the fp32 reads (along c) and the writes (along k) are
+// contiguous.  grid: (C tiles, K tiles, R*S)
 template <class T>
 __global__ void k_dgrad_filter(const float *__restrict__ w, T *__restrict__ wt, int K, int R, int S, int C)
 {
-    size_t i = (size_t)blockIdx.x * TPB + threadIdx.x;
-    size_t total = (size_t)K * R * S * C;
-    if (i >= total) return;
-    int k = (int)(i % K);
-    size_t t = i / K;
-    int s = (int)(t % S);
-    t /= S;
-    int r = (int)(t % R);
-    int c = (int)(t / R);
-    wt[i] = from_f32<T>(w[(((size_t)k * R + (R - 1 - r)) * S + (S - 1 - s)) * C + c]);
+    __shared__ float tile[64][65];
+    const int c0 = blockIdx.x * 64, k0 = blockIdx.y * 64;
+    const int tap = blockIdx.z, r = tap / S, q = tap - r * S;
+    const int src_tap = (R - 1 - r) * S + (S - 1 - q);
+    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;          // 64 x 4
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        const int k = k0 + ty + 4 * i, c = c0 + tx;
+        tile[ty + 4 * i][tx] = (k < K && c < C) ? w[((size_t)k * R * S + src_tap) * C + c] : 0.0f;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        const int c = c0 + ty + 4 * i, k = k0 + tx;
+        if (c < C && k < K) wt[((size_t)c * R * S + tap) * K + k] = from_f32<T>(tile[tx][ty + 4 * i]);
+    }
 }
 
 __global__ void k_fill(float *p, float v, size_t n)
@@ -828,7 +837,8 @@ hipError_t make_dgrad_filter(int dt, const float *w, void *wt, int K, int R, int
     size_t n = (size_t)K * R * S * C;
     if (n == 0) return hipSuccess;
     DISPATCH_T(dt, {
-        hipLaunchKernelGGL((k_dgrad_filter<T>), dim3(blocks_for(n)), dim3(TPB), 0, s, w, (T *)wt, K, R, S, C);
+        hipLaunchKernelGGL((k_dgrad_filter<T>), dim3((unsigned)((C + 63) / 64), (unsigned)((K + 63) / 64), (unsigned)(R * S)),
+                           dim3(256), 0, s, w, (T *)wt, K, R, S, C);
     });
     return hipGetLastError();
 }
