@@ -702,19 +702,24 @@ __global__ __launch_bounds__(WKO *WCI * 64, 2) void k_wgrad_mfma(const bf16_t *_
             for (int v = 0; v < 16; ++v) stg[(8 * (v >> 2) + 4 * half + (v & 3)) * WT_CI + b * 32 + col] = acc[a][b][v];
         WAIT_LGKMCNT(0);
         __builtin_amdgcn_wave_barrier();
+        // all reads of the slice first, then all writes: one round trip to memory per slice, not one per row group
+        constexpr int IT = 32 / RPI;
+        float4 t[IT], o[IT];
 #pragma unroll
-        for (int it = 0; it < 32 / RPI; ++it) {
+        for (int it = 0; it < IT; ++it) {
             const int row = it * RPI + lane / F4R, c4 = (lane % F4R) * 4;
             const int ko = ko0 + wk * WT_KO + a * 32 + row, n = n0 + wi * WT_CI + c4;
-            if (ko < c.K && n < Ntot) {
-                float4 t = *reinterpret_cast<const float4 *>(stg + row * WT_CI + c4);
-                float4 *d = reinterpret_cast<float4 *>(dst + (size_t)ko * Ntot + n);
-                if (add_to_dst) {                                 // single split: straight into dw
-                    const float4 o = *d;
-                    t.x += o.x; t.y += o.y; t.z += o.z; t.w += o.w;
-                }
-                *d = t;
-            }
+            t[it] = *reinterpret_cast<const float4 *>(stg + row * WT_CI + c4);
+            o[it] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (add_to_dst && ko < c.K && n < Ntot) o[it] = *reinterpret_cast<const float4 *>(dst + (size_t)ko * Ntot + n);
+        }
+#pragma unroll
+        for (int it = 0; it < IT; ++it) {
+            const int row = it * RPI + lane / F4R, c4 = (lane % F4R) * 4;
+            const int ko = ko0 + wk * WT_KO + a * 32 + row, n = n0 + wi * WT_CI + c4;
+            if (ko < c.K && n < Ntot)
+                *reinterpret_cast<float4 *>(dst + (size_t)ko * Ntot + n) =
+                    make_float4(t[it].x + o[it].x, t[it].y + o[it].y, t[it].z + o[it].z, t[it].w + o[it].w);
         }
         WAIT_LGKMCNT(0);
         __builtin_amdgcn_wave_barrier();
