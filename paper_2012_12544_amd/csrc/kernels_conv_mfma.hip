@@ -547,6 +547,8 @@ __global__ __launch_bounds__(WKO *WCI * 64, 2) void k_wgrad_mfma(const bf16_t *_
     int bp[BL], ph[BL], pw[BL], br[BL], bs[BL];
     unsigned boff[BL];
     const int Qs = c.Q * c.stride, Ps = c.P * c.stride;
+    const bool one_pixel = c.P == 1 && c.Q == 1;
+    const unsigned sample_bytes = (unsigned)(c.H * c.W * c.C) * 2u;
     const unsigned colstep = (unsigned)(c.stride * c.C) * 2u;
     const unsigned rowstep = (unsigned)(c.stride * (c.W - c.Q) * c.C) * 2u;                 // extra, on top of Q columns
     const unsigned imgstep = (unsigned)((c.H - c.P * c.stride) * c.W * c.C) * 2u;           // extra, on top of P rows
@@ -593,6 +595,10 @@ __global__ __launch_bounds__(WKO *WCI * 64, 2) void k_wgrad_mfma(const bf16_t *_
 #pragma unroll
         for (int i = 0; i < BL; ++i) {
             bp[i] += BKP;
+            if (one_pixel) {                     // linear layers: every "pixel" is the next sample
+                boff[i] += BKP * sample_bytes;
+                continue;
+            }
             pw[i] += BKP * c.stride;
             boff[i] += BKP * colstep;
             while (pw[i] >= Qs) {
