@@ -199,13 +199,23 @@ __device__ __forceinline__ void col_partial_body(F f, int rows, ColPlan p, float
     if (active) {
         int r0 = chunk * p.rows_per_chunk, r1 = r0 + p.rows_per_chunk;
         if (r1 > rows) r1 = rows;
-        for (int r = r0 + ry; r < r1; r += p.RY) {
-            float v[NQ][V];
-            f(r, cg, v);
+        // four rows per trip, all loads first (row index clamped, contribution masked): the trip costs one
+        // memory round trip instead of four
+        for (int r = r0 + ry; r < r1; r += 4 * p.RY) {
+            float v[4][NQ][V];
 #pragma unroll
-            for (int qn = 0; qn < NQ; ++qn)
+            for (int u = 0; u < 4; ++u) {
+                const int rr = r + u * p.RY;
+                f(rr < r1 ? rr : r1 - 1, cg, v[u]);
+            }
 #pragma unroll
-                for (int j = 0; j < V; ++j) acc[qn][j] += v[qn][j];
+            for (int u = 0; u < 4; ++u) {
+                const float keep = r + u * p.RY < r1 ? 1.0f : 0.0f;
+#pragma unroll
+                for (int qn = 0; qn < NQ; ++qn)
+#pragma unroll
+                    for (int j = 0; j < V; ++j) acc[qn][j] += keep * v[u][qn][j];
+            }
         }
     }
 #pragma unroll
@@ -237,10 +247,10 @@ __global__ void k_colsum_partial(const T *__restrict__ a, int rows, int C, ColPl
     col_partial_body<T, V, 1>(f, rows, p, part, C);
 }
 
-// Final pass over the per-chunk partials: a block owns 16 channels, 16 lanes per channel walk
-// the chunks with stride 16, and the lanes are combined through LDS in lane order, so the
+// Final pass over the per-chunk partials: a block owns 4 channels, 64 lanes per channel walk
+// the chunks with stride 64, and the lanes are combined through LDS in lane order, so the
 // result does not depend on scheduling.  Returns true in the lane that holds the totals.
-constexpr int FIN_CH = 16, FIN_LANES = TPB / FIN_CH;
+constexpr int FIN_CH = 4, FIN_LANES = TPB / FIN_CH;
 template <int NQ>
 __device__ __forceinline__ bool col_final_sums(const float *__restrict__ part, int chunks, int C, int &c,
                                                double (&tot)[NQ])
@@ -252,9 +262,19 @@ __device__ __forceinline__ bool col_final_sums(const float *__restrict__ part, i
 #pragma unroll
     for (int q = 0; q < NQ; ++q) s[q] = 0.0;
     if (c < C)
-        for (int k = cl; k < chunks; k += FIN_LANES)
+        for (int k = cl; k < chunks; k += 4 * FIN_LANES) {      // four independent loads per quantity and trip
+            float v[4][NQ];
 #pragma unroll
-            for (int q = 0; q < NQ; ++q) s[q] += (double)part[((size_t)q * chunks + k) * C + c];
+            for (int u = 0; u < 4; ++u) {
+                const int kk = k + u * FIN_LANES;
+#pragma unroll
+                for (int q = 0; q < NQ; ++q) v[u][q] = kk < chunks ? part[((size_t)q * chunks + kk) * C + c] : 0.0f;
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+#pragma unroll
+                for (int q = 0; q < NQ; ++q) s[q] += (double)v[u][q];
+        }
 #pragma unroll
     for (int q = 0; q < NQ; ++q) red[q][cl][cc] = s[q];
     __syncthreads();
@@ -332,11 +352,20 @@ __global__ void k_bn_apply(const T *__restrict__ x, const float *__restrict__ ga
     const int r0 = blockIdx.y * (p.RY * BN_ROWS_PER_THREAD);
     int r1 = r0 + p.RY * BN_ROWS_PER_THREAD;
     if (r1 > rows) r1 = rows;
-    for (int r = r0 + ry; r < r1; r += p.RY) {
-        vec_t<T, V> a = xv[(size_t)r * p.CV + cg], o;
+    vec_t<T, V> a[BN_ROWS_PER_THREAD];
+#pragma unroll
+    for (int u = 0; u < BN_ROWS_PER_THREAD; ++u) {            // all loads of the thread first
+        const int r = r0 + ry + u * p.RY;
+        a[u] = xv[(size_t)(r < r1 ? r : r1 - 1) * p.CV + cg];
+    }
+#pragma unroll
+    for (int u = 0; u < BN_ROWS_PER_THREAD; ++u) {
+        const int r = r0 + ry + u * p.RY;
+        if (r >= r1) break;
+        vec_t<T, V> o;
 #pragma unroll
         for (int j = 0; j < V; ++j) {
-            float xh = (to_f32(a.e[j]) - mu[j]) * inv[j];
+            float xh = (to_f32(a[u].e[j]) - mu[j]) * inv[j];
             float v = ga[j] * xh + be[j];
             if (relu) v = fmaxf(v, 0.0f);
             o.e[j] = from_f32<T>(v);
@@ -411,18 +440,32 @@ __global__ void k_bn_bwd_apply(const T *__restrict__ x, const T *__restrict__ dy
     const int r0 = blockIdx.y * (p.RY * BN_ROWS_PER_THREAD);
     int r1 = r0 + p.RY * BN_ROWS_PER_THREAD;
     if (r1 > rows) r1 = rows;
-    for (int r = r0 + ry; r < r1; r += p.RY) {
-        const size_t i = (size_t)r * p.CV + cg;
-        vec_t<T, V> a = xv[i], g = gv[i], old, gt, o;
-        if (accum) old = dv[i];
-        if (gate) gt = tv[i];
+    constexpr int HALF = BN_ROWS_PER_THREAD / 2;
 #pragma unroll
-        for (int j = 0; j < V; ++j) {
-            float xh = (to_f32(a.e[j]) - mu[j]) * inv[j];
-            float v = gi[j] * (to_f32(g.e[j]) - m1[j] - xh * m2[j]);
-            o.e[j] = grad_out<T>(v, accum != 0, old.e[j], gate != nullptr, gt.e[j]);
+    for (int h = 0; h < 2; ++h) {                               // four rows at a time: loads first, then stores
+        vec_t<T, V> a[HALF], g[HALF], old[HALF], gt[HALF];
+#pragma unroll
+        for (int u = 0; u < HALF; ++u) {
+            const int r = r0 + ry + (h * HALF + u) * p.RY;
+            const size_t i = (size_t)(r < r1 ? r : r1 - 1) * p.CV + cg;
+            a[u] = xv[i];
+            g[u] = gv[i];
+            if (accum) old[u] = dv[i];
+            if (gate) gt[u] = tv[i];
         }
-        dv[i] = o;
+#pragma unroll
+        for (int u = 0; u < HALF; ++u) {
+            const int r = r0 + ry + (h * HALF + u) * p.RY;
+            if (r >= r1) break;
+            vec_t<T, V> o;
+#pragma unroll
+            for (int j = 0; j < V; ++j) {
+                float xh = (to_f32(a[u].e[j]) - mu[j]) * inv[j];
+                float v = gi[j] * (to_f32(g[u].e[j]) - m1[j] - xh * m2[j]);
+                o.e[j] = grad_out<T>(v, accum != 0, old[u].e[j], gate != nullptr, gt[u].e[j]);
+            }
+            dv[(size_t)r * p.CV + cg] = o;
+        }
     }
 }
 
