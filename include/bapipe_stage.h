@@ -62,7 +62,8 @@ typedef enum {
     BAPIPE_ADD = 4,          /* y = src0 + src1                                             */
     BAPIPE_FLATTEN = 5,      /* (C,H,W) -> (C*H*W,1,1)                                      */
     BAPIPE_LINEAR = 6,       /* y = x W^T + b                                               */
-    BAPIPE_SOFTMAX_XENT = 7  /* last layer only: p = softmax(z); loss from labels in bwd    */
+    BAPIPE_SOFTMAX_XENT = 7, /* last layer only: p = softmax(z); loss from labels in bwd    */
+    BAPIPE_AVGPOOL2D = 8     /* mean of k x k windows, stride = k, pad = 0 (k = H: global)  */
 } bapipe_layer_kind_t;
 
 /* One layer of the stage.  src0/src1: index of the producing layer in the list, -1 = the

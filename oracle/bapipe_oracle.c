@@ -9,7 +9,9 @@
  * definition of the layer and of its adjoint, written as direct loops:
  *   convolution = cross-correlation with zero padding, Ho = floor((H+2p-k)/s)+1 ;
  *   ReLU backward passes the gradient where the forward output is > 0 ;
- *   max-pool keeps the first maximum in row-major window order ;
+ *   max-pool keeps the first maximum in row-major window order (padded positions are not
+ *   candidates; overlapping windows that pick the same input add their gradients) ;
+ *   average pool is the mean of a k x k window, stride k, its adjoint spreads dy / k^2 ;
  *   batch-norm uses biased per-channel statistics of the given (micro-)batch ;
  *   the loss is softmax cross-entropy scaled by a caller-given factor ;
  *   the update is plain SGD (the paper's 2*w weights memory leaves no optimiser state).
@@ -218,6 +220,40 @@ void orc_maxpool_bwd(const double *dy, const uint8_t *idx, double *dx,
                     d[(size_t)ih * W + iw] += dy[IDX4(n, c, p, q, C, Ho, Wo)];
                 }
         }
+}
+
+/* y[n,c,p,q] = mean of the kh x kw window at (p*kh, q*kw): stride = window, no padding;
+ * rows / columns beyond the last full window are ignored. */
+void orc_avgpool_fwd(const double *x, double *y, int N, int C, int H, int W, int kh, int kw)
+{
+    const int Ho = H / kh, Wo = W / kw;
+#pragma omp parallel for collapse(2) schedule(static)
+    for (int n = 0; n < N; ++n)
+        for (int c = 0; c < C; ++c)
+            for (int p = 0; p < Ho; ++p)
+                for (int q = 0; q < Wo; ++q) {
+                    double s = 0.0;
+                    for (int dh = 0; dh < kh; ++dh)
+                        for (int dw = 0; dw < kw; ++dw)
+                            s += x[IDX4(n, c, p * kh + dh, q * kw + dw, C, H, W)];
+                    y[IDX4(n, c, p, q, C, Ho, Wo)] = s / (double)(kh * kw);
+                }
+}
+
+/* Adjoint of the above: every input of a window receives dy / (kh*kw); inputs outside all
+ * windows receive zero. */
+void orc_avgpool_bwd(const double *dy, double *dx, int N, int C, int H, int W, int kh, int kw)
+{
+    const int Ho = H / kh, Wo = W / kw;
+#pragma omp parallel for collapse(2) schedule(static)
+    for (int n = 0; n < N; ++n)
+        for (int c = 0; c < C; ++c)
+            for (int h = 0; h < H; ++h)
+                for (int w = 0; w < W; ++w) {
+                    const int p = h / kh, q = w / kw;
+                    dx[IDX4(n, c, h, w, C, H, W)] =
+                        (p < Ho && q < Wo) ? dy[IDX4(n, c, p, q, C, Ho, Wo)] / (double)(kh * kw) : 0.0;
+                }
 }
 
 /* Training-mode batch-norm over (N,H,W) per channel:

@@ -114,6 +114,23 @@ def maxpool_bwd(dy, idx, x_shape, k=2, stride=2, pad=0):
     return dx
 
 
+def avgpool_fwd(x, k):
+    x = _f64(x)
+    N, C, H, W = x.shape
+    y = np.empty((N, C, H // k, W // k))
+    lib().orc_avgpool_fwd(_p(x), _p(y), N, C, H, W, k, k)
+    return y
+
+
+def avgpool_bwd(dy, x_shape, k):
+    dy = _f64(dy)
+    N, C, H, W = x_shape
+    assert dy.shape == (N, C, H // k, W // k)
+    dx = np.empty(x_shape)
+    lib().orc_avgpool_bwd(_p(dy), _p(dx), N, C, H, W, k, k)
+    return dx
+
+
 def bn_fwd(x, gamma, beta, eps):
     x, gamma, beta = _f64(x), _f64(gamma), _f64(beta)
     N, C, H, W = x.shape

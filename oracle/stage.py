@@ -8,7 +8,7 @@ micro-batch, at most N-i+1 of them under 1F1B, Table I/II "Features memory"), an
 change once, after the backward passes of the whole mini-batch.
 
 storage="bf16" applies nearest-even bf16 rounding exactly where a tensor would be stored in
-16 bits: each layer's output in forward (conv/linear/BN/add after bias and ReLU), each
+16 bits: each layer's output in forward (conv/linear/BN/add after bias and ReLU, average pool), each
 input-gradient contribution in backward and their sum where a tensor feeds two layers, and
 the working copy of conv/linear weight matrices.  Bias, gamma, beta, weight gradients,
 BN statistics, softmax and loss are never rounded.  storage="exact" rounds nothing.
@@ -87,6 +87,8 @@ class OracleStage:
                 y = ops.relu_fwd(a)
             elif k == C.MAXPOOL2D:
                 y, extra = ops.maxpool_fwd(a, L["kh"], L["stride"], L["pad"])
+            elif k == C.AVGPOOL2D:
+                y = q(ops.avgpool_fwd(a, L["kh"]))
             elif k == C.BATCHNORM2D:
                 y, mean, invstd = ops.bn_fwd(a, self.w[i], self.b[i], L["eps"])
                 extra = (mean, invstd)
@@ -166,6 +168,8 @@ class OracleStage:
                 give(L["src0"], ops.relu_bwd(outs[i], g))
             elif k == C.MAXPOOL2D:
                 give(L["src0"], ops.maxpool_bwd(g, aux[i], a.shape, L["kh"], L["stride"], L["pad"]))
+            elif k == C.AVGPOOL2D:
+                give(L["src0"], ops.avgpool_bwd(g, a.shape, L["kh"]))
             elif k == C.BATCHNORM2D:
                 mean, invstd = aux[i]
                 dx = ops.bn_bwd(a, g, self.w[i], mean, invstd, self.dw[i], self.db[i])

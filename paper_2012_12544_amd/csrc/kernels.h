@@ -80,6 +80,16 @@ hipError_t maxpool2x2_fwd(int dt, const void *x, void *y, uint8_t *idx, int N, i
 // gate (if any) is indexed like dy (the pooled tensor), not like dx.
 hipError_t maxpool2x2_bwd(int dt, const void *dy, const uint8_t *idx, void *dx, GradEpi epi_pooled_gate,
                           int N, int H, int W, int C, hipStream_t s);
+// any window / stride / padding (kh*kw <= 255): idx = dh*kw + dw of the first maximum inside the
+// padded window; backward adds the gradients of all windows that chose an input (fixed order)
+hipError_t maxpool_fwd(int dt, const void *x, void *y, uint8_t *idx, int N, int H, int W, int C, int kh,
+                       int kw, int stride, int pad, hipStream_t s);
+hipError_t maxpool_bwd(int dt, const void *dy, const uint8_t *idx, void *dx, GradEpi epi_pooled_gate, int N,
+                       int H, int W, int C, int kh, int kw, int stride, int pad, hipStream_t s);
+// mean over kh x kw windows at stride (kh, kw), no padding; gate (if any) indexed like dx
+hipError_t avgpool_fwd(int dt, const void *x, void *y, int N, int H, int W, int C, int kh, int kw, hipStream_t s);
+hipError_t avgpool_bwd(int dt, const void *dy, void *dx, GradEpi epi, int N, int H, int W, int C, int kh, int kw,
+                       hipStream_t s);
 hipError_t add_fwd(int dt, const void *a, const void *b, void *y, int relu, size_t n, hipStream_t s);
 // dx (+)= dy with the epilogue of grad_out
 hipError_t grad_copy(int dt, const void *dy, void *dx, GradEpi epi, size_t n, hipStream_t s);

@@ -149,6 +149,163 @@ __global__ void k_pool_bwd(const T *__restrict__ dy, const uint8_t *__restrict__
     }
 }
 
+// ------------------------------------------------------------------ windowed pooling (any window / stride / pad)
+struct PoolWin {
+    int N, H, W, CV, Ho, Wo, kh, kw, stride, pad;
+};
+
+// Max over the in-image part of each window, first maximum in row-major window order; the index
+// stored is dh*kw + dw of the winner inside the (padded) window.
+template <class T, int V>
+__global__ void k_poolw_fwd(const T *__restrict__ x, T *__restrict__ y, uint8_t *__restrict__ idx, PoolWin g)
+{
+    size_t i = (size_t)blockIdx.x * TPB + threadIdx.x;
+    size_t total = (size_t)g.N * g.Ho * g.Wo * g.CV;
+    if (i >= total) return;
+    int cv = (int)(i % g.CV);
+    size_t t = i / g.CV;
+    int q = (int)(t % g.Wo);
+    t /= g.Wo;
+    int p = (int)(t % g.Ho);
+    int n = (int)(t / g.Ho);
+    const vec_t<T, V> *xv = reinterpret_cast<const vec_t<T, V> *>(x);
+    float best[V];
+    int bi[V];
+#pragma unroll
+    for (int j = 0; j < V; ++j) { best[j] = 0.0f; bi[j] = -1; }
+    for (int dh = 0; dh < g.kh; ++dh) {
+        const int ih = p * g.stride + dh - g.pad;
+        if (ih < 0 || ih >= g.H) continue;
+        for (int dw = 0; dw < g.kw; ++dw) {
+            const int iw = q * g.stride + dw - g.pad;
+            if (iw < 0 || iw >= g.W) continue;
+            vec_t<T, V> a = xv[(((size_t)n * g.H + ih) * g.W + iw) * g.CV + cv];
+#pragma unroll
+            for (int j = 0; j < V; ++j) {
+                float v = to_f32(a.e[j]);
+                if (bi[j] < 0 || v > best[j]) { best[j] = v; bi[j] = dh * g.kw + dw; }
+            }
+        }
+    }
+    vec_t<T, V> r;
+    vec_t<uint8_t, V> ri;
+#pragma unroll
+    for (int j = 0; j < V; ++j) {
+        r.e[j] = from_f32<T>(best[j]);
+        ri.e[j] = (uint8_t)(bi[j] < 0 ? 0 : bi[j]);
+    }
+    reinterpret_cast<vec_t<T, V> *>(y)[i] = r;
+    reinterpret_cast<vec_t<uint8_t, V> *>(idx)[i] = ri;
+}
+
+// One thread per INPUT position: it visits the windows that contain the position (in (p,q)
+// order, so the sum is reproducible) and adds the gradient of those whose arg-max it is.
+// `gate`, indexed like dy, holds the pooled forward values: a window whose maximum is not
+// positive passes nothing (its winner was zeroed by the producer's ReLU).
+template <class T, int V>
+__global__ void k_poolw_bwd(const T *__restrict__ dy, const uint8_t *__restrict__ idx, T *dx,
+                            const T *__restrict__ gate, int accum, PoolWin g)
+{
+    size_t i = (size_t)blockIdx.x * TPB + threadIdx.x;
+    size_t total = (size_t)g.N * g.H * g.W * g.CV;
+    if (i >= total) return;
+    int cv = (int)(i % g.CV);
+    size_t t = i / g.CV;
+    int w = (int)(t % g.W);
+    t /= g.W;
+    int h = (int)(t % g.H);
+    int n = (int)(t / g.H);
+    const int hp = h + g.pad, wp = w + g.pad;
+    int p0 = hp - g.kh + 1, q0 = wp - g.kw + 1;
+    p0 = p0 <= 0 ? 0 : (p0 + g.stride - 1) / g.stride;
+    q0 = q0 <= 0 ? 0 : (q0 + g.stride - 1) / g.stride;
+    int p1 = hp / g.stride, q1 = wp / g.stride;
+    p1 = p1 < g.Ho - 1 ? p1 : g.Ho - 1;
+    q1 = q1 < g.Wo - 1 ? q1 : g.Wo - 1;
+    float acc[V];
+#pragma unroll
+    for (int j = 0; j < V; ++j) acc[j] = 0.0f;
+    for (int p = p0; p <= p1; ++p)
+        for (int q = q0; q <= q1; ++q) {
+            const size_t o = (((size_t)n * g.Ho + p) * g.Wo + q) * g.CV + cv;
+            const int want = (hp - p * g.stride) * g.kw + (wp - q * g.stride);
+            vec_t<uint8_t, V> ix = reinterpret_cast<const vec_t<uint8_t, V> *>(idx)[o];
+            vec_t<T, V> gv = reinterpret_cast<const vec_t<T, V> *>(dy)[o], gt;
+            if (gate) gt = reinterpret_cast<const vec_t<T, V> *>(gate)[o];
+#pragma unroll
+            for (int j = 0; j < V; ++j) {
+                bool take = ix.e[j] == want;
+                if (gate) take = take && to_f32(gt.e[j]) > 0.0f;
+                acc[j] += take ? to_f32(gv.e[j]) : 0.0f;
+            }
+        }
+    vec_t<T, V> *dxv = reinterpret_cast<vec_t<T, V> *>(dx);
+    vec_t<T, V> old, r;
+    if (accum) old = dxv[i];
+#pragma unroll
+    for (int j = 0; j < V; ++j) r.e[j] = grad_out<T>(acc[j], accum != 0, old.e[j], false, old.e[j]);
+    dxv[i] = r;
+}
+
+// Mean over kh x kw windows at stride (kh, kw), no padding.
+template <class T, int V>
+__global__ void k_avgpool_fwd(const T *__restrict__ x, T *__restrict__ y, PoolWin g)
+{
+    size_t i = (size_t)blockIdx.x * TPB + threadIdx.x;
+    size_t total = (size_t)g.N * g.Ho * g.Wo * g.CV;
+    if (i >= total) return;
+    int cv = (int)(i % g.CV);
+    size_t t = i / g.CV;
+    int q = (int)(t % g.Wo);
+    t /= g.Wo;
+    int p = (int)(t % g.Ho);
+    int n = (int)(t / g.Ho);
+    const vec_t<T, V> *xv = reinterpret_cast<const vec_t<T, V> *>(x);
+    float acc[V];
+#pragma unroll
+    for (int j = 0; j < V; ++j) acc[j] = 0.0f;
+    for (int dh = 0; dh < g.kh; ++dh)
+        for (int dw = 0; dw < g.kw; ++dw) {
+            vec_t<T, V> a = xv[(((size_t)n * g.H + p * g.kh + dh) * g.W + q * g.kw + dw) * g.CV + cv];
+#pragma unroll
+            for (int j = 0; j < V; ++j) acc[j] += to_f32(a.e[j]);
+        }
+    const float cnt = (float)(g.kh * g.kw);
+    vec_t<T, V> r;
+#pragma unroll
+    for (int j = 0; j < V; ++j) r.e[j] = from_f32<T>(acc[j] / cnt);
+    reinterpret_cast<vec_t<T, V> *>(y)[i] = r;
+}
+
+// dx = dy / (kh*kw) for every input of a window, zero outside all windows; gate indexed like dx.
+template <class T, int V>
+__global__ void k_avgpool_bwd(const T *__restrict__ dy, T *dx, const T *__restrict__ gate, int accum, PoolWin g)
+{
+    size_t i = (size_t)blockIdx.x * TPB + threadIdx.x;
+    size_t total = (size_t)g.N * g.H * g.W * g.CV;
+    if (i >= total) return;
+    int cv = (int)(i % g.CV);
+    size_t t = i / g.CV;
+    int w = (int)(t % g.W);
+    t /= g.W;
+    int h = (int)(t % g.H);
+    int n = (int)(t / g.H);
+    const int p = h / g.kh, q = w / g.kw;
+    const bool inside = p < g.Ho && q < g.Wo;
+    vec_t<T, V> gv, gt, old, r;
+    if (inside) gv = reinterpret_cast<const vec_t<T, V> *>(dy)[(((size_t)n * g.Ho + p) * g.Wo + q) * g.CV + cv];
+    if (gate) gt = reinterpret_cast<const vec_t<T, V> *>(gate)[i];
+    vec_t<T, V> *dxv = reinterpret_cast<vec_t<T, V> *>(dx);
+    if (accum) old = dxv[i];
+    const float cnt = (float)(g.kh * g.kw);
+#pragma unroll
+    for (int j = 0; j < V; ++j) {
+        float v = inside ? to_f32(gv.e[j]) / cnt : 0.0f;
+        r.e[j] = grad_out<T>(v, accum != 0, old.e[j], gate != nullptr, gt.e[j]);
+    }
+    dxv[i] = r;
+}
+
 // ------------------------------------------------------------------ column reductions
 // A [rows][C] matrix is cut into `chunks` row ranges; block (bx, chunk) owns up to TPB channel
 // groups... each block reduces its rows for CGB channel groups with RY row lanes, the lanes are
@@ -762,6 +919,79 @@ hipError_t maxpool2x2_bwd(int dt, const void *dy, const uint8_t *idx, void *dx, 
         size_t nv = outs / V;
         hipLaunchKernelGGL((k_pool_bwd<T, V>), dim3(blocks_for(nv)), dim3(TPB), 0, s, (const T *)dy, idx,
                            (T *)dx, (const T *)epi.gate, epi.accum, N, H, W, C / V);
+    });
+    return hipGetLastError();
+}
+
+static PoolWin pool_win(int N, int H, int W, int C, int V, int kh, int kw, int stride, int pad)
+{
+    PoolWin g{N, H, W, C / V, (H + 2 * pad - kh) / stride + 1, (W + 2 * pad - kw) / stride + 1, kh, kw, stride, pad};
+    return g;
+}
+
+hipError_t maxpool_fwd(int dt, const void *x, void *y, uint8_t *idx, int N, int H, int W, int C, int kh,
+                       int kw, int stride, int pad, hipStream_t s)
+{
+    if (kh < 1 || kw < 1 || kh * kw > 255 || stride < 1 || pad < 0 || pad >= kh || pad >= kw ||
+        H + 2 * pad < kh || W + 2 * pad < kw)
+        return hipErrorInvalidValue;
+    if (kh == 2 && kw == 2 && stride == 2 && pad == 0) return maxpool2x2_fwd(dt, x, y, idx, N, H, W, C, s);
+    int Vw = dt == DT_F32 ? 4 : 8;
+    bool vec = (C % Vw == 0) && aligned16(x) && aligned16(y) && ((uintptr_t)idx % 8 == 0);
+    DISPATCH_TV(dt, vec, {
+        PoolWin g = pool_win(N, H, W, C, V, kh, kw, stride, pad);
+        size_t nv = (size_t)N * g.Ho * g.Wo * g.CV;
+        if (nv == 0) return hipSuccess;
+        hipLaunchKernelGGL((k_poolw_fwd<T, V>), dim3(blocks_for(nv)), dim3(TPB), 0, s, (const T *)x, (T *)y, idx, g);
+    });
+    return hipGetLastError();
+}
+
+hipError_t maxpool_bwd(int dt, const void *dy, const uint8_t *idx, void *dx, GradEpi epi, int N, int H, int W,
+                       int C, int kh, int kw, int stride, int pad, hipStream_t s)
+{
+    if (kh < 1 || kw < 1 || kh * kw > 255 || stride < 1 || pad < 0 || pad >= kh || pad >= kw ||
+        H + 2 * pad < kh || W + 2 * pad < kw)
+        return hipErrorInvalidValue;
+    if (kh == 2 && kw == 2 && stride == 2 && pad == 0) return maxpool2x2_bwd(dt, dy, idx, dx, epi, N, H, W, C, s);
+    int Vw = dt == DT_F32 ? 4 : 8;
+    bool vec = (C % Vw == 0) && aligned16(dy) && aligned16(dx) && aligned16(epi.gate) && ((uintptr_t)idx % 8 == 0);
+    DISPATCH_TV(dt, vec, {
+        PoolWin g = pool_win(N, H, W, C, V, kh, kw, stride, pad);
+        size_t nv = (size_t)N * H * W * g.CV;
+        if (nv == 0) return hipSuccess;
+        hipLaunchKernelGGL((k_poolw_bwd<T, V>), dim3(blocks_for(nv)), dim3(TPB), 0, s, (const T *)dy, idx, (T *)dx,
+                           (const T *)epi.gate, epi.accum, g);
+    });
+    return hipGetLastError();
+}
+
+hipError_t avgpool_fwd(int dt, const void *x, void *y, int N, int H, int W, int C, int kh, int kw, hipStream_t s)
+{
+    if (kh < 1 || kw < 1 || kh > H || kw > W) return hipErrorInvalidValue;
+    int Vw = dt == DT_F32 ? 4 : 8;
+    bool vec = (C % Vw == 0) && aligned16(x) && aligned16(y);
+    DISPATCH_TV(dt, vec, {
+        PoolWin g{N, H, W, C / V, H / kh, W / kw, kh, kw, 0, 0};
+        size_t nv = (size_t)N * g.Ho * g.Wo * g.CV;
+        if (nv == 0) return hipSuccess;
+        hipLaunchKernelGGL((k_avgpool_fwd<T, V>), dim3(blocks_for(nv)), dim3(TPB), 0, s, (const T *)x, (T *)y, g);
+    });
+    return hipGetLastError();
+}
+
+hipError_t avgpool_bwd(int dt, const void *dy, void *dx, GradEpi epi, int N, int H, int W, int C, int kh, int kw,
+                       hipStream_t s)
+{
+    if (kh < 1 || kw < 1 || kh > H || kw > W) return hipErrorInvalidValue;
+    int Vw = dt == DT_F32 ? 4 : 8;
+    bool vec = (C % Vw == 0) && aligned16(dy) && aligned16(dx) && aligned16(epi.gate);
+    DISPATCH_TV(dt, vec, {
+        PoolWin g{N, H, W, C / V, H / kh, W / kw, kh, kw, 0, 0};
+        size_t nv = (size_t)N * H * W * g.CV;
+        if (nv == 0) return hipSuccess;
+        hipLaunchKernelGGL((k_avgpool_bwd<T, V>), dim3(blocks_for(nv)), dim3(TPB), 0, s, (const T *)dy, (T *)dx,
+                           (const T *)epi.gate, epi.accum, g);
     });
     return hipGetLastError();
 }

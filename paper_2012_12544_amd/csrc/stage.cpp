@@ -336,8 +336,16 @@ int layer_forward(bapipe_stage *st, int li, const FwdCtx &c)
         if (L.fused) break;                       // done in the producing conv's epilogue
         const Tensor &A = st->tensors[L.a];
         const bool tp = st->tap_begin(BAPIPE_KC_POOL);
-        HIPCHK(maxpool2x2_fwd(dt, a, o, (uint8_t *)(st->slot(c.mbid) + L.aux_off), st->mb, A.H, A.W, A.C, s));
+        HIPCHK(maxpool_fwd(dt, a, o, (uint8_t *)(st->slot(c.mbid) + L.aux_off), st->mb, A.H, A.W, A.C, L.d.kh, L.d.kw,
+                           L.d.stride, L.d.pad, s));
         st->tap_end(tp, 0.0, (double)A.bytes() + O.bytes() + O.elems);           // read x, write y + idx
+        break;
+    }
+    case BAPIPE_AVGPOOL2D: {
+        const Tensor &A = st->tensors[L.a];
+        const bool tp = st->tap_begin(BAPIPE_KC_POOL);
+        HIPCHK(avgpool_fwd(dt, a, o, st->mb, A.H, A.W, A.C, L.d.kh, L.d.kw, s));
+        st->tap_end(tp, 0.0, (double)A.bytes() + O.bytes());
         break;
     }
     case BAPIPE_BATCHNORM2D: {
@@ -456,9 +464,17 @@ int layer_backward(bapipe_stage *st, int li, BwdCtx &c)
         if (a_grad) {
             GradEpi e = epi_for(st, L.a, c, L.o);
             const bool tp = st->tap_begin(BAPIPE_KC_POOL);
-            HIPCHK(maxpool2x2_bwd(dt, grad_ptr(st, L.o, c), (const uint8_t *)(st->slot(c.mbid) + L.aux_off),
-                                  grad_ptr(st, L.a, c), e, st->mb, A.H, A.W, A.C, s));
+            HIPCHK(maxpool_bwd(dt, grad_ptr(st, L.o, c), (const uint8_t *)(st->slot(c.mbid) + L.aux_off),
+                               grad_ptr(st, L.a, c), e, st->mb, A.H, A.W, A.C, L.d.kh, L.d.kw, L.d.stride, L.d.pad, s));
             st->tap_end(tp, 0.0, (double)O.bytes() + O.elems + A.bytes() + (e.gate ? O.bytes() : 0));
+        }
+        break;
+    case BAPIPE_AVGPOOL2D:
+        if (a_grad) {
+            GradEpi e = epi_for(st, L.a, c);
+            const bool tp = st->tap_begin(BAPIPE_KC_POOL);
+            HIPCHK(avgpool_bwd(dt, grad_ptr(st, L.o, c), grad_ptr(st, L.a, c), e, st->mb, A.H, A.W, A.C, L.d.kh, L.d.kw, s));
+            st->tap_end(tp, 0.0, (double)O.bytes() + A.bytes() * (e.gate ? 2.0 : 1.0));
         }
         break;
     case BAPIPE_BATCHNORM2D: {
@@ -642,10 +658,23 @@ int bapipe_stage_create(const bapipe_layer_desc_t *layers, int n_layers, int mic
             O.C = A.C; O.H = A.H; O.W = A.W;
             break;
         case BAPIPE_MAXPOOL2D:
-            if (d.kh != 2 || d.kw != 2 || d.stride != 2 || d.pad != 0)
-                return create_fail(BAPIPE_E_UNSUPPORTED, "layer %d: only 2x2 stride-2 unpadded max-pool", i);
-            if (A.H < 2 || A.W < 2) return create_fail(BAPIPE_E_SHAPE, "layer %d: pool input smaller than window", i);
-            O.C = A.C; O.H = A.H / 2; O.W = A.W / 2;
+            if (d.kh <= 0 || d.kw <= 0 || d.stride <= 0 || d.pad < 0)
+                return create_fail(BAPIPE_E_INVALID, "layer %d: bad pool parameters", i);
+            if (d.kh * d.kw > 255) return create_fail(BAPIPE_E_UNSUPPORTED, "layer %d: pool window above 255 positions", i);
+            if (d.pad >= d.kh || d.pad >= d.kw)           // a window must never lie wholly in the padding
+                return create_fail(BAPIPE_E_UNSUPPORTED, "layer %d: pool padding must be smaller than the window", i);
+            if (A.H + 2 * d.pad < d.kh || A.W + 2 * d.pad < d.kw)
+                return create_fail(BAPIPE_E_SHAPE, "layer %d: pool input smaller than window", i);
+            O.C = A.C;
+            O.H = (A.H + 2 * d.pad - d.kh) / d.stride + 1;
+            O.W = (A.W + 2 * d.pad - d.kw) / d.stride + 1;
+            break;
+        case BAPIPE_AVGPOOL2D:
+            if (d.kh <= 0 || d.kw <= 0) return create_fail(BAPIPE_E_INVALID, "layer %d: bad pool parameters", i);
+            if (d.kh != d.kw || d.stride != d.kh || d.pad != 0)
+                return create_fail(BAPIPE_E_UNSUPPORTED, "layer %d: average pool needs a square window, stride = window, no padding", i);
+            if (A.H < d.kh || A.W < d.kw) return create_fail(BAPIPE_E_SHAPE, "layer %d: pool input smaller than window", i);
+            O.C = A.C; O.H = A.H / d.kh; O.W = A.W / d.kw;
             break;
         case BAPIPE_BATCHNORM2D:
             if (d.cin != A.C || d.cout != A.C) return create_fail(BAPIPE_E_SHAPE, "layer %d: batch-norm over %d channels, input has %d", i, d.cin, A.C);
@@ -756,6 +785,7 @@ int bapipe_stage_create(const bapipe_layer_desc_t *layers, int n_layers, int mic
         if (L.d.kind != BAPIPE_CONV2D || st->dt != DT_BF16 || L.o == last_t || O.stashed || O.consumers.size() != 1) continue;
         Layer &P = st->layers[O.consumers[0]];
         if (P.d.kind != BAPIPE_MAXPOOL2D || P.a != L.o) continue;
+        if (P.d.kh != 2 || P.d.kw != 2 || P.d.stride != 2 || P.d.pad != 0) continue;
         if (!conv3x3_halo_supported(fwd_geom(st, L)) || (O.H & 1) || (O.W & 1)) continue;
         L.fuse_pool = O.consumers[0];
         P.fused = true;

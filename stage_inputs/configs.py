@@ -11,9 +11,9 @@ A layer is a dict with the integer fields of the C descriptor:
 `src0`/`src1` name the producing layer (index in the list), -1 = stage input.
 """
 
-CONV2D, RELU, MAXPOOL2D, BATCHNORM2D, ADD, FLATTEN, LINEAR, SOFTMAX_XENT = range(8)
+CONV2D, RELU, MAXPOOL2D, BATCHNORM2D, ADD, FLATTEN, LINEAR, SOFTMAX_XENT, AVGPOOL2D = range(9)
 KIND_NAMES = ["conv2d", "relu", "maxpool2d", "batchnorm2d", "add", "flatten",
-              "linear", "softmax_xent"]
+              "linear", "softmax_xent", "avgpool2d"]
 
 FP32, BF16 = 0, 1
 SCHED_1F1B, SCHED_1F1B_SO = 0, 1
@@ -41,8 +41,12 @@ class _Builder:
                         pad=(k // 2 if pad is None else pad), has_bias=bias,
                         fuse_relu=relu, src0=src)
 
-    def pool(self, src=None):
-        return self.add(kind=MAXPOOL2D, k=2, stride=2, pad=0, src0=src)
+    def pool(self, src=None, k=2, stride=2, pad=0):
+        return self.add(kind=MAXPOOL2D, k=k, stride=stride, pad=pad, src0=src)
+
+    def avgpool(self, k, src=None):
+        """k x k mean, stride k, no padding (k = feature-map size: global average pool)."""
+        return self.add(kind=AVGPOOL2D, k=k, stride=k, pad=0, src0=src)
 
     def relu(self, src=None):
         return self.add(kind=RELU, src0=src)
@@ -163,8 +167,97 @@ def resnet50_stage(cin=256, mid3=128, mid4=256, hw=56, n3=4, n4=6, micro_batch=3
                   BASE_SEED + 5, "kaiming")
 
 
+def vgg16_conv3(cin=128, c=256, hw=56, micro_batch=32, n_micro=8, dtype=BF16):
+    """conv3_1..3_3 at hw, pool: the VGG-16 layers between stage 1 and the deep stage."""
+    b = _Builder()
+    b.conv(cin, c, 3, relu=1, src=-1)
+    b.conv(c, c, 3, relu=1)
+    b.conv(c, c, 3, relu=1)
+    b.pool()
+    return _stage("vgg16_conv3", b.layers, dtype, (cin, hw, hw), micro_batch, n_micro, 2, 4, 1,
+                  BASE_SEED + 6, "kaiming")
+
+
+def resnet50_stem(c=64, hw=224, n2=3, micro_batch=32, n_micro=8, dtype=BF16, cin=3):
+    """7x7 stride-2 conv, BN, ReLU, 3x3 stride-2 max-pool, conv2_x (n2 bottlenecks
+    c -> c -> 4c, projection shortcut on the first): the head of ResNet-50."""
+    b = _Builder()
+    b.conv(cin, c, 7, stride=2, pad=3, bias=0, src=-1)
+    b.bn(c, relu=1)
+    cur = b.pool(k=3, stride=2, pad=1)
+    ch = c
+    for i in range(n2):
+        cur = _bottleneck(b, cur, ch, c, 4 * c, 1, i == 0)
+        ch = 4 * c
+    return _stage("resnet50_stem", b.layers, dtype, (cin, hw, hw), micro_batch, n_micro, 1, 4, 0,
+                  BASE_SEED + 7, "kaiming")
+
+
+def resnet50_tail(cin=1024, mid=512, hw=14, n5=3, classes=1000, micro_batch=32, n_micro=8,
+                  dtype=BF16):
+    """conv5_x (n5 bottlenecks, stride 2 in the first), global average pool, FC, softmax
+    cross-entropy: the end of ResNet-50."""
+    b = _Builder()
+    cur, c = -1, cin
+    for i in range(n5):
+        cur = _bottleneck(b, cur, c, mid, 4 * mid, 2 if i == 0 else 1, i == 0)
+        c = 4 * mid
+    out_hw = (hw + 2 - 3) // 2 + 1
+    b.avgpool(out_hw)
+    b.flatten()
+    b.linear(c, classes, relu=0)
+    b.xent()
+    return _stage("resnet50_tail", b.layers, dtype, (cin, hw, hw), micro_batch, n_micro, 4, 4, 1,
+                  BASE_SEED + 8, "kaiming")
+
+
+def _concat(name, parts, micro_batch, n_micro, seed, init):
+    """One stage holding the layers of consecutive stages (a whole network on one accelerator:
+    what the per-layer profile is taken on before it is partitioned)."""
+    layers = []
+    for st in parts:
+        base = len(layers)
+        for L in st["layers"]:
+            L = dict(L)
+            L["src0"] = L["src0"] + base if L["src0"] >= 0 else base - 1
+            if L["kind"] == ADD:
+                L["src1"] = L["src1"] + base if L["src1"] >= 0 else base - 1
+            layers.append(L)
+    f = parts[0]
+    return _stage(name, layers, f["dtype"], (f["in_c"], f["in_h"], f["in_w"]), micro_batch, n_micro,
+                  1, 1, 0, seed, init)
+
+
+def vgg16_full(micro_batch=32, n_micro=8, dtype=BF16, hw=224, width=64, hidden=4096, classes=1000):
+    """All of VGG-16 (13 conv, 5 pool, 3 FC, loss) as one stage."""
+    w = width
+    parts = [vgg16_stage1(c1=w, c2=2 * w, hw=hw, micro_batch=micro_batch, dtype=dtype),
+             vgg16_conv3(cin=2 * w, c=4 * w, hw=hw // 4, micro_batch=micro_batch, dtype=dtype),
+             vgg16_deep(cin=4 * w, c=8 * w, hw=hw // 8, micro_batch=micro_batch, dtype=dtype),
+             vgg16_classifier(c=8 * w, hw=hw // 32, hidden=hidden, classes=classes,
+                              micro_batch=micro_batch, dtype=dtype)]
+    return _concat("vgg16_full", parts, micro_batch, n_micro, BASE_SEED + 9, "kaiming")
+
+
+def resnet50_full(micro_batch=32, n_micro=8, dtype=BF16, hw=224, width=64, classes=1000,
+                  blocks=(3, 4, 6, 3)):
+    """All of ResNet-50 (stem, conv2_x..conv5_x, average pool, FC, loss) as one stage."""
+    w = width
+    parts = [resnet50_stem(c=w, hw=hw, n2=blocks[0], micro_batch=micro_batch, dtype=dtype),
+             resnet50_stage(cin=4 * w, mid3=2 * w, mid4=4 * w, hw=hw // 4, n3=blocks[1], n4=blocks[2],
+                            micro_batch=micro_batch, dtype=dtype),
+             resnet50_tail(cin=16 * w, mid=8 * w, hw=hw // 16, n5=blocks[3], classes=classes,
+                           micro_batch=micro_batch, dtype=dtype)]
+    return _concat("resnet50_full", parts, micro_batch, n_micro, BASE_SEED + 10, "kaiming")
+
+
 FULL = {
     "tiny": tiny_stage,
+    "vgg16_conv3": vgg16_conv3,
+    "resnet50_stem": resnet50_stem,
+    "resnet50_tail": resnet50_tail,
+    "vgg16_full": vgg16_full,
+    "resnet50_full": resnet50_full,
     "vgg16_stage1": vgg16_stage1,
     "vgg16_deep": vgg16_deep,
     "vgg16_classifier": vgg16_classifier,
@@ -184,7 +277,7 @@ def infer_shapes(stage):
             ho = (s[1] + 2 * L["pad"] - L["kh"]) // L["stride"] + 1
             wo = (s[2] + 2 * L["pad"] - L["kw"]) // L["stride"] + 1
             o = (L["cout"], ho, wo)
-        elif k == MAXPOOL2D:
+        elif k in (MAXPOOL2D, AVGPOOL2D):
             ho = (s[1] + 2 * L["pad"] - L["kh"]) // L["stride"] + 1
             wo = (s[2] + 2 * L["pad"] - L["kw"]) // L["stride"] + 1
             o = (s[0], ho, wo)
@@ -232,3 +325,24 @@ def flops_per_minibatch(stage):
             passes = 2
         fl += 2 * m * passes
     return fl * stage["micro_batch"] * stage["n_micro"]
+
+
+def cut_crossings(stage):
+    """For the cut after each layer l: (number of tensors, elements per sample) produced at or
+    before l - the stage input included - and read by a layer after l.  A pipeline boundary
+    placed at a cut has to send all of them; cuts crossed by one tensor are the ones a stage
+    with a single input and a single output can be built for."""
+    shapes = infer_shapes(stage)
+    inp = (stage["in_c"], stage["in_h"], stage["in_w"])
+    last_use = {}
+    for i, L in enumerate(stage["layers"]):
+        last_use[L["src0"]] = i
+        if L["kind"] == ADD:
+            last_use[L["src1"]] = i
+    out = []
+    for l in range(len(stage["layers"])):
+        live = [t for t, u in last_use.items() if t <= l and u > l]
+        elems = sum(int(inp[0] * inp[1] * inp[2]) if t < 0 else int(shapes[t][0] * shapes[t][1] * shapes[t][2])
+                    for t in live)
+        out.append((len(live), elems))
+    return out

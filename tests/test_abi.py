@@ -72,7 +72,7 @@ def test_create_type_checks_the_layer_list():
         _create(stage, layers=bad)
     assert e.value.status == B.E_SHAPE
     bad = [dict(L) for L in stage["layers"]]
-    bad[2]["kh"] = bad[2]["kw"] = 3                    # only 2x2/2 pooling exists
+    bad[2]["pad"] = 2                                  # a window may not lie wholly in the padding
     with pytest.raises(B.BapipeError) as e:
         _create(stage, layers=bad)
     assert e.value.status == B.E_UNSUPPORTED

@@ -178,3 +178,22 @@ def test_vgg16_classifier_layerwise_full_shapes():
 @pytest.mark.timeout(900)
 def test_resnet50_stage_layerwise_full_shapes():
     _layerwise(C.resnet50_stage(n_micro=1), "cfg5 layerwise")
+
+
+# ------------------------------------------------------------------------------ the remaining stages
+@pytest.mark.timeout(900)
+def test_vgg16_conv3_full_shapes():
+    _end_to_end_report(C.vgg16_conv3(n_micro=1), gate_forward=True)
+    _layerwise(C.vgg16_conv3(n_micro=1), "vgg16 conv3 layerwise")
+
+
+@pytest.mark.timeout(900)
+def test_resnet50_stem_full_shapes():
+    _end_to_end_report(C.resnet50_stem(n_micro=1), gate_forward=False)
+    _layerwise(C.resnet50_stem(n_micro=1), "resnet50 stem layerwise")
+
+
+@pytest.mark.timeout(900)
+def test_resnet50_tail_full_shapes():
+    _end_to_end_report(C.resnet50_tail(n_micro=1), gate_forward=False)
+    _layerwise(C.resnet50_tail(n_micro=1), "resnet50 tail layerwise")

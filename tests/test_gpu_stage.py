@@ -82,6 +82,82 @@ def test_pool_only_stage_indices_bit_exact(dtype, c, hw, mb):
     g.close()
 
 
+@pytest.mark.parametrize("dtype", DT)
+@pytest.mark.parametrize("k,stride,pad", [(3, 2, 1), (3, 2, 0), (3, 1, 1), (2, 1, 0), (2, 2, 1)])
+@pytest.mark.parametrize("c,hw,mb", [(16, (12, 10), 3), (6, (9, 7), 2), (64, (112, 112), 2)])
+def test_windowed_pool_only_stage_bit_exact(dtype, k, stride, pad, c, hw, mb):
+    """Overlapping / padded windows (the ResNet stem's 3x3 stride-2 pool and relatives) on identical
+    inputs: indices, outputs and the summed routed gradients agree exactly in fp32; in bf16 the sum
+    of several routed gradients is rounded once on both sides."""
+    if hw[0] > 100 and (k, stride, pad) != (3, 2, 1):
+        pytest.skip("full stem shape only for the stem's own window")
+    st = single(lambda b: b.pool(src=-1, k=k, stride=stride, pad=pad), c, hw, dtype, micro_batch=mb, n_micro=1)
+    xs, gs = stage_io(st)
+    xs[0][:, :, 1, :] = xs[0][:, :, 0, :]
+    xs[0][:, :, :, 3] = xs[0][:, :, :, 2]
+    xs[0][0, 0, :4, :4] = 0.0
+    from oracle.stage import OracleStage
+    orc = OracleStage(st, gen.all_params(st))
+    g = GpuStage(st, gen.all_params(st))
+    y_ref, y = orc.forward(0, xs[0]), g.forward(0, xs[0])
+    assert np.array_equal(orc.pool_indices(0, 0), g.pool_indices(0, 0))
+    assert np.array_equal(y_ref, y)
+    dx_ref, dx = orc.backward(0, gs[0]), g.backward(0, gs[0])
+    if dtype == C.FP32:
+        assert np.allclose(dx_ref, dx, rtol=1e-6, atol=1e-6)       # up to four fp32 terms per input
+    else:
+        assert np.max(np.abs(dx_ref - dx)) <= 2.0 ** -7 * np.max(np.abs(dx_ref))   # one bf16 ulp of the largest
+    assert np.array_equal(dx_ref == 0, dx == 0)
+    g.close()
+
+
+@pytest.mark.parametrize("dtype", DT)
+@pytest.mark.parametrize("layout", [B.NCHW, B.NHWC])
+def test_gated_windowed_pool_and_average_pool(dtype, layout):
+    """ReLU-gated producers in front of both pools: the window maximum gates the max-pool gradient,
+    the producer's own output gates the average pool's."""
+    def build(b):
+        x = b.conv(8, 16, 3, relu=1, src=-1)
+        p = b.pool(k=3, stride=2, pad=1)
+        c2 = b.conv(16, 16, 1, relu=1)
+        b.avgpool(3)
+    st = single(build, 8, (12, 12), dtype)
+    compare_minibatch(st, layout=layout, verbose="conv-pool3x3-conv-avgpool layout %d" % layout)
+
+
+@pytest.mark.parametrize("dtype", DT)
+@pytest.mark.parametrize("c,hw,k", [(16, (7, 7), 7), (6, (9, 6), 3), (2048, (7, 7), 7)])
+def test_average_pool_only_stage(dtype, c, hw, k):
+    st = single(lambda b: b.avgpool(k, src=-1), c, hw, dtype, micro_batch=4, n_micro=1)
+    compare_minibatch(st, tol=1e-6 if dtype == C.FP32 else 2.0 ** -8, verbose="avgpool %s k%d" % (hw, k))
+
+
+@pytest.mark.parametrize("dtype", DT)
+@pytest.mark.parametrize("hw,cout,mb", [((20, 18), 16, 2), ((64, 48), 64, 3)])
+def test_stem_conv_7x7_stride_2(dtype, hw, cout, mb):
+    st = single(lambda b: b.conv(3, cout, 7, stride=2, pad=3, bias=0, relu=0, src=-1), 3, hw, dtype, micro_batch=mb,
+                need_input_grad=0)
+    compare_minibatch(st, verbose="7x7 s2 conv %s" % (hw,))
+
+
+@pytest.mark.parametrize("dtype", DT)
+def test_remaining_stages_small(dtype):
+    """Shrunken copies of the VGG-16 conv3 block, the ResNet-50 head and the ResNet-50 end."""
+    compare_minibatch(C.vgg16_conv3(cin=8, c=16, hw=16, micro_batch=2, n_micro=2, dtype=dtype), verbose="conv3 small")
+    compare_minibatch(C.resnet50_stem(c=8, hw=32, n2=2, micro_batch=3, n_micro=2, dtype=dtype), verbose="stem small")
+    compare_minibatch(C.resnet50_tail(cin=32, mid=8, hw=8, n5=2, classes=11, micro_batch=4, n_micro=2, dtype=dtype),
+                      verbose="tail small")
+
+
+def test_whole_networks_small_fp32():
+    """Every layer of VGG-16 and of a one-block-per-group ResNet in one stage (what the per-layer
+    profile is taken on), shrunken, fp32."""
+    compare_minibatch(C.vgg16_full(micro_batch=2, n_micro=2, dtype=C.FP32, hw=32, width=4, hidden=24, classes=10),
+                      verbose="vgg16 whole small")
+    compare_minibatch(C.resnet50_full(micro_batch=4, n_micro=2, dtype=C.FP32, hw=64, width=4, classes=10,
+                                      blocks=(1, 1, 1, 1)), verbose="resnet whole small")
+
+
 @pytest.mark.parametrize("cin,cout,hw,mb", [(64, 64, (32, 16), 2), (64, 128, (16, 48), 2), (128, 64, (16, 16), 3)])
 def test_conv_with_pool_in_its_epilogue(cin, cout, hw, mb):
     """16-aligned 3x3 conv (+ReLU) whose output only feeds a 2x2 max-pool: pooled values and arg-max
@@ -146,6 +222,63 @@ def test_profile_feeds_the_partition_explorer():
     assert sb[0] == 0 and sb[-1] == len(prof) and 0 < sb[1] < len(prof)
     total = sum(f) + sum(b)
     assert total / 2 * (1 - 1e-9) <= rep["bottleneck_ms"] <= total and math.isclose(rep["ideal_stage_ms"], total / 2, rel_tol=1e-9)
+
+
+@pytest.mark.parametrize("net", ["vgg16_full", "resnet50_full"])
+def test_whole_network_profile_is_partitioned_into_four_stages(net):
+    """The loop the profiler exists for (Sec. III-A / III-B): profile every layer of a whole network
+    at its real layer shapes on the device, hand the profile to the partition explorer, and check the
+    result against brute force over the measured numbers.  A cut inside a residual block is crossed
+    by two tensors; it is priced at their total size, and with a finite link the explorer's own
+    feature threshold a_th keeps boundaries out of the blocks."""
+    from oracle import plan as P
+    st = C.FULL[net](micro_batch=8, n_micro=4)
+    g = GpuStage(st, gen.all_params(st))
+    L = len(st["layers"])
+    prof = B.bapipe_profile_layers(g.h, 1, 3, L)
+    g.close()
+    f, b = [p["fwd_ms"] for p in prof], [p["bwd_ms"] for p in prof]
+    assert min(f) >= 0 and min(b) >= 0 and sum(f) > 0 and sum(b) > sum(f) * 0.5
+    cross = C.cut_crossings(st)
+    assert cross[-1] == (0, 0) and all(n >= 1 for n, _ in cross[:-1])
+    if net == "vgg16_full":
+        assert all(n == 1 for n, _ in cross[:-1])
+    else:
+        assert sum(1 for n, _ in cross[:-1] if n == 1) == 16 + 3 + 3       # after each block, stem layers, head
+    esz = 2
+    single = [e * esz * 8 for n, e in cross]
+    assert all(prof[l]["out_feature_bytes"] == single[l] for l in range(L - 1) if cross[l][0] == 1 and
+               st["layers"][l]["kind"] != C.SOFTMAX_XENT)
+    out_bytes = [float(e * esz * 8) if n == 1 else 1e15 for n, e in cross]
+    N = 4
+    wb, sbts = [p["weight_bytes"] for p in prof], [p["stash_bytes"] for p in prof]
+    total = sum(f) + sum(b)
+    link = 1e15 / (total / N) / 10.0                  # a_th = T x link = 1e14: above every real tensor, below the penalty
+    sb, rep = B.bapipe_partition([f] * N, [b] * N, out_bytes, wb, sbts, link_bytes_per_ms=link, n_micro=4,
+                                 schedule=B.PLAN_1F1B_SNO)
+    assert sb[0] == 0 and sb[-1] == L and all(sb[i] < sb[i + 1] for i in range(N))
+    assert all(cross[sb[i] - 1][0] == 1 for i in range(1, N)), "a boundary fell inside a residual block"
+    p = dict(fwd_ms=[f] * N, bwd_ms=[b] * N, out_bytes=out_bytes, weight_bytes=wb, stash_bytes=sbts,
+             link_bytes_per_ms=link, n_micro=4, schedule=P.S_1F1B_SNO)
+    legal = [l + 1 for l in range(L - 1) if cross[l][0] == 1]
+    best = min(max(sum(f[lo:hi]) + sum(b[lo:hi]) for lo, hi in zip((0,) + c, c + (L,)))
+               for c in __import__("itertools").combinations(legal, N - 1))
+    assert math.isclose(rep["bottleneck_ms"], best, rel_tol=1e-9), (rep, best)
+    assert math.isclose(rep["ideal_stage_ms"], total / N, rel_tol=1e-9)
+    print("  %s: stages begin at %s, slowest %.3f ms vs ideal %.3f ms" % (net, sb, rep["bottleneck_ms"], total / N), flush=True)
+    # every stage of the partition can be built and run as a stage of its own
+    for i in range(N):
+        sub = [dict(l) for l in st["layers"][sb[i]:sb[i + 1]]]
+        for l in sub:
+            l["src0"] = max(l["src0"] - sb[i], -1)
+            if l["kind"] == C.ADD:
+                l["src1"] = max(l["src1"] - sb[i], -1)
+        shp = (st["in_c"], st["in_h"], st["in_w"]) if sb[i] == 0 else C.infer_shapes(st)[sb[i] - 1]
+        part = C._stage("%s.part%d" % (net, i), sub, st["dtype"], shp, 8, 2, i + 1, N, 1 if i else 0, st["seed"], st["init"])
+        gp = GpuStage(part, gen.all_params(part))
+        per, depth = B.bapipe_stage_stash_bytes(gp.h)
+        assert depth == min(2, N - i)
+        gp.close()
 
 
 def test_profile_sweep_over_micro_batch_sizes():

@@ -259,6 +259,37 @@ def test_maxpool_3x3_s2_pad1_vs_torch():
     assert np.allclose(ops.maxpool_bwd(dy, idx, x.shape, 3, 2, 1), xt.grad.numpy(), atol=1e-14)
 
 
+def test_maxpool_overlapping_windows_add_their_gradients():
+    # 1x5 row, 3-wide windows at stride 2 with one pad: windows cover {-,0,1}, {1,2,3}, {3,4,-};
+    # the peak at position 1 wins the first two windows, position 4 the last
+    x = np.array([0.0, 9.0, 1.0, 2.0, 5.0]).reshape(1, 1, 1, 5)
+    y, idx = ops.maxpool_fwd(x, 3, 2, 1)
+    assert y.shape == (1, 1, 1, 3) and np.array_equal(y.ravel(), [9.0, 9.0, 5.0])
+    # window row 0 is the padding row, so the in-window index is 3 + column
+    assert np.array_equal(idx.ravel(), [3 + 2, 3 + 0, 3 + 1])
+    dx = ops.maxpool_bwd(np.array([1.0, 10.0, 100.0]).reshape(1, 1, 1, 3), idx, x.shape, 3, 2, 1)
+    assert np.array_equal(dx.ravel(), [0.0, 11.0, 0.0, 0.0, 100.0])
+
+
+def test_avgpool_hand_global_and_torch():
+    x = np.arange(16.0).reshape(1, 1, 4, 4)
+    assert np.array_equal(ops.avgpool_fwd(x, 2)[0, 0], [[2.5, 4.5], [10.5, 12.5]])
+    assert ops.avgpool_fwd(x, 4).ravel()[0] == 7.5                      # global: the plain mean
+    x = RNG.standard_normal((3, 5, 7, 7))
+    y = ops.avgpool_fwd(x, 7)
+    assert np.allclose(y[:, :, 0, 0], x.mean(axis=(2, 3)), atol=1e-15)
+    x = RNG.standard_normal((2, 3, 9, 6))                               # 9 rows: the last is in no window
+    y = ops.avgpool_fwd(x, 2)
+    assert np.allclose(y, F.avg_pool2d(_t(x), 2).numpy(), atol=1e-15)
+    dy = RNG.standard_normal(y.shape)
+    dx = ops.avgpool_bwd(dy, x.shape, 2)
+    assert abs(np.sum(y * dy) - np.sum(x * dx)) < 1e-12                 # adjoint of a linear map
+    assert not dx[:, :, 8].any()
+    xt = _t(x).requires_grad_()
+    F.avg_pool2d(xt, 2).backward(_t(dy))
+    assert np.allclose(dx, xt.grad.numpy(), atol=1e-15)
+
+
 # ------------------------------------------------------------------ batch-norm
 def test_bn_forward_invariants():
     x = 3.0 + 2.0 * RNG.standard_normal((4, 5, 6, 7))

@@ -19,6 +19,9 @@ def small_stages():
         "vgg16_deep": C.vgg16_deep(cin=4, c=6, hw=8, micro_batch=2, n_micro=2),
         "vgg16_classifier": C.vgg16_classifier(c=4, hw=3, hidden=10, classes=7, micro_batch=3, n_micro=2),
         "resnet50_stage": C.resnet50_stage(cin=8, mid3=4, mid4=6, hw=8, n3=2, n4=2, micro_batch=3, n_micro=2),
+        "vgg16_conv3": C.vgg16_conv3(cin=4, c=6, hw=8, micro_batch=2, n_micro=2),
+        "resnet50_stem": C.resnet50_stem(c=4, hw=16, n2=2, micro_batch=3, n_micro=2),
+        "resnet50_tail": C.resnet50_tail(cin=8, mid=4, hw=4, n5=2, classes=5, micro_batch=3, n_micro=2),
     }
 
 
@@ -210,9 +213,12 @@ def test_bf16_storage_outputs_are_representable_and_close_to_exact():
 
 
 def test_workload_shapes_and_flop_table():
-    """MAC counts per sample fixed by the layer shapes of the five workloads."""
+    """MAC counts per sample fixed by the layer shapes of the workloads; the whole networks add up
+    to the well-known 15.47 GMAC (VGG-16) and 4.09 GMAC (ResNet-50, stride on the 3x3)."""
     want = {"tiny": 2.80e6, "vgg16_stage1": 4.711e9, "vgg16_deep": 6.011e9,
-            "vgg16_classifier": 123.6e6, "resnet50_stage": 2.492e9}
+            "vgg16_classifier": 123.6e6, "resnet50_stage": 2.492e9, "vgg16_conv3": 4.624e9,
+            "resnet50_stem": 785.9e6, "resnet50_tail": 811.3e6, "vgg16_full": 15.47e9,
+            "resnet50_full": 4.089e9}
     for name, f in C.FULL.items():
         st = f()
         macs, _ = C.conv_fc_macs_per_sample(st)
@@ -222,6 +228,14 @@ def test_workload_shapes_and_flop_table():
     st5 = C.resnet50_stage()
     assert C.infer_shapes(st5)[-1] == (1024, 14, 14)
     assert sum(1 for L in st5["layers"] if L["kind"] == C.BATCHNORM2D) == 32
+    v, r = C.vgg16_full(), C.resnet50_full()
+    assert sum(1 for L in v["layers"] if L["kind"] == C.CONV2D) == 13
+    assert sum(1 for L in v["layers"] if L["kind"] == C.LINEAR) == 3
+    assert C.infer_shapes(v)[-1] == (1000, 1, 1) and C.infer_shapes(r)[-1] == (1000, 1, 1)
+    assert sum(1 for L in r["layers"] if L["kind"] == C.CONV2D) == 53       # 1 + 3*16 + 4 projections
+    assert sum(1 for L in r["layers"] if L["kind"] == C.BATCHNORM2D) == 53
+    assert C.infer_shapes(C.resnet50_stem())[-1] == (256, 56, 56)
+    assert C.infer_shapes(C.resnet50_tail())[-3] == (2048, 1, 1)
 
 
 def test_input_generators_are_deterministic_and_bf16_representable():
