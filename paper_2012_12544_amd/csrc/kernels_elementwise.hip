@@ -626,6 +626,201 @@ __global__ void k_bn_bwd_apply(const T *__restrict__ x, const T *__restrict__ dy
     }
 }
 
+// ------------------------------------------------------------------ batch-norm in one launch
+// For tensors of up to 2048 rows one block owns ONE group of V = 4 channels over ALL rows: every thread keeps its R rows in registers, the block
+// reduces the statistics (wave butterflies, then the 16 wave results added in double in wave
+// order: fixed order, bit-reproducible), and the same registers are normalised and stored.  The
+// activations are read once, nothing goes through a workspace and there is no second launch.
+// Neighbouring blocks read neighbouring pieces of the same cache lines: poor use of the load
+// path, acceptable only because tensors this small are bound by launch latency.
+constexpr int OP_NT = 1024, OP_WAVES = OP_NT / 64;
+
+// Makes the compiler forget what it knows about a register-resident vector (so that values derived
+// from it before a reduction are recomputed after it instead of being kept alive in registers).
+template <class T, int V>
+__device__ __forceinline__ void forget(vec_t<T, V> &a)
+{
+    static_assert(sizeof(a) % 4 == 0, "whole dwords");
+    uint32_t *w = reinterpret_cast<uint32_t *>(&a);
+#pragma unroll
+    for (int i = 0; i < (int)sizeof(a) / 4; ++i) asm volatile("" : "+v"(w[i]));
+}
+
+template <int NQV>
+__device__ __forceinline__ void block_sums(float (&v)[NQV], float (*wpart)[NQV], double *tot)
+{
+#pragma unroll
+    for (int q = 0; q < NQV; ++q) v[q] = wave_sum(v[q]);
+    if ((threadIdx.x & 63) == 0) {
+#pragma unroll
+        for (int q = 0; q < NQV; ++q) wpart[threadIdx.x >> 6][q] = v[q];
+    }
+    __syncthreads();
+    if (threadIdx.x < NQV) {
+        double t = 0.0;
+        for (int w = 0; w < OP_WAVES; ++w) t += (double)wpart[w][threadIdx.x];
+        tot[threadIdx.x] = t;
+    }
+    __syncthreads();
+}
+
+template <class T, int V, int R>
+__global__ __launch_bounds__(OP_NT) void k_bn_fwd_onepass(const T *__restrict__ x, const float *__restrict__ gamma,
+                                                          const float *__restrict__ beta, float eps,
+                                                          T *__restrict__ y, float *__restrict__ stats, int relu,
+                                                          int rows, int C)
+{
+    __shared__ float wpart[OP_WAVES][2 * V];
+    __shared__ double tot[2 * V];
+    __shared__ float mi[2 * V];
+    const int CV = C / V, cg = blockIdx.x;
+    const vec_t<T, V> *xv = reinterpret_cast<const vec_t<T, V> *>(x);
+    vec_t<T, V> *yv = reinterpret_cast<vec_t<T, V> *>(y);
+    vec_t<T, V> a[R];
+#pragma unroll
+    for (int u = 0; u < R; ++u) {
+        const int r = threadIdx.x + u * OP_NT;
+        a[u] = xv[(size_t)(r < rows ? r : rows - 1) * CV + cg];
+    }
+    float acc[2 * V];
+#pragma unroll
+    for (int j = 0; j < 2 * V; ++j) acc[j] = 0.0f;
+#pragma unroll
+    for (int u = 0; u < R; ++u) {
+        const bool in = threadIdx.x + u * OP_NT < rows;
+#pragma unroll
+        for (int j = 0; j < V; ++j) {
+            const float t = in ? to_f32(a[u].e[j]) : 0.0f;
+            acc[j] += t;
+            acc[V + j] += t * t;
+        }
+    }
+    block_sums<2 * V>(acc, wpart, tot);
+    if (threadIdx.x < V) {
+        const double m = (double)rows, mu = tot[threadIdx.x] / m;
+        double var = tot[V + threadIdx.x] / m - mu * mu;
+        if (var < 0.0) var = 0.0;
+        const float fm = (float)mu, fi = (float)(1.0 / sqrt(var + (double)eps));
+        mi[threadIdx.x] = fm;
+        mi[V + threadIdx.x] = fi;
+        stats[cg * V + threadIdx.x] = fm;
+        stats[C + cg * V + threadIdx.x] = fi;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int u = 0; u < R; ++u) forget(a[u]);
+    float mu[V], inv[V], ga[V], be[V];
+#pragma unroll
+    for (int j = 0; j < V; ++j) {
+        mu[j] = mi[j];
+        inv[j] = mi[V + j];
+        ga[j] = gamma[cg * V + j];
+        be[j] = beta[cg * V + j];
+    }
+#pragma unroll
+    for (int u = 0; u < R; ++u) {
+        const int r = threadIdx.x + u * OP_NT;
+        if (r >= rows) break;
+        vec_t<T, V> o;
+#pragma unroll
+        for (int j = 0; j < V; ++j) {
+            float xh = (to_f32(a[u].e[j]) - mu[j]) * inv[j];
+            float v = ga[j] * xh + be[j];
+            if (relu) v = fmaxf(v, 0.0f);
+            o.e[j] = from_f32<T>(v);
+        }
+        yv[(size_t)r * CV + cg] = o;
+    }
+}
+
+template <class T, int V, int R>
+__global__ __launch_bounds__(OP_NT) void k_bn_bwd_onepass(const T *__restrict__ x, const T *__restrict__ dy,
+                                                          const float *__restrict__ gamma,
+                                                          const float *__restrict__ stats, T *dx,
+                                                          const T *__restrict__ gate, int accum, float *dgamma,
+                                                          float *dbeta, float inv_m, int rows, int C)
+{
+    __shared__ float wpart[OP_WAVES][2 * V];
+    __shared__ double tot[2 * V];
+    const int CV = C / V, cg = blockIdx.x;
+    const vec_t<T, V> *xv = reinterpret_cast<const vec_t<T, V> *>(x);
+    const vec_t<T, V> *gv = reinterpret_cast<const vec_t<T, V> *>(dy);
+    vec_t<T, V> a[R], g[R];
+#pragma unroll
+    for (int u = 0; u < R; ++u) {
+        const int r = threadIdx.x + u * OP_NT;
+        const size_t i = (size_t)(r < rows ? r : rows - 1) * CV + cg;
+        a[u] = xv[i];
+        g[u] = gv[i];
+    }
+    float mu[V], inv[V];
+#pragma unroll
+    for (int j = 0; j < V; ++j) {
+        mu[j] = stats[cg * V + j];
+        inv[j] = stats[C + cg * V + j];
+    }
+    float acc[2 * V];
+#pragma unroll
+    for (int j = 0; j < 2 * V; ++j) acc[j] = 0.0f;
+#pragma unroll
+    for (int u = 0; u < R; ++u) {
+        const bool in = threadIdx.x + u * OP_NT < rows;
+#pragma unroll
+        for (int j = 0; j < V; ++j) {
+            const float gg = in ? to_f32(g[u].e[j]) : 0.0f;
+            const float xh = (to_f32(a[u].e[j]) - mu[j]) * inv[j];
+            acc[j] += gg;
+            acc[V + j] += gg * xh;
+        }
+    }
+    block_sums<2 * V>(acc, wpart, tot);
+    if (threadIdx.x < V) {
+        dbeta[cg * V + threadIdx.x] += (float)tot[threadIdx.x];
+        dgamma[cg * V + threadIdx.x] += (float)tot[V + threadIdx.x];
+    }
+    if (!dx) return;
+#pragma unroll
+    for (int u = 0; u < R; ++u) {
+        forget(a[u]);
+        forget(g[u]);
+    }
+    float gi[V], m1[V], m2[V];
+#pragma unroll
+    for (int j = 0; j < V; ++j) {
+        gi[j] = gamma[cg * V + j] * inv[j];
+        m1[j] = (float)tot[j] * inv_m;
+        m2[j] = (float)tot[V + j] * inv_m;
+    }
+    const vec_t<T, V> *tv = reinterpret_cast<const vec_t<T, V> *>(gate);
+    vec_t<T, V> *dv = reinterpret_cast<vec_t<T, V> *>(dx);
+    constexpr int G = R < 2 ? R : 2;
+#pragma unroll
+    for (int h = 0; h < R / G; ++h) {
+        vec_t<T, V> old[G], gt[G];
+#pragma unroll
+        for (int u = 0; u < G; ++u) {
+            const int r = threadIdx.x + (h * G + u) * OP_NT;
+            const size_t i = (size_t)(r < rows ? r : rows - 1) * CV + cg;
+            if (accum) old[u] = dv[i];
+            if (gate) gt[u] = tv[i];
+        }
+#pragma unroll
+        for (int u = 0; u < G; ++u) {
+            const int r = threadIdx.x + (h * G + u) * OP_NT;
+            if (r < rows) {
+                vec_t<T, V> o;
+#pragma unroll
+                for (int j = 0; j < V; ++j) {
+                    float xh = (to_f32(a[h * G + u].e[j]) - mu[j]) * inv[j];
+                    float v = gi[j] * (to_f32(g[h * G + u].e[j]) - m1[j] - xh * m2[j]);
+                    o.e[j] = grad_out<T>(v, accum != 0, old[u].e[j], gate != nullptr, gt[u].e[j]);
+                }
+                dv[(size_t)r * CV + cg] = o;
+            }
+        }
+    }
+}
+
 // ------------------------------------------------------------------ softmax cross-entropy
 template <class T>
 __global__ void k_softmax_fwd(const T *__restrict__ z, float *__restrict__ p, int K)
@@ -1023,12 +1218,33 @@ hipError_t colsum_accumulate(int dt, const void *a, int rows, int C, float *out,
     return hipGetLastError();
 }
 
+// The one-launch kernels pay for their strided 8-byte loads (measured: 3x slower than the three
+// coalesced launches at 6272 rows), so they are used only where launch latency is all there is:
+// 16-byte aligned tensors of at most OP_R rows per thread and at least 32 channel groups.
+constexpr int OP_R = 2;
+static bool bn_onepass(int Vsel, int rows, int C) { return Vsel > 1 && rows <= OP_R * OP_NT && C / 4 >= 32; }
+
+// channels per block of the one-launch kernels: 8 bytes of bf16 / 16 bytes of float per row
+constexpr int OP_V = 4;
+#define BN_FWD_OP(T_, R_)                                                                                        \
+    hipLaunchKernelGGL((k_bn_fwd_onepass<T_, OP_V, R_>), dim3(C / OP_V), dim3(OP_NT), 0, s, (const T_ *)x, gamma, \
+                       beta, eps, (T_ *)y, stats, relu, rows, C)
+#define BN_BWD_OP(T_, R_)                                                                                        \
+    hipLaunchKernelGGL((k_bn_bwd_onepass<T_, OP_V, R_>), dim3(C / OP_V), dim3(OP_NT), 0, s, (const T_ *)x,        \
+                       (const T_ *)dy, gamma, stats, (T_ *)dx, (const T_ *)epi.gate, epi.accum, dgamma, dbeta,    \
+                       1.0f / (float)rows, rows, C)
+
 hipError_t bn_fwd(int dt, const void *x, const float *gamma, const float *beta, float eps, void *y,
                   float *stats, int relu, int rows, int C, void *workspace, hipStream_t s)
 {
     if (rows <= 0 || C <= 0) return hipSuccess;
     int Vsel = col_vec(dt, C, x, y);
     float *part = (float *)workspace;
+    if (bn_onepass(Vsel, rows, C)) {
+        if (dt == DT_F32) BN_FWD_OP(float, OP_R);
+        else BN_FWD_OP(bf16_t, OP_R);
+        return hipGetLastError();
+    }
     DISPATCH_TV(dt, Vsel > 1, {
         ColPlan p = col_plan(rows, C, V);
         hipLaunchKernelGGL((k_bn_stat_partial<T, V>), dim3(p.gx, p.chunks), dim3(TPB), 0, s, (const T *)x,
@@ -1050,6 +1266,11 @@ hipError_t bn_bwd(int dt, const void *x, const void *dy, const float *gamma, con
     int Vsel = col_vec(dt, C, x, dy, dx);
     if (!aligned16(epi.gate)) Vsel = 1;
     float *part = (float *)workspace;
+    if (bn_onepass(Vsel, rows, C)) {
+        if (dt == DT_F32) BN_BWD_OP(float, OP_R);
+        else BN_BWD_OP(bf16_t, OP_R);
+        return hipGetLastError();
+    }
     DISPATCH_TV(dt, Vsel > 1, {
         ColPlan p = col_plan(rows, C, V);
         float *sums = part + (size_t)2 * p.chunks * C;
