@@ -43,7 +43,7 @@ template <int BK> __device__ __forceinline__ int swz(int row)
 // STAGES tiles form a ring; tile kt+STAGES-1 is requested right after the barrier that retires
 // tile kt-1, so STAGES-1 K-tiles of latency are covered while the MFMAs run.
 template <int BP, int BC, int WP, int WC, int BK, int STAGES, bool S1, bool TAPS_INNER>
-__global__ __launch_bounds__(WP *WC * 64, 2) void k_gather_mfma(
+__global__ __launch_bounds__(WP *WC * 64, WP *WC >= 8 ? 1 : 2) void k_gather_mfma(
     const bf16_t *__restrict__ in, const bf16_t *__restrict__ wt, const float *__restrict__ bias,
     bf16_t *out, const bf16_t *__restrict__ gate, int accum, int relu, int is_grad, GatherConv g,
     int tiles_c, unsigned in_bytes, unsigned wt_bytes, float *__restrict__ part, int kt_per_split)
@@ -423,6 +423,9 @@ GatherPlan gather_plan(const GatherConv &g)
     // the bottleneck blocks): halve the pixel tile rather than split K, whose fp32 partials cost more
     // than the smaller tile loses (measured on 512-channel 14x14 layers: 73 us against 100 us)
     if (p.bp == 256 && p.bc == 128 && tiles_of(256) < 400) p.bp = 128;
+    // plenty of 256-pixel tiles and whole 256-channel tiles: one 8-wave block per CU owns 256 x 256, which
+    // halves the L2 -> LDS traffic of two independent 256 x 128 blocks (3 % on the 512-channel 28x28 layers)
+    if (p.bp == 256 && p.bc == 128 && g.Co % 256 == 0) p.bc = 256;
     const long long tiles = tiles_of(p.bp);
     const int BK = 32;
     const int KT = g.Ci % BK == 0 ? (g.Ci / BK) * g.R * g.S : (g.R * g.S * g.Ci + BK - 1) / BK;
@@ -444,7 +447,7 @@ hipError_t launch_gather(const void *in, const void *wt, const float *bias, void
     constexpr size_t main_bytes = (size_t)STAGES * (BP + BC) * BK * 2;
     constexpr size_t epi_bytes = (size_t)BP * (BC + 4) * 2;
     constexpr size_t smem = (main_bytes > epi_bytes ? main_bytes : epi_bytes) + BC * sizeof(float);
-    static_assert(smem <= 80 * 1024, "two blocks must fit the 160 KB LDS of a CU");
+    static_assert(smem <= (NT >= 512 ? 160 : 80) * 1024, "two blocks of 4 waves (one of 8) must fit the 160 KB LDS of a CU");
     const long long npix = (long long)g.N * g.Ho * g.Wo;
     const int tiles_p = (int)((npix + BP - 1) / BP), tiles_c = (g.Co + BC - 1) / BC;
     const int is_grad = (epi.gate != nullptr || epi.accum) ? 1 : 0;
@@ -833,6 +836,7 @@ hipError_t conv_gather_mfma(const void *in, const void *wt, const float *bias, v
     const GatherPlan p = gather_plan(g);
     if (p.bp == 64) return launch_gather<64, 128, 1, 4, 32, 3>(in, wt, bias, out, relu, epi, g, p, workspace, s);
     if (p.bc == 64) return launch_gather<256, 64, 4, 1, 32, 3>(in, wt, bias, out, relu, epi, g, p, workspace, s);
+    if (p.bc == 256) return launch_gather<256, 256, 2, 4, 32, 3>(in, wt, bias, out, relu, epi, g, p, workspace, s);
     if (p.bp == 128) return launch_gather<128, 128, 2, 2, 32, 3>(in, wt, bias, out, relu, epi, g, p, workspace, s);
     return launch_gather<256, 128, 2, 2, 32, 3>(in, wt, bias, out, relu, epi, g, p, workspace, s);
 }
