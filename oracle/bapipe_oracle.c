@@ -13,6 +13,8 @@
  *   candidates; overlapping windows that pick the same input add their gradients) ;
  *   average pool is the mean of a k x k window, stride k, its adjoint spreads dy / k^2 ;
  *   batch-norm uses biased per-channel statistics of the given (micro-)batch ;
+ *   the LSTM layer (the sequence-to-sequence workload's layer, Sec. IV-A) is the standard cell with
+ *   gates in the order input, forget, cell candidate, output, zero initial state ;
  *   the loss is softmax cross-entropy scaled by a caller-given factor ;
  *   the update is plain SGD (the paper's 2*w weights memory leaves no optimiser state).
  * All tensors are double, activations NCHW, conv weights OIHW, linear weights [out][in].
@@ -21,6 +23,7 @@
  */
 #include <math.h>
 #include <stdint.h>
+#include <stdlib.h>
 #include <string.h>
 #include <omp.h>
 
@@ -254,6 +257,116 @@ void orc_avgpool_bwd(const double *dy, double *dx, int N, int C, int H, int W, i
                     dx[IDX4(n, c, h, w, C, H, W)] =
                         (p < Ho && q < Wo) ? dy[IDX4(n, c, p, q, C, Ho, Wo)] / (double)(kh * kw) : 0.0;
                 }
+}
+
+/* LSTM layer over sequences of T steps.  x is [N][In][T] (the sequence axis is the H axis of an
+ * NCHW tensor of width 1), y is [N][Hd][T].  w is [4*Hd][In+Hd]: row k of gate block q (q = 0..3
+ * for input, forget, candidate, output; k = q*Hd + j) holds the In input weights, then the Hd
+ * recurrent weights; b is [4*Hd] or NULL.  With h_{-1} = c_{-1} = 0:
+ *   P_t   = W_x x_t + b                              (input projection, all steps)
+ *   a_t   = P_t + W_h h_{t-1}
+ *   i,f,o = sigmoid(a_t[0], a_t[1], a_t[3]) ; g = tanh(a_t[2])
+ *   c_t   = f*c_{t-1} + i*g ; h_t = o*tanh(c_t) ; y[:, :, t] = h_t
+ * gates [N][T][4*Hd] (i, f, g, o after their non-linearities) and cells [N][T][Hd] are returned
+ * for the backward pass.  round16 != 0 rounds P_t and h_t to bf16 where an implementation with
+ * 16-bit storage keeps them (P is a stored GEMM output, h_t is the layer output). */
+static double sigm(double v) { return 1.0 / (1.0 + exp(-v)); }
+
+void orc_lstm_fwd(const double *x, const double *w, const double *b, double *y, double *gates,
+                  double *cells, int N, int In, int Hd, int T, int round16)
+{
+    const int G = 4 * Hd, ld = In + Hd;
+#pragma omp parallel for schedule(static)
+    for (int n = 0; n < N; ++n) {
+        double *a = (double *)malloc(sizeof(double) * (size_t)(G + 2 * Hd));
+        double *hp = a + G, *cp = hp + Hd;
+        for (int j = 0; j < Hd; ++j) hp[j] = cp[j] = 0.0;
+        for (int t = 0; t < T; ++t) {
+            for (int k = 0; k < G; ++k) {
+                double p = b ? b[k] : 0.0;
+                for (int c = 0; c < In; ++c) p += w[(size_t)k * ld + c] * x[((size_t)n * In + c) * T + t];
+                if (round16) p = round_bf16_one(p);
+                double r = 0.0;
+                for (int j = 0; j < Hd; ++j) r += w[(size_t)k * ld + In + j] * hp[j];
+                a[k] = p + r;
+            }
+            double *gt = gates + ((size_t)n * T + t) * G, *ct = cells + ((size_t)n * T + t) * Hd;
+            for (int j = 0; j < Hd; ++j) {
+                const double ig = sigm(a[j]), fg = sigm(a[Hd + j]), gg = tanh(a[2 * Hd + j]), og = sigm(a[3 * Hd + j]);
+                gt[j] = ig; gt[Hd + j] = fg; gt[2 * Hd + j] = gg; gt[3 * Hd + j] = og;
+                ct[j] = fg * cp[j] + ig * gg;
+            }
+            for (int j = 0; j < Hd; ++j) {
+                double h = gt[3 * Hd + j] * tanh(ct[j]);
+                if (round16) h = round_bf16_one(h);
+                cp[j] = ct[j];
+                hp[j] = h;
+                y[((size_t)n * Hd + j) * T + t] = h;
+            }
+        }
+        free(a);
+    }
+}
+
+/* Back-propagation through time of the layer above.  With dh_t = dy_t + W_h^T D_{t+1} and
+ * dc_t = dh_t*o*(1-tanh(c_t)^2) + dc_{t+1}*f_{t+1}, the gradient w.r.t. the pre-activations is
+ *   D_t = ( dc_t*g*i(1-i), dc_t*c_{t-1}*f(1-f), dc_t*i*(1-g^2), dh_t*tanh(c_t)*o(1-o) )
+ * and dx_t = W_x^T D_t, dW_x += D_t x_t^T, dW_h += D_t h_{t-1}^T, db += D_t.
+ * round16 != 0 rounds D_t to bf16 (it is stored as the operand of those products).
+ * dx may be NULL; dw [4*Hd][In+Hd] and db (may be NULL) are accumulated into.  y is the forward
+ * output (h_t), D is scratch of N*T*4*Hd doubles supplied by the caller. */
+void orc_lstm_bwd(const double *x, const double *y, const double *w, const double *gates,
+                  const double *cells, const double *dy, double *dx, double *dw, double *db, double *D,
+                  int N, int In, int Hd, int T, int round16)
+{
+    const int G = 4 * Hd, ld = In + Hd;
+#pragma omp parallel for schedule(static)
+    for (int n = 0; n < N; ++n) {
+        double *r = (double *)malloc(sizeof(double) * (size_t)(2 * Hd));
+        double *dcn = r + Hd;                          /* dc_{t+1} * f_{t+1} */
+        for (int j = 0; j < Hd; ++j) r[j] = dcn[j] = 0.0;
+        for (int t = T - 1; t >= 0; --t) {
+            const double *gt = gates + ((size_t)n * T + t) * G, *ct = cells + ((size_t)n * T + t) * Hd;
+            double *Dt = D + ((size_t)n * T + t) * G;
+            for (int j = 0; j < Hd; ++j) {
+                const double ig = gt[j], fg = gt[Hd + j], gg = gt[2 * Hd + j], og = gt[3 * Hd + j];
+                const double th = tanh(ct[j]);
+                const double cprev = t > 0 ? ct[j - Hd] : 0.0;
+                const double dh = dy[((size_t)n * Hd + j) * T + t] + r[j];
+                const double dc = dh * og * (1.0 - th * th) + dcn[j];
+                Dt[j] = dc * gg * ig * (1.0 - ig);
+                Dt[Hd + j] = dc * cprev * fg * (1.0 - fg);
+                Dt[2 * Hd + j] = dc * ig * (1.0 - gg * gg);
+                Dt[3 * Hd + j] = dh * th * og * (1.0 - og);
+                dcn[j] = dc * fg;
+            }
+            if (round16)
+                for (int k = 0; k < G; ++k) Dt[k] = round_bf16_one(Dt[k]);
+            for (int j = 0; j < Hd; ++j) {
+                double s = 0.0;
+                for (int k = 0; k < G; ++k) s += Dt[k] * w[(size_t)k * ld + In + j];
+                r[j] = s;
+            }
+            if (dx)
+                for (int c = 0; c < In; ++c) {
+                    double s = 0.0;
+                    for (int k = 0; k < G; ++k) s += Dt[k] * w[(size_t)k * ld + c];
+                    dx[((size_t)n * In + c) * T + t] = s;
+                }
+        }
+        free(r);
+    }
+#pragma omp parallel for schedule(static)
+    for (int k = 0; k < G; ++k) {
+        for (int n = 0; n < N; ++n)
+            for (int t = 0; t < T; ++t) {
+                const double d = D[((size_t)n * T + t) * G + k];
+                for (int c = 0; c < In; ++c) dw[(size_t)k * ld + c] += d * x[((size_t)n * In + c) * T + t];
+                if (t > 0)
+                    for (int j = 0; j < Hd; ++j) dw[(size_t)k * ld + In + j] += d * y[((size_t)n * Hd + j) * T + t - 1];
+                if (db) db[k] += d;
+            }
+    }
 }
 
 /* Training-mode batch-norm over (N,H,W) per channel:

@@ -152,6 +152,34 @@ def bn_bwd(x, dy, gamma, mean, invstd, dgamma, dbeta):
     return dx
 
 
+def lstm_fwd(x, w, b, round16=False):
+    """x [N][In][T][1], w [4*Hd][In+Hd], b [4*Hd] or None -> (y [N][Hd][T][1], (gates, cells))."""
+    x, w = _f64(x), _f64(w)
+    b = None if b is None else _f64(b)
+    N, In, T, one = x.shape
+    assert one == 1 and w.shape[0] % 4 == 0
+    Hd = w.shape[0] // 4
+    assert w.shape[1] == In + Hd
+    y = np.empty((N, Hd, T, 1))
+    gates = np.empty((N, T, 4 * Hd))
+    cells = np.empty((N, T, Hd))
+    lib().orc_lstm_fwd(_p(x), _p(w), _p(b), _p(y), _p(gates), _p(cells), N, In, Hd, T, int(bool(round16)))
+    return y, (gates, cells)
+
+
+def lstm_bwd(x, y, w, saved, dy, dw, db, want_dx=True, round16=False):
+    """Returns dx (or None); accumulates into dw, db."""
+    x, y, w, dy = _f64(x), _f64(y), _f64(w), _f64(dy)
+    gates, cells = saved
+    N, In, T, _ = x.shape
+    Hd = w.shape[0] // 4
+    dx = np.empty_like(x) if want_dx else None
+    D = np.empty((N, T, 4 * Hd))
+    lib().orc_lstm_bwd(_p(x), _p(y), _p(w), _p(gates), _p(cells), _p(dy), _p(dx), _p(dw), _p(db), _p(D),
+                       N, In, Hd, T, int(bool(round16)))
+    return dx
+
+
 def linear_fwd(x, w, b):
     x, w = _f64(x), _f64(w)
     b = None if b is None else _f64(b)

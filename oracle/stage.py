@@ -11,7 +11,9 @@ storage="bf16" applies nearest-even bf16 rounding exactly where a tensor would b
 16 bits: each layer's output in forward (conv/linear/BN/add after bias and ReLU, average pool), each
 input-gradient contribution in backward and their sum where a tensor feeds two layers, and
 the working copy of conv/linear weight matrices.  Bias, gamma, beta, weight gradients,
-BN statistics, softmax and loss are never rounded.  storage="exact" rounds nothing.
+BN statistics, softmax and loss are never rounded.  Inside an LSTM layer the input projection
+of all steps and the pre-activation gradients are stored tensors too (rounded); the cell state
+and the recurrent sums are not.  storage="exact" rounds nothing.
 """
 import numpy as np
 
@@ -32,6 +34,7 @@ class OracleStage:
         if storage is None:
             storage = "bf16" if stage["dtype"] == C.BF16 else "exact"
         assert storage in ("bf16", "exact")
+        self.storage = storage
         self.q = ops.round_bf16 if storage == "bf16" else (lambda a: a)
         self.M = stage["n_micro"]
         i, N = stage["stage_index"], stage["n_stages"]
@@ -107,6 +110,8 @@ class OracleStage:
                 if L["fuse_relu"]:
                     y = ops.relu_fwd(y)
                 y = q(y).reshape(a.shape[0], -1, 1, 1)
+            elif k == C.LSTM:
+                y, extra = ops.lstm_fwd(a, q(self.w[i]), self.b[i], round16=self.storage == "bf16")
             elif k == C.SOFTMAX_XENT:
                 y = ops.softmax_fwd(a.reshape(a.shape[0], -1)).reshape(a.shape)
             else:
@@ -179,6 +184,11 @@ class OracleStage:
                 give(L["src1"], g)
             elif k == C.FLATTEN:
                 give(L["src0"], g.reshape(a.shape))
+            elif k == C.LSTM:
+                dx = ops.lstm_bwd(a, outs[i], q(self.w[i]), aux[i], g, self.dw[i], self.db[i], want_dx=wants,
+                                  round16=self.storage == "bf16")
+                if wants:
+                    give(L["src0"], dx)
             elif k == C.LINEAR:
                 a2 = a.reshape(a.shape[0], -1)
                 g2 = g.reshape(g.shape[0], -1)

@@ -11,9 +11,9 @@ A layer is a dict with the integer fields of the C descriptor:
 `src0`/`src1` name the producing layer (index in the list), -1 = stage input.
 """
 
-CONV2D, RELU, MAXPOOL2D, BATCHNORM2D, ADD, FLATTEN, LINEAR, SOFTMAX_XENT, AVGPOOL2D = range(9)
+CONV2D, RELU, MAXPOOL2D, BATCHNORM2D, ADD, FLATTEN, LINEAR, SOFTMAX_XENT, AVGPOOL2D, LSTM = range(10)
 KIND_NAMES = ["conv2d", "relu", "maxpool2d", "batchnorm2d", "add", "flatten",
-              "linear", "softmax_xent", "avgpool2d"]
+              "linear", "softmax_xent", "avgpool2d", "lstm"]
 
 FP32, BF16 = 0, 1
 SCHED_1F1B, SCHED_1F1B_SO = 0, 1
@@ -63,6 +63,10 @@ class _Builder:
 
     def linear(self, cin, cout, relu=0, src=None):
         return self.add(kind=LINEAR, cin=cin, cout=cout, has_bias=1, fuse_relu=relu, src0=src)
+
+    def lstm(self, cin, hidden, src=None):
+        """LSTM over the H axis of a (cin, T, 1) tensor -> (hidden, T, 1); w [4*hidden][cin+hidden]."""
+        return self.add(kind=LSTM, cin=cin, cout=hidden, has_bias=1, src0=src)
 
     def xent(self, src=None):
         return self.add(kind=SOFTMAX_XENT, src0=src)
@@ -211,6 +215,19 @@ def resnet50_tail(cin=1024, mid=512, hw=14, n5=3, classes=1000, micro_batch=32, 
                   BASE_SEED + 8, "kaiming")
 
 
+def gnmt_lstm_stage(hidden=1024, seq=50, n_layers=2, micro_batch=64, n_micro=8, dtype=BF16):
+    """n_layers unidirectional LSTM layers of GNMT's width, each with the residual connection of
+    the upper encoder / decoder layers (output = input + LSTM(input)): a middle stage of a
+    4-way split of an 8-layer GNMT.  A sequence is a (hidden, seq, 1) tensor."""
+    b = _Builder()
+    cur = -1
+    for _ in range(n_layers):
+        y = b.lstm(hidden, hidden, src=cur)
+        cur = b.addl(y, cur, relu=0)
+    return _stage("gnmt_lstm_stage", b.layers, dtype, (hidden, seq, 1), micro_batch, n_micro, 2, 4, 1,
+                  BASE_SEED + 11, "lstm")
+
+
 def _concat(name, parts, micro_batch, n_micro, seed, init):
     """One stage holding the layers of consecutive stages (a whole network on one accelerator:
     what the per-layer profile is taken on before it is partitioned)."""
@@ -256,6 +273,7 @@ FULL = {
     "vgg16_conv3": vgg16_conv3,
     "resnet50_stem": resnet50_stem,
     "resnet50_tail": resnet50_tail,
+    "gnmt_lstm_stage": gnmt_lstm_stage,
     "vgg16_full": vgg16_full,
     "resnet50_full": resnet50_full,
     "vgg16_stage1": vgg16_stage1,
@@ -292,6 +310,9 @@ def infer_shapes(stage):
         elif k == LINEAR:
             assert s[0] * s[1] * s[2] == L["cin"], (idx, s, L)
             o = (L["cout"], 1, 1)
+        elif k == LSTM:
+            assert s[0] == L["cin"] and s[2] == 1, (idx, s, L)
+            o = (L["cout"], s[1], 1)
         else:
             raise ValueError(k)
         shapes.append(o)
@@ -299,7 +320,7 @@ def infer_shapes(stage):
 
 
 def conv_fc_macs_per_sample(stage):
-    """Forward multiply-accumulates per sample over CONV2D and LINEAR layers."""
+    """Forward multiply-accumulates per sample over CONV2D, LINEAR and LSTM layers."""
     shapes = infer_shapes(stage)
     total = 0
     per_layer = []
@@ -309,6 +330,8 @@ def conv_fc_macs_per_sample(stage):
             m = o[0] * o[1] * o[2] * L["cin"] * L["kh"] * L["kw"]
         elif L["kind"] == LINEAR:
             m = L["cin"] * L["cout"]
+        elif L["kind"] == LSTM:
+            m = o[1] * 4 * L["cout"] * (L["cin"] + L["cout"])
         per_layer.append(m)
         total += m
     return total, per_layer

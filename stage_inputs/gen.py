@@ -61,6 +61,7 @@ def layer_params(stage, idx, perturb=False):
 
     conv: Kaiming-normal std sqrt(2/fan_in), fan_in = cin*kh*kw ('kaiming' stages) ;
     linear: Xavier-uniform bound sqrt(6/(fan_in+fan_out)) ('xavier' stages) ;
+    lstm: w [4*hidden][cin+hidden] and (perturbed) bias uniform in +-1/sqrt(hidden) ;
     batchnorm: w = gamma = 1, b = beta = 0 ; biases 0.
     perturb=True draws biases/beta ~ 0.1*N(0,1) and gamma ~ 1 + 0.1*N(0,1) instead, so that
     tests can see a dropped bias or scale term."""
@@ -75,6 +76,14 @@ def layer_params(stage, idx, perturb=False):
     elif k == C.LINEAR:
         shp = (L["cout"], L["cin"])
         fan_in, fan_out = L["cin"], L["cout"]
+    elif k == C.LSTM:
+        hd = L["cout"]
+        bound = 1.0 / np.sqrt(hd)
+        w = r.uniform(-bound, bound, size=(4 * hd, L["cin"] + hd)).astype(np.float32)
+        b = np.zeros(4 * hd, np.float32)
+        if perturb:
+            b = rb.uniform(-bound, bound, size=4 * hd).astype(np.float32)
+        return w, b
     elif k == C.BATCHNORM2D:
         g = np.ones(L["cout"], np.float32)
         b = np.zeros(L["cout"], np.float32)

@@ -290,6 +290,85 @@ def test_avgpool_hand_global_and_torch():
     assert np.allclose(dx, xt.grad.numpy(), atol=1e-15)
 
 
+# ------------------------------------------------------------------ LSTM
+def _torch_lstm(x, w, b, In, Hd):
+    """torch.nn.LSTM (CPU, fp64) loaded with the same weights: x [N][In][T][1] -> module, sequence-first view."""
+    m = torch.nn.LSTM(In, Hd, batch_first=True).double()
+    with torch.no_grad():
+        m.weight_ih_l0.copy_(_t(w[:, :In]))
+        m.weight_hh_l0.copy_(_t(w[:, In:]))
+        m.bias_ih_l0.copy_(_t(b))
+        m.bias_hh_l0.zero_()
+    return m
+
+
+def test_lstm_one_step_closed_form_and_saturated_forget_gate():
+    # zero weights: every gate sees only its bias
+    Hd, In = 3, 2
+    w = np.zeros((4 * Hd, In + Hd))
+    b = RNG.standard_normal(4 * Hd)
+    x = RNG.standard_normal((2, In, 1, 1))
+    y, _ = ops.lstm_fwd(x, w, b)
+    sg = lambda v: 1 / (1 + np.exp(-v))
+    want = sg(b[3 * Hd:]) * np.tanh(sg(b[:Hd]) * np.tanh(b[2 * Hd:3 * Hd]))
+    assert np.allclose(y[:, :, 0, 0], want[None, :], atol=1e-15)
+    # forget gate held at 1 (bias +40), constant input gate and candidate: c_t grows by i*g per step
+    b2 = b.copy()
+    b2[Hd:2 * Hd] = 40.0
+    T = 6
+    y, (gates, cells) = ops.lstm_fwd(np.zeros((1, In, T, 1)), w, b2)
+    step = sg(b2[:Hd]) * np.tanh(b2[2 * Hd:3 * Hd])
+    for t in range(T):
+        assert np.allclose(cells[0, t], (t + 1) * step, atol=1e-12)
+        assert np.allclose(y[0, :, t, 0], sg(b2[3 * Hd:]) * np.tanh((t + 1) * step), atol=1e-12)
+
+
+@pytest.mark.parametrize("N,In,Hd,T", [(3, 4, 5, 7), (2, 6, 3, 1), (1, 2, 2, 9)])
+def test_lstm_vs_torch_autograd_and_finite_differences(N, In, Hd, T):
+    x = RNG.standard_normal((N, In, T, 1))
+    w = RNG.standard_normal((4 * Hd, In + Hd)) * 0.5
+    b = RNG.standard_normal(4 * Hd) * 0.5
+    dy = RNG.standard_normal((N, Hd, T, 1))
+    y, saved = ops.lstm_fwd(x, w, b)
+    dw, db = np.zeros_like(w), np.zeros_like(b)
+    dx = ops.lstm_bwd(x, y, w, saved, dy, dw, db)
+    m = _torch_lstm(x, w, b, In, Hd)
+    xt = _t(x[:, :, :, 0].transpose(0, 2, 1).copy()).requires_grad_()       # [N][T][In]
+    yt, _ = m(xt)
+    assert np.allclose(y[:, :, :, 0].transpose(0, 2, 1), yt.detach().numpy(), atol=1e-13)
+    yt.backward(_t(dy[:, :, :, 0].transpose(0, 2, 1).copy()))
+    assert np.allclose(dx[:, :, :, 0].transpose(0, 2, 1), xt.grad.numpy(), atol=1e-12)
+    assert np.allclose(dw[:, :In], m.weight_ih_l0.grad.numpy(), atol=1e-12)
+    assert np.allclose(dw[:, In:], m.weight_hh_l0.grad.numpy(), atol=1e-12)
+    assert np.allclose(db, m.bias_ih_l0.grad.numpy(), atol=1e-12)
+    # central differences of <lstm(x), dy> in a few random directions
+    f = lambda x_, w_, b_: float(np.sum(ops.lstm_fwd(x_, w_, b_)[0] * dy))
+    h = 1e-6
+    for _ in range(3):
+        ex, ew, eb = RNG.standard_normal(x.shape), RNG.standard_normal(w.shape), RNG.standard_normal(b.shape)
+        fd = (f(x + h * ex, w + h * ew, b + h * eb) - f(x - h * ex, w - h * ew, b - h * eb)) / (2 * h)
+        an = np.sum(dx * ex) + np.sum(dw * ew) + np.sum(db * eb)
+        assert abs(fd - an) <= 1e-7 * max(1.0, abs(an)), (fd, an)
+
+
+def test_lstm_gradients_accumulate_and_rounding_points():
+    N, In, Hd, T = 2, 3, 4, 5
+    x = ops.round_bf16(RNG.standard_normal((N, In, T, 1)))
+    w = ops.round_bf16(RNG.standard_normal((4 * Hd, In + Hd)) * 0.5)
+    b = RNG.standard_normal(4 * Hd) * 0.5
+    y, saved = ops.lstm_fwd(x, w, b, round16=True)
+    assert np.array_equal(y, ops.round_bf16(y))                     # the layer output is a stored tensor
+    y_exact, _ = ops.lstm_fwd(x, w, b)
+    assert 0 < np.max(np.abs(y - y_exact)) < 2e-2
+    dy = RNG.standard_normal(y.shape)
+    dw, db = np.ones_like(w), np.ones_like(b)
+    ops.lstm_bwd(x, y, w, saved, dy, dw, db)
+    dw2, db2 = np.zeros_like(w), np.zeros_like(b)
+    ops.lstm_bwd(x, y, w, saved, dy, dw2, db2)
+    assert np.allclose(dw, 1 + dw2, atol=1e-13) and np.allclose(db, 1 + db2, atol=1e-13)
+    assert ops.lstm_bwd(x, y, w, saved, dy, dw2, db2, want_dx=False) is None
+
+
 # ------------------------------------------------------------------ batch-norm
 def test_bn_forward_invariants():
     x = 3.0 + 2.0 * RNG.standard_normal((4, 5, 6, 7))

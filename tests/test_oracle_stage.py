@@ -22,6 +22,7 @@ def small_stages():
         "vgg16_conv3": C.vgg16_conv3(cin=4, c=6, hw=8, micro_batch=2, n_micro=2),
         "resnet50_stem": C.resnet50_stem(c=4, hw=16, n2=2, micro_batch=3, n_micro=2),
         "resnet50_tail": C.resnet50_tail(cin=8, mid=4, hw=4, n5=2, classes=5, micro_batch=3, n_micro=2),
+        "gnmt_lstm_stage": C.gnmt_lstm_stage(hidden=5, seq=6, n_layers=2, micro_batch=3, n_micro=2),
     }
 
 
@@ -218,7 +219,7 @@ def test_workload_shapes_and_flop_table():
     want = {"tiny": 2.80e6, "vgg16_stage1": 4.711e9, "vgg16_deep": 6.011e9,
             "vgg16_classifier": 123.6e6, "resnet50_stage": 2.492e9, "vgg16_conv3": 4.624e9,
             "resnet50_stem": 785.9e6, "resnet50_tail": 811.3e6, "vgg16_full": 15.47e9,
-            "resnet50_full": 4.089e9}
+            "resnet50_full": 4.089e9, "gnmt_lstm_stage": 2 * 50 * 4 * 1024 * 2048}
     for name, f in C.FULL.items():
         st = f()
         macs, _ = C.conv_fc_macs_per_sample(st)
