@@ -210,7 +210,7 @@ def main():
         # about 10-30 s of oracle work on the 16 host threads of the GPU machine
         default_sample = {"tiny": 16, "vgg16_stage1": 32, "vgg16_deep": 32, "vgg16_classifier": 64,
                           "resnet50_stage": 32, "vgg16_conv3": 32, "resnet50_stem": 32, "resnet50_tail": 32,
-                          "vgg16_full": 16, "resnet50_full": 32}[a.workload]
+                          "vgg16_full": 16, "resnet50_full": 32, "gnmt_lstm_stage": 64}[a.workload]
         sample = min(mb * M if a.workload == "tiny" else mb, a.cpu_sample or default_sample)
         sample = min(sample, mb)
         out["cpu_baseline"] = cpu_baseline(stage, sample)

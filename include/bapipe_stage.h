@@ -30,7 +30,11 @@
  *    opts->io_layout; softmax outputs and losses are always float.
  *  - Parameter layouts at this boundary follow the PyTorch conventions: conv weights OIHW,
  *    linear weights [out][in] where `in` indexes the NCHW flattening (c*H*W + h*W + w) of
- *    the producing tensor, batch-norm w = gamma, b = beta.
+ *    the producing tensor, batch-norm w = gamma, b = beta.  LSTM (the layer of the paper's
+ *    sequence-to-sequence workload, Sec. IV-A; hidden size cout, zero initial state, gates in
+ *    the order input, forget, candidate, output): w is [4*cout][cin+cout], row q*cout + j =
+ *    gate q of unit j, first the cin input weights, then the cout recurrent ones; b is
+ *    [4*cout] (the sum of PyTorch's two bias vectors).
  */
 #ifndef BAPIPE_STAGE_H
 #define BAPIPE_STAGE_H
@@ -63,7 +67,8 @@ typedef enum {
     BAPIPE_FLATTEN = 5,      /* (C,H,W) -> (C*H*W,1,1)                                      */
     BAPIPE_LINEAR = 6,       /* y = x W^T + b                                               */
     BAPIPE_SOFTMAX_XENT = 7, /* last layer only: p = softmax(z); loss from labels in bwd    */
-    BAPIPE_AVGPOOL2D = 8     /* mean of k x k windows, stride = k, pad = 0 (k = H: global)  */
+    BAPIPE_AVGPOOL2D = 8,    /* mean of k x k windows, stride = k, pad = 0 (k = H: global)  */
+    BAPIPE_LSTM = 9          /* LSTM over the H axis of a (cin, T, 1) tensor -> (cout, T, 1) */
 } bapipe_layer_kind_t;
 
 /* One layer of the stage.  src0/src1: index of the producing layer in the list, -1 = the

@@ -57,6 +57,11 @@ hipError_t conv3x3_c8_mfma(const void *in, const void *wt, const float *bias, vo
 // [N][H/2][W/2][Co] and the arg-max indices (one byte each, same layout); the conv output is not stored
 hipError_t conv3x3_halo_pool_mfma(const void *in, const void *wt, const float *bias, int relu, void *pool_out,
                                   uint8_t *pool_idx, const GatherConv &g, hipStream_t s);
+// The same implicit GEMM leaving raw fp32 sums: part[split][pixel][co], *splits partial results the
+// caller adds up (no bias, no epilogue, no rounding).  Used for the recurrent products of the LSTM.
+size_t conv_gather_mfma_raw_workspace(const GatherConv &g);
+hipError_t conv_gather_mfma_raw(const void *in, const void *wt, const GatherConv &g, float *part, int *splits,
+                                hipStream_t s);
 bool wgrad3x3_halo_supported(const ConvShape &c);
 size_t wgrad3x3_halo_workspace(const ConvShape &c);
 hipError_t wgrad3x3_halo_mfma(const void *x, const void *dy, float *dw, float *db, void *workspace,
@@ -93,6 +98,18 @@ hipError_t avgpool_bwd(int dt, const void *dy, void *dx, GradEpi epi, int N, int
 hipError_t add_fwd(int dt, const void *a, const void *b, void *y, int relu, size_t n, hipStream_t s);
 // dx (+)= dy with the epilogue of grad_out
 hipError_t grad_copy(int dt, const void *dy, void *dx, GradEpi epi, size_t n, hipStream_t s);
+
+// ---- LSTM cell, one time step t over all N sequences (gate order i, f, g, o; H = hidden size)
+// P: input projection incl. bias [N][T][4H] (storage type); gh: S partial recurrent sums [S][N][4H]
+// (S = 0 at t = 0); writes gates [N][T][4H] and cells [N][T][H] (float), h [N][T][H] and the
+// one-step-delayed copy hs (hs[:, t+1] = h[:, t], hs[:, 0] = 0) in the storage type.
+hipError_t lstm_cell_fwd(int dt, const void *P, const float *gh, int S, float *gates, float *cells, void *h,
+                         void *hs, int N, int T, int H, int t, hipStream_t s);
+// dy: gradient of h [N][T][H]; r: S partial sums of W_h^T D_{t+1} [S][N][H] (S = 0 at t = T-1);
+// dcn [N][H] carries dc_{t+1}*f_{t+1} between steps; writes D[:, t] (pre-activation gradients,
+// [N][T][4H], storage type).
+hipError_t lstm_cell_bwd(int dt, const void *dy, const float *r, int S, const float *gates, const float *cells,
+                         float *dcn, void *D, int N, int T, int H, int t, hipStream_t s);
 
 size_t bn_workspace(int rows, int C);
 // stats: [2][C] floats (mean, invstd)

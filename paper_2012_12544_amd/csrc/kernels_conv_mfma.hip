@@ -441,7 +441,7 @@ GatherPlan gather_plan(const GatherConv &g)
 
 template <int BP, int BC, int WP, int WC, int BK, int STAGES>
 hipError_t launch_gather(const void *in, const void *wt, const float *bias, void *out, int relu, GradEpi epi,
-                         const GatherConv &g, const GatherPlan &plan, void *workspace, hipStream_t s)
+                         const GatherConv &g, const GatherPlan &plan, void *workspace, hipStream_t s, bool raw = false)
 {
     constexpr int NT = WP * WC * 64;
     constexpr size_t main_bytes = (size_t)STAGES * (BP + BC) * BK * 2;
@@ -453,7 +453,7 @@ hipError_t launch_gather(const void *in, const void *wt, const float *bias, void
     const int is_grad = (epi.gate != nullptr || epi.accum) ? 1 : 0;
     const unsigned in_bytes = (unsigned)((size_t)g.N * g.Hi * g.Wi * g.Ci * 2);
     const unsigned wt_bytes = (unsigned)((size_t)g.Co * g.R * g.S * g.Ci * 2);
-    float *part = plan.splits > 1 ? (float *)workspace : nullptr;
+    float *part = (plan.splits > 1 || raw) ? (float *)workspace : nullptr;      // raw: the fp32 partials are the result
     dim3 grid((unsigned)(tiles_p * tiles_c), (unsigned)plan.splits);
 #define GATHER_LAUNCH(S1_, TI_)                                                                                   \
     do {                                                                                                          \
@@ -477,7 +477,7 @@ hipError_t launch_gather(const void *in, const void *wt, const float *bias, void
         else GATHER_LAUNCH(false, false);
     }
 #undef GATHER_LAUNCH
-    if (part) {
+    if (part && !raw) {
         const size_t total = (size_t)npix * g.Co;
         hipLaunchKernelGGL(k_gather_splitk_reduce, dim3((unsigned)((total / 8 + 255) / 256)), dim3(256), 0, s, part,
                            plan.splits, total, g.Co, bias, (bf16_t *)out, (const bf16_t *)epi.gate, epi.accum, relu,
@@ -839,6 +839,26 @@ hipError_t conv_gather_mfma(const void *in, const void *wt, const float *bias, v
     if (p.bc == 256) return launch_gather<256, 256, 2, 4, 32, 3>(in, wt, bias, out, relu, epi, g, p, workspace, s);
     if (p.bp == 128) return launch_gather<128, 128, 2, 2, 32, 3>(in, wt, bias, out, relu, epi, g, p, workspace, s);
     return launch_gather<256, 128, 2, 2, 32, 3>(in, wt, bias, out, relu, epi, g, p, workspace, s);
+}
+
+size_t conv_gather_mfma_raw_workspace(const GatherConv &g)
+{
+    return (size_t)gather_plan(g).splits * g.N * g.Ho * g.Wo * g.Co * sizeof(float);
+}
+
+hipError_t conv_gather_mfma_raw(const void *in, const void *wt, const GatherConv &g, float *part, int *splits,
+                                hipStream_t s)
+{
+    if (!conv_gather_mfma_supported(g) || !part || !splits || g.Co % 4 != 0) return hipErrorInvalidValue;
+    const GatherPlan p = gather_plan(g);
+    *splits = p.splits;
+    if ((long long)g.N * g.Ho * g.Wo == 0) return hipSuccess;
+    const GradEpi none{nullptr, 0};
+    if (p.bp == 64) return launch_gather<64, 128, 1, 4, 32, 3>(in, wt, nullptr, nullptr, 0, none, g, p, part, s, true);
+    if (p.bc == 64) return launch_gather<256, 64, 4, 1, 32, 3>(in, wt, nullptr, nullptr, 0, none, g, p, part, s, true);
+    if (p.bc == 256) return launch_gather<256, 256, 2, 4, 32, 3>(in, wt, nullptr, nullptr, 0, none, g, p, part, s, true);
+    if (p.bp == 128) return launch_gather<128, 128, 2, 2, 32, 3>(in, wt, nullptr, nullptr, 0, none, g, p, part, s, true);
+    return launch_gather<256, 128, 2, 2, 32, 3>(in, wt, nullptr, nullptr, 0, none, g, p, part, s, true);
 }
 
 bool conv_wgrad_mfma_supported(const ConvShape &c)

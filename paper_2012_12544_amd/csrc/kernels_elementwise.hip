@@ -821,6 +821,68 @@ __global__ __launch_bounds__(OP_NT) void k_bn_bwd_onepass(const T *__restrict__ 
     }
 }
 
+// ------------------------------------------------------------------ LSTM cell
+__device__ __forceinline__ float sigmoidf(float v) { return 1.0f / (1.0f + expf(-v)); }
+
+template <class T>
+__global__ void k_lstm_cell_fwd(const T *__restrict__ P, const float *__restrict__ gh, int S,
+                                float *__restrict__ gates, float *__restrict__ cells, T *__restrict__ h,
+                                T *__restrict__ hs, int N, int Tn, int H, int t)
+{
+    const size_t i = (size_t)blockIdx.x * TPB + threadIdx.x;
+    if (i >= (size_t)N * H) return;
+    const int n = (int)(i / H), j = (int)(i % H);
+    const size_t row = (size_t)n * Tn + t;
+    float a[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        a[q] = to_f32(P[row * 4 * H + (size_t)q * H + j]);
+        float rsum = 0.0f;
+        for (int sp = 0; sp < S; ++sp) rsum += gh[((size_t)sp * N + n) * 4 * H + (size_t)q * H + j];
+        a[q] += rsum;
+    }
+    const float ig = sigmoidf(a[0]), fg = sigmoidf(a[1]), gg = tanhf(a[2]), og = sigmoidf(a[3]);
+    const float cprev = t > 0 ? cells[(row - 1) * H + j] : 0.0f;
+    const float c = fg * cprev + ig * gg;
+    float *gt = gates + row * 4 * H + j;
+    gt[0] = ig;
+    gt[H] = fg;
+    gt[2 * (size_t)H] = gg;
+    gt[3 * (size_t)H] = og;
+    cells[row * H + j] = c;
+    const T hv = from_f32<T>(og * tanhf(c));
+    h[row * H + j] = hv;
+    if (t + 1 < Tn) hs[(row + 1) * H + j] = hv;
+    if (t == 0) hs[row * H + j] = from_f32<T>(0.0f);
+}
+
+template <class T>
+__global__ void k_lstm_cell_bwd(const T *__restrict__ dy, const float *__restrict__ r, int S,
+                                const float *__restrict__ gates, const float *__restrict__ cells,
+                                float *__restrict__ dcn, T *__restrict__ D, int N, int Tn, int H, int t)
+{
+    const size_t i = (size_t)blockIdx.x * TPB + threadIdx.x;
+    if (i >= (size_t)N * H) return;
+    const int n = (int)(i / H), j = (int)(i % H);
+    const size_t row = (size_t)n * Tn + t;
+    float dh = to_f32(dy[row * H + j]);
+    float rsum = 0.0f;
+    for (int sp = 0; sp < S; ++sp) rsum += r[((size_t)sp * N + n) * H + j];
+    dh += rsum;
+    const float *gt = gates + row * 4 * H + j;
+    const float ig = gt[0], fg = gt[H], gg = gt[2 * (size_t)H], og = gt[3 * (size_t)H];
+    const float th = tanhf(cells[row * H + j]);
+    const float cprev = t > 0 ? cells[(row - 1) * H + j] : 0.0f;
+    const float carry = t + 1 < Tn ? dcn[i] : 0.0f;
+    const float dc = dh * og * (1.0f - th * th) + carry;
+    T *d = D + row * 4 * H + j;
+    d[0] = from_f32<T>(dc * gg * ig * (1.0f - ig));
+    d[H] = from_f32<T>(dc * cprev * fg * (1.0f - fg));
+    d[2 * (size_t)H] = from_f32<T>(dc * ig * (1.0f - gg * gg));
+    d[3 * (size_t)H] = from_f32<T>(dh * th * og * (1.0f - og));
+    dcn[i] = dc * fg;
+}
+
 // ------------------------------------------------------------------ softmax cross-entropy
 template <class T>
 __global__ void k_softmax_fwd(const T *__restrict__ z, float *__restrict__ p, int K)
@@ -1284,6 +1346,28 @@ hipError_t bn_bwd(int dt, const void *x, const void *dy, const float *gamma, con
                                (const T *)x, (const T *)dy, gamma, stats, sums, (T *)dx, (const T *)epi.gate,
                                epi.accum, 1.0f / (float)rows, rows, C, p);
         }
+    });
+    return hipGetLastError();
+}
+
+hipError_t lstm_cell_fwd(int dt, const void *P, const float *gh, int S, float *gates, float *cells, void *h,
+                         void *hs, int N, int Tn, int H, int t, hipStream_t s)
+{
+    if (N <= 0 || H <= 0 || t < 0 || t >= Tn || S < 0 || (t == 0 && S != 0)) return hipErrorInvalidValue;
+    DISPATCH_T(dt, {
+        hipLaunchKernelGGL((k_lstm_cell_fwd<T>), dim3(blocks_for((size_t)N * H)), dim3(TPB), 0, s, (const T *)P, gh, S,
+                           gates, cells, (T *)h, (T *)hs, N, Tn, H, t);
+    });
+    return hipGetLastError();
+}
+
+hipError_t lstm_cell_bwd(int dt, const void *dy, const float *r, int S, const float *gates, const float *cells,
+                         float *dcn, void *D, int N, int Tn, int H, int t, hipStream_t s)
+{
+    if (N <= 0 || H <= 0 || t < 0 || t >= Tn || S < 0 || (t == Tn - 1 && S != 0)) return hipErrorInvalidValue;
+    DISPATCH_T(dt, {
+        hipLaunchKernelGGL((k_lstm_cell_bwd<T>), dim3(blocks_for((size_t)N * H)), dim3(TPB), 0, s, (const T *)dy, r, S,
+                           gates, cells, dcn, (T *)D, N, Tn, H, t);
     });
     return hipGetLastError();
 }

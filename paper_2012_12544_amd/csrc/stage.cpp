@@ -65,6 +65,10 @@ struct Layer {
     // the conv output is never stored (fuse_pool = index of that pool layer; fused marks the pool)
     int fuse_pool = -1;
     bool fused = false;
+    // LSTM: per in-flight micro-batch the slot keeps the gates and cell states (float), the delayed
+    // copy of h that the recurrent products read, the buffer shared by the input projection
+    // (forward) and the pre-activation gradients (backward) and the cell-gradient carry
+    size_t off_gates = 0, off_cells = 0, off_hs = 0, off_pd = 0, off_dcn = 0;
     bool permute_in = false;             // LINEAR fed by a flattened (C,H,W) tensor
     int pc = 0, ph = 0, pw = 0;
 };
@@ -163,7 +167,11 @@ int create_fail(int code, const char *fmt, ...)
     return code;
 }
 
-bool has_params(int kind) { return kind == BAPIPE_CONV2D || kind == BAPIPE_LINEAR || kind == BAPIPE_BATCHNORM2D; }
+bool has_params(int kind)
+{
+    return kind == BAPIPE_CONV2D || kind == BAPIPE_LINEAR || kind == BAPIPE_BATCHNORM2D || kind == BAPIPE_LSTM;
+}
+bool has_matrix(int kind) { return kind == BAPIPE_CONV2D || kind == BAPIPE_LINEAR || kind == BAPIPE_LSTM; }
 
 GatherConv fwd_geom(const bapipe_stage *st, const Layer &L)
 {
@@ -228,6 +236,14 @@ bool use_mfma_wgrad(const bapipe_stage *st, const ConvShape &c) { return st->dt 
 void to_internal(const Layer &L, const float *src, float *dst)
 {
     const int K = L.d.cout;
+    if (L.d.kind == BAPIPE_LSTM) {       // [4H][In+H] rows -> the input block [4H][In], then the recurrent block [4H][H]
+        const int In = L.d.cin, H = L.d.cout, G = 4 * H;
+        for (int k = 0; k < G; ++k) {
+            memcpy(dst + (size_t)k * In, src + (size_t)k * (In + H), sizeof(float) * In);
+            memcpy(dst + (size_t)G * In + (size_t)k * H, src + (size_t)k * (In + H) + In, sizeof(float) * H);
+        }
+        return;
+    }
     if (L.d.kind == BAPIPE_LINEAR) {
         const int In = L.d.cin;
         if (!L.permute_in) {
@@ -254,6 +270,14 @@ void to_internal(const Layer &L, const float *src, float *dst)
 void from_internal(const Layer &L, const float *src, float *dst)
 {
     const int K = L.d.cout;
+    if (L.d.kind == BAPIPE_LSTM) {
+        const int In = L.d.cin, H = L.d.cout, G = 4 * H;
+        for (int k = 0; k < G; ++k) {
+            memcpy(dst + (size_t)k * (In + H), src + (size_t)k * In, sizeof(float) * In);
+            memcpy(dst + (size_t)k * (In + H) + In, src + (size_t)G * In + (size_t)k * H, sizeof(float) * H);
+        }
+        return;
+    }
     if (L.d.kind == BAPIPE_LINEAR) {
         const int In = L.d.cin;
         if (!L.permute_in) {
@@ -277,13 +301,135 @@ void from_internal(const Layer &L, const float *src, float *dst)
 }
 
 // working copies of one layer's weights from its fp32 master
-hipError_t refresh_work(bapipe_stage *st, Layer &L)
+// channel-transposed (and flipped) copy of the master weights that the input-gradient GEMMs read
+hipError_t refresh_transposed(bapipe_stage *st, Layer &L)
 {
-    if (L.d.kind != BAPIPE_CONV2D && L.d.kind != BAPIPE_LINEAR) return hipSuccess;
-    hipError_t e = recast(st->dt, L.w, L.w_work, L.w_elems, st->stream);
-    if (e != hipSuccess) return e;
+    if (L.d.kind == BAPIPE_LSTM) {       // [In][4H] for dx, then [H][4H] for the recurrent gradient
+        const int In = L.d.cin, H = L.d.cout, G = 4 * H;
+        const size_t es = dt_size(st->dt);
+        hipError_t e = make_dgrad_filter(st->dt, L.w, L.w_t, G, 1, 1, In, st->stream);
+        if (e != hipSuccess) return e;
+        return make_dgrad_filter(st->dt, L.w + (size_t)G * In, (char *)L.w_t + (size_t)G * In * es, G, 1, 1, H, st->stream);
+    }
     int R = L.d.kind == BAPIPE_LINEAR ? 1 : L.d.kh, S = L.d.kind == BAPIPE_LINEAR ? 1 : L.d.kw;
     return make_dgrad_filter(st->dt, L.w, L.w_t, L.d.cout, R, S, L.cin_p, st->stream);
+}
+
+hipError_t refresh_work(bapipe_stage *st, Layer &L)
+{
+    if (!has_matrix(L.d.kind)) return hipSuccess;
+    hipError_t e = recast(st->dt, L.w, L.w_work, L.w_elems, st->stream);
+    if (e != hipSuccess) return e;
+    return refresh_transposed(st, L);
+}
+
+// ---------------------------------------------------------------- LSTM layer (sequence axis = H, W = 1)
+// GEMM over all N*T rows of a [N][T][ci] tensor: out[row][co] = sum in[row][ci] * wt[co][ci]
+GatherConv rows_geom(int N, int T, int ci, int co)
+{
+    GatherConv g;
+    g.N = N; g.Hi = T; g.Wi = 1; g.Ci = ci;
+    g.Ho = T; g.Wo = 1; g.Co = co;
+    g.R = g.S = 1; g.s_out = g.s_in = 1; g.pad_h = g.pad_w = 0;
+    return g;
+}
+// the same product restricted to the rows (n, t) of every sequence: one output row per sequence
+GatherConv step_geom(int N, int T, int ci, int co, int t)
+{
+    GatherConv g = rows_geom(N, T, ci, co);
+    g.Ho = 1;
+    g.pad_h = -t;                      // output row 0 reads input row t
+    return g;
+}
+
+// fp32 sums of one recurrent product: *S partial results [S][N][co] in the workspace
+int step_product(bapipe_stage *st, const void *in, const void *wt, const GatherConv &g, int *S)
+{
+    if (st->dt == DT_BF16) {
+        HIPCHK(conv_gather_mfma_raw(in, wt, g, (float *)st->work, S, st->stream));
+    } else {
+        GradEpi none{nullptr, 0};
+        HIPCHK(conv_gather_direct(st->dt, in, wt, nullptr, st->work, 0, none, g, st->stream));
+        *S = 1;
+    }
+    return BAPIPE_OK;
+}
+
+int lstm_forward(bapipe_stage *st, Layer &L, const void *x, void *h, int mbid)
+{
+    const Tensor &A = st->tensors[L.a];
+    const int N = st->mb, T = A.H, In = A.Cp, H = L.d.cout, G = 4 * H;
+    hipStream_t s = st->stream;
+    char *slot = st->slot(mbid);
+    void *P = slot + L.off_pd, *hs = slot + L.off_hs;
+    float *gates = (float *)(slot + L.off_gates), *cells = (float *)(slot + L.off_cells);
+    const char *w_hh = (const char *)L.w_work + (size_t)G * In * dt_size(st->dt);
+    GradEpi none{nullptr, 0};
+    const GatherConv gx = rows_geom(N, T, In, G);
+    const bool tp = st->tap_begin(st->dt == DT_BF16 ? BAPIPE_KC_CONV_GATHER_MFMA : BAPIPE_KC_CONV_DIRECT);
+    if (st->dt == DT_BF16)
+        HIPCHK(conv_gather_mfma(x, L.w_work, L.bias, P, 0, none, gx, st->work, s));
+    else
+        HIPCHK(conv_gather_direct(st->dt, x, L.w_work, L.bias, P, 0, none, gx, s));
+    for (int t = 0; t < T; ++t) {
+        int S = 0;
+        if (t > 0) {                                   // W_h h_{t-1}: row t of the delayed copy
+            int rc = step_product(st, hs, w_hh, step_geom(N, T, H, G, t), &S);
+            if (rc != BAPIPE_OK) return rc;
+        }
+        HIPCHK(lstm_cell_fwd(st->dt, P, (const float *)st->work, S, gates, cells, h, hs, N, T, H, t, s));
+    }
+    st->tap_end(tp, 2.0 * N * T * (double)G * (L.d.cin + H), 0.0);
+    return BAPIPE_OK;
+}
+
+// dy: gradient of the layer output [N][T][H]; dx (may be NULL) receives W_x^T D through the epilogue e
+int lstm_backward(bapipe_stage *st, Layer &L, const void *x, const void *dy, void *dx, GradEpi e, int mbid)
+{
+    const Tensor &A = st->tensors[L.a];
+    const int N = st->mb, T = A.H, In = A.Cp, H = L.d.cout, G = 4 * H;
+    const size_t es = dt_size(st->dt);
+    hipStream_t s = st->stream;
+    char *slot = st->slot(mbid);
+    void *D = slot + L.off_pd;
+    const void *hs = slot + L.off_hs;
+    const float *gates = (const float *)(slot + L.off_gates), *cells = (const float *)(slot + L.off_cells);
+    float *dcn = (float *)(slot + L.off_dcn);
+    const char *wt_x = (const char *)L.w_t, *wt_h = wt_x + (size_t)G * In * es;
+    const bool mf = st->dt == DT_BF16;
+    bool tp = st->tap_begin(mf ? BAPIPE_KC_CONV_GATHER_MFMA : BAPIPE_KC_CONV_DIRECT);
+    for (int t = T - 1; t >= 0; --t) {
+        int S = 0;
+        if (t + 1 < T) {                               // W_h^T D_{t+1}
+            int rc = step_product(st, D, wt_h, step_geom(N, T, G, H, t + 1), &S);
+            if (rc != BAPIPE_OK) return rc;
+        }
+        HIPCHK(lstm_cell_bwd(st->dt, dy, (const float *)st->work, S, gates, cells, dcn, D, N, T, H, t, s));
+    }
+    double flop = 2.0 * N * (T - 1) * (double)G * H;
+    if (dx) {
+        const GatherConv gd = rows_geom(N, T, G, In);
+        if (mf)
+            HIPCHK(conv_gather_mfma(D, wt_x, nullptr, dx, 0, e, gd, st->work, s));
+        else
+            HIPCHK(conv_gather_direct(st->dt, D, wt_x, nullptr, dx, 0, e, gd, s));
+        flop += 2.0 * N * T * (double)G * L.d.cin;
+    }
+    st->tap_end(tp, flop, 0.0);
+    // dW_x += D^T x (the bias gradient rides along), dW_h += D^T (delayed h)
+    ConvShape cx{N, T, 1, In, T, 1, G, 1, 1, 1, 0}, ch{N, T, 1, H, T, 1, G, 1, 1, 1, 0};
+    float *dw_h = L.dw + (size_t)G * In;
+    tp = st->tap_begin(mf ? BAPIPE_KC_CONV_WGRAD_MFMA : BAPIPE_KC_CONV_DIRECT);
+    if (mf) {
+        HIPCHK(conv_wgrad_mfma(x, D, L.dw, L.db, st->work, cx, s));
+        HIPCHK(conv_wgrad_mfma(hs, D, dw_h, nullptr, st->work, ch, s));
+    } else {
+        HIPCHK(conv_wgrad_direct(st->dt, x, D, L.dw, st->work, cx, s));
+        HIPCHK(conv_wgrad_direct(st->dt, hs, D, dw_h, st->work, ch, s));
+        if (L.db) HIPCHK(colsum_accumulate(st->dt, D, N * T, G, L.db, st->work, s));
+    }
+    st->tap_end(tp, 2.0 * N * T * (double)G * (L.d.cin + H), 0.0);
+    return BAPIPE_OK;
 }
 
 // ---------------------------------------------------------------- per-layer forward
@@ -364,6 +510,11 @@ int layer_forward(bapipe_stage *st, int li, const FwdCtx &c)
     }
     case BAPIPE_FLATTEN:
         break;   // alias of its input
+    case BAPIPE_LSTM: {
+        int rc = lstm_forward(st, L, a, o, c.mbid);
+        if (rc != BAPIPE_OK) return rc;
+        break;
+    }
     case BAPIPE_SOFTMAX_XENT:
         HIPCHK(softmax_fwd(dt, a, (float *)o, st->mb, O.C, s));
         break;
@@ -510,6 +661,17 @@ int layer_backward(bapipe_stage *st, int li, BwdCtx &c)
     }
     case BAPIPE_FLATTEN:
         break;
+    case BAPIPE_LSTM: {
+        GradEpi e{nullptr, 0};
+        void *dx = nullptr;
+        if (a_grad) {
+            e = epi_for(st, L.a, c);
+            dx = grad_ptr(st, L.a, c);
+        }
+        int rc = lstm_backward(st, L, st->tptr(L.a, c.mbid), grad_ptr(st, L.o, c), dx, e, c.mbid);
+        if (rc != BAPIPE_OK) return rc;
+        break;
+    }
     case BAPIPE_SOFTMAX_XENT:
         if (a_grad) {
             c.written[A.root] = 1;
@@ -654,6 +816,19 @@ int bapipe_stage_create(const bapipe_layer_desc_t *layers, int n_layers, int mic
             if (R.H * R.W > 1) { L.permute_in = true; L.pc = R.C; L.ph = R.H; L.pw = R.W; }
             break;
         }
+        case BAPIPE_LSTM: {
+            if (d.cin <= 0 || d.cout <= 0) return create_fail(BAPIPE_E_INVALID, "layer %d: bad LSTM parameters", i);
+            if (A.C != d.cin) return create_fail(BAPIPE_E_SHAPE, "layer %d: cin=%d but input has %d channels", i, d.cin, A.C);
+            if (A.W != 1) return create_fail(BAPIPE_E_SHAPE, "layer %d: LSTM input must be (cin, T, 1)", i);
+            if (A.Cp != A.C) return create_fail(BAPIPE_E_UNSUPPORTED, "layer %d: LSTM input with padded channels", i);
+            if (opts->dtype == BAPIPE_BF16 && (d.cin % 8 || d.cout % 8))
+                return create_fail(BAPIPE_E_UNSUPPORTED, "layer %d: bf16 LSTM needs cin and cout that are multiples of 8", i);
+            O.C = d.cout; O.H = A.H; O.W = 1;
+            L.cin_p = A.Cp;
+            L.w_elems = (size_t)4 * d.cout * (d.cin + d.cout);
+            L.b_elems = d.has_bias ? (size_t)4 * d.cout : 0;
+            break;
+        }
         case BAPIPE_RELU:
             O.C = A.C; O.H = A.H; O.W = A.W;
             break;
@@ -736,7 +911,7 @@ int bapipe_stage_create(const bapipe_layer_desc_t *layers, int n_layers, int mic
         const Layer &L = st->layers[i];
         Tensor &RA = st->tensors[root_of(L.a)];
         switch (L.d.kind) {
-        case BAPIPE_CONV2D: case BAPIPE_LINEAR: case BAPIPE_BATCHNORM2D:
+        case BAPIPE_CONV2D: case BAPIPE_LINEAR: case BAPIPE_BATCHNORM2D: case BAPIPE_LSTM:
             RA.stashed = true;
             break;
         case BAPIPE_RELU: case BAPIPE_SOFTMAX_XENT:
@@ -800,6 +975,34 @@ int bapipe_stage_create(const bapipe_layer_desc_t *layers, int n_layers, int mic
             size_t w = bn_workspace(micro_batch * A.H * A.W, A.C);
             work = w > work ? w : work;
         }
+        if (L.d.kind == BAPIPE_LSTM) {
+            const int N = micro_batch, T = A.H, In = A.Cp, H = L.d.cout, G = 4 * H;
+            const size_t rows = (size_t)N * T;
+            L.aux_off = slot;
+            L.off_gates = slot; slot += align_up(rows * G * sizeof(float));
+            L.off_cells = slot; slot += align_up(rows * H * sizeof(float));
+            L.off_hs = slot; slot += align_up(rows * H * es);
+            L.off_pd = slot; slot += align_up(rows * G * es);
+            L.off_dcn = slot; slot += align_up((size_t)N * H * sizeof(float));
+            L.aux_bytes = slot - L.aux_off;
+            size_t w = 0, v;
+            const ConvShape cx{N, T, 1, In, T, 1, G, 1, 1, 1, 0}, ch{N, T, 1, H, T, 1, G, 1, 1, 1, 0};
+            if (st->dt == DT_BF16) {
+                // the widest request among the whole-sequence products and one step of either recurrence
+                v = conv_gather_mfma_workspace(rows_geom(N, T, In, G)); w = v > w ? v : w;
+                v = conv_gather_mfma_workspace(rows_geom(N, T, G, In)); w = v > w ? v : w;
+                v = conv_gather_mfma_raw_workspace(step_geom(N, T, H, G, 1)); w = v > w ? v : w;
+                v = conv_gather_mfma_raw_workspace(step_geom(N, T, G, H, 1)); w = v > w ? v : w;
+                v = conv_wgrad_mfma_workspace(cx); w = v > w ? v : w;
+                v = conv_wgrad_mfma_workspace(ch); w = v > w ? v : w;
+            } else {
+                w = (size_t)N * G * sizeof(float);
+                v = conv_wgrad_direct_workspace(cx); w = v > w ? v : w;
+                v = conv_wgrad_direct_workspace(ch); w = v > w ? v : w;
+                v = colsum_workspace(N * T, G); w = v > w ? v : w;
+            }
+            work = w > work ? w : work;
+        }
         if (L.d.kind == BAPIPE_CONV2D || L.d.kind == BAPIPE_LINEAR) {
             ConvShape cs = conv_shape(st, L);
             if (L.d.kind == BAPIPE_LINEAR && n_micro > 1 && use_mfma_wgrad(st, cs)) {
@@ -835,7 +1038,7 @@ int bapipe_stage_create(const bapipe_layer_desc_t *layers, int n_layers, int mic
     st->accum_bytes = pb - st->accum_off;
     for (int i = 0; i < n_layers; ++i) {
         const Layer &L = st->layers[i];
-        bool mat = L.d.kind == BAPIPE_CONV2D || L.d.kind == BAPIPE_LINEAR;
+        bool mat = has_matrix(L.d.kind);
         o_ww[i] = pb; pb += mat ? align_up(L.w_elems * es) : 0;
         o_wt[i] = pb; pb += mat ? align_up(L.w_elems * es) : 0;
     }
@@ -986,10 +1189,7 @@ int bapipe_stage_step(bapipe_stage_t *st, float lr)
         const bool mat = L.d.kind != BAPIPE_BATCHNORM2D;
         HIPCHK(sgd_step(st->dt, L.w, L.dw, lr, mat ? L.w_work : nullptr, L.w_elems, st->stream));
         if (L.b_elems) HIPCHK(sgd_step(st->dt, L.bias, L.db, lr, nullptr, L.b_elems, st->stream));
-        if (mat) {
-            int R = L.d.kind == BAPIPE_LINEAR ? 1 : L.d.kh, S = L.d.kind == BAPIPE_LINEAR ? 1 : L.d.kw;
-            HIPCHK(make_dgrad_filter(st->dt, L.w, L.w_t, L.d.cout, R, S, L.cin_p, st->stream));
-        }
+        if (mat) HIPCHK(refresh_transposed(st, L));
     }
     st->n_fwd = st->n_bwd = 0;
     st->flushed = 0;

@@ -197,3 +197,9 @@ def test_resnet50_stem_full_shapes():
 def test_resnet50_tail_full_shapes():
     _end_to_end_report(C.resnet50_tail(n_micro=1), gate_forward=False)
     _layerwise(C.resnet50_tail(n_micro=1), "resnet50 tail layerwise")
+
+
+@pytest.mark.timeout(900)
+def test_gnmt_lstm_stage_full_shapes():
+    _end_to_end_report(C.gnmt_lstm_stage(n_micro=1), gate_forward=True)
+    _layerwise(C.gnmt_lstm_stage(n_micro=1), "gnmt lstm layerwise")

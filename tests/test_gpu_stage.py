@@ -140,6 +140,24 @@ def test_stem_conv_7x7_stride_2(dtype, hw, cout, mb):
     compare_minibatch(st, verbose="7x7 s2 conv %s" % (hw,))
 
 
+@pytest.mark.parametrize("cin,hidden,T,mb,dtype", [
+    (5, 7, 6, 3, C.FP32), (8, 8, 1, 2, C.FP32), (16, 24, 9, 4, C.FP32),
+    (8, 16, 5, 3, C.BF16), (24, 40, 9, 4, C.BF16), (16, 16, 1, 5, C.BF16),
+    (64, 64, 12, 70, C.BF16),                       # more sequences than one 64-row tile
+])
+@pytest.mark.parametrize("need_dx", [1, 0])
+def test_lstm_layer(cin, hidden, T, mb, dtype, need_dx):
+    st = single(lambda b: b.lstm(cin, hidden, src=-1), cin, (T, 1), dtype, micro_batch=mb, need_input_grad=need_dx)
+    compare_minibatch(st, verbose="lstm %d->%d T=%d N=%d" % (cin, hidden, T, mb))
+
+
+@pytest.mark.parametrize("dtype", DT)
+@pytest.mark.parametrize("layout", [B.NCHW, B.NHWC])
+def test_lstm_stage_with_residual_connections(dtype, layout):
+    st = C.gnmt_lstm_stage(hidden=16, seq=7, n_layers=2, micro_batch=3, n_micro=3, dtype=dtype)
+    compare_minibatch(st, layout=layout, verbose="gnmt-like stage layout %d" % layout)
+
+
 @pytest.mark.parametrize("dtype", DT)
 def test_remaining_stages_small(dtype):
     """Shrunken copies of the VGG-16 conv3 block, the ResNet-50 head and the ResNet-50 end."""
