@@ -175,10 +175,20 @@ def main():
     flop = C.flops_per_minibatch(stage)
     tflops = flop / (ms_per_step * 1e-3) / 1e12
 
+    other = None
     if tap in ("gather", "wgrad", "direct"):
         ach = r["flop"] / (r["total_ms"] * 1e-3) / 1e12 if r["total_ms"] > 0 else 0.0
         bound, unit = ("alu", "TFLOP/s") if tap == "direct" else ("mfma", "TFLOP/s")
         peak = PEAK_FP32_VALU_TFLOPS if tap == "direct" else PEAK_BF16_TFLOPS
+        # a contraction with little reuse (weight streaming of the linear layers, one-step recurrent products)
+        # sits on the HBM roof instead: report the roof the launches are closer to, keep the other beside it
+        gbs = r["bytes"] / (r["total_ms"] * 1e-3) / 1e9 if r["total_ms"] > 0 else 0.0
+        if tap != "direct" and gbs / PEAK_HBM_GBS > ach / peak:
+            other = dict(bound=bound, achieved=round(ach, 2), peak=peak, unit=unit, frac=round(ach / peak, 4))
+            ach, bound, unit, peak = gbs, "hbm", "GB/s", PEAK_HBM_GBS
+        else:
+            other = dict(bound="hbm", achieved=round(gbs, 2), peak=PEAK_HBM_GBS, unit="GB/s",
+                         frac=round(gbs / PEAK_HBM_GBS, 4))
     else:
         ach = r["bytes"] / (r["total_ms"] * 1e-3) / 1e9 if r["total_ms"] > 0 else 0.0
         bound, unit, peak = "hbm", "GB/s", PEAK_HBM_GBS
@@ -193,6 +203,8 @@ def main():
                 launches=int(r["launches"]),
                 avg_launch_ms=round(r["total_ms"] / max(1, r["launches"]), 5),
                 share_of_step=round(r["total_ms"] / ms, 4))
+    if other is not None:
+        roof["other_roof"] = other
 
     out = {
         "metric": "stage fwd+bwd samples/s (1F1B mini-batch incl. weight update)",

@@ -1053,6 +1053,23 @@ __global__ void k_repad(const T *__restrict__ src, T *__restrict__ dst, size_t r
     dst[i] = c < Cs ? src[r * Cs + c] : from_f32<T>(0.0f);
 }
 
+// the common case (RGB input padded to 8 bf16 channels): one thread builds one 16-byte pixel
+template <int CS>
+__global__ void k_repad_to8(const uint16_t *__restrict__ src, uint4 *__restrict__ dst, size_t rows)
+{
+    size_t r = (size_t)blockIdx.x * TPB + threadIdx.x;
+    if (r >= rows) return;
+    uint16_t v[8];
+#pragma unroll
+    for (int c = 0; c < 8; ++c) v[c] = c < CS ? src[r * CS + c] : (uint16_t)0;
+    uint4 o;
+    o.x = v[0] | ((uint32_t)v[1] << 16);
+    o.y = v[2] | ((uint32_t)v[3] << 16);
+    o.z = v[4] | ((uint32_t)v[5] << 16);
+    o.w = v[6] | ((uint32_t)v[7] << 16);
+    dst[r] = o;
+}
+
 #define DISPATCH_T(dt, ...)                        \
     do {                                           \
         if ((dt) == DT_F32) {                      \
@@ -1456,6 +1473,15 @@ hipError_t nhwc_repad(int dt, const void *src, void *dst, size_t rows, int Cs, i
 {
     size_t n = rows * Cd;
     if (n == 0) return hipSuccess;
+    if (dt == DT_BF16 && Cd == 8 && aligned16(dst) && (Cs == 3 || Cs == 1 || Cs == 4)) {
+#define REPAD8(CS_) \
+    hipLaunchKernelGGL((k_repad_to8<CS_>), dim3(blocks_for(rows)), dim3(TPB), 0, s, (const uint16_t *)src, (uint4 *)dst, rows)
+        if (Cs == 3) REPAD8(3);
+        else if (Cs == 1) REPAD8(1);
+        else REPAD8(4);
+#undef REPAD8
+        return hipGetLastError();
+    }
     DISPATCH_T(dt, {
         hipLaunchKernelGGL((k_repad<T>), dim3(blocks_for(n)), dim3(TPB), 0, s, (const T *)src, (T *)dst, rows, Cs, Cd);
     });

@@ -379,7 +379,9 @@ int lstm_forward(bapipe_stage *st, Layer &L, const void *x, void *h, int mbid)
         }
         HIPCHK(lstm_cell_fwd(st->dt, P, (const float *)st->work, S, gates, cells, h, hs, N, T, H, t, s));
     }
-    st->tap_end(tp, 2.0 * N * T * (double)G * (L.d.cin + H), 0.0);
+    // x and W_x once, W_h once per step, P written and read, h written
+    st->tap_end(tp, 2.0 * N * T * (double)G * (L.d.cin + H),
+                dt_size(st->dt) * ((double)N * T * (In + 2.0 * G + H) + (double)G * In + (double)(T - 1) * G * H));
     return BAPIPE_OK;
 }
 
@@ -415,7 +417,8 @@ int lstm_backward(bapipe_stage *st, Layer &L, const void *x, const void *dy, voi
             HIPCHK(conv_gather_direct(st->dt, D, wt_x, nullptr, dx, 0, e, gd, s));
         flop += 2.0 * N * T * (double)G * L.d.cin;
     }
-    st->tap_end(tp, flop, 0.0);
+    st->tap_end(tp, flop, dt_size(st->dt) * ((double)N * T * (H + 2.0 * G + (dx ? In : 0)) + (double)G * In +
+                                             (double)(T - 1) * G * H));
     // dW_x += D^T x (the bias gradient rides along), dW_h += D^T (delayed h)
     ConvShape cx{N, T, 1, In, T, 1, G, 1, 1, 1, 0}, ch{N, T, 1, H, T, 1, G, 1, 1, 1, 0};
     float *dw_h = L.dw + (size_t)G * In;
@@ -428,7 +431,8 @@ int lstm_backward(bapipe_stage *st, Layer &L, const void *x, const void *dy, voi
         HIPCHK(conv_wgrad_direct(st->dt, hs, D, dw_h, st->work, ch, s));
         if (L.db) HIPCHK(colsum_accumulate(st->dt, D, N * T, G, L.db, st->work, s));
     }
-    st->tap_end(tp, 2.0 * N * T * (double)G * (L.d.cin + H), 0.0);
+    st->tap_end(tp, 2.0 * N * T * (double)G * (L.d.cin + H),
+                dt_size(st->dt) * (double)N * T * (In + H + 2.0 * G) + 8.0 * L.w_elems);
     return BAPIPE_OK;
 }
 
@@ -469,7 +473,12 @@ int layer_forward(bapipe_stage *st, int li, const FwdCtx &c)
             HIPCHK(conv_gather_mfma(a, L.w_work, L.bias, o, L.d.fuse_relu, none, g, st->work, s));
         else
             HIPCHK(conv_gather_direct(dt, a, L.w_work, L.bias, o, L.d.fuse_relu, none, g, s));
-        st->tap_end(tp, conv_flop(g, L.d.cin), 0.0);
+        // algorithmic bytes: input and filter read once, output (or pooled output + indices) written once
+        const double wbytes = (double)L.w_elems * dt_size(dt);
+        const double obytes = L.fuse_pool >= 0 ? (double)st->tensors[st->layers[L.fuse_pool].o].bytes() +
+                                                     (double)st->tensors[st->layers[L.fuse_pool].o].elems
+                                               : (double)O.bytes();
+        st->tap_end(tp, conv_flop(g, L.d.cin), (double)st->tensors[L.a].bytes() + wbytes + obytes);
         break;
     }
     case BAPIPE_RELU: {
@@ -581,7 +590,7 @@ int layer_backward(bapipe_stage *st, int li, BwdCtx &c)
                 HIPCHK(conv_wgrad_mfma(x, g, L.dw, L.db, st->work, cs, s));      // bias gradient rides along
             else
                 HIPCHK(conv_wgrad_direct(dt, x, g, L.dw, st->work, cs, s));
-            st->tap_end(tp, flop, 0.0);
+            st->tap_end(tp, flop, (double)A.bytes() + O.bytes() + 8.0 * L.w_elems);   // x, dy read; fp32 dw read and written
             bias_done = mf;
         }
         if (L.db && !bias_done) {
@@ -599,7 +608,9 @@ int layer_backward(bapipe_stage *st, int li, BwdCtx &c)
                 HIPCHK(conv_gather_mfma(g, L.w_t, nullptr, dx, 0, e, dg, st->work, s));
             else
                 HIPCHK(conv_gather_direct(dt, g, L.w_t, nullptr, dx, 0, e, dg, s));
-            st->tap_end(tp, flop, 0.0);
+            // dy and filter read, dx written, plus the gate and the previous dx where the epilogue uses them
+            st->tap_end(tp, flop, (double)O.bytes() + (double)L.w_elems * dt_size(dt) +
+                                      (double)A.bytes() * (1.0 + (e.gate ? 1.0 : 0.0) + (e.accum ? 1.0 : 0.0)));
         }
         break;
     }
@@ -698,7 +709,7 @@ int flush_deferred(bapipe_stage *st)
         const char *g = L.def_g + (size_t)st->flushed * L.def_g_bytes;
         const bool tp = st->tap_begin(BAPIPE_KC_CONV_WGRAD_MFMA);
         HIPCHK(conv_wgrad_mfma(x, g, L.dw, nullptr, st->work, cs, st->stream));
-        st->tap_end(tp, conv_flop(fwd_geom(st, L), L.d.cin) * n, 0.0);
+        st->tap_end(tp, conv_flop(fwd_geom(st, L), L.d.cin) * n, (double)n * (L.def_x_bytes + L.def_g_bytes) + 8.0 * L.w_elems);
     }
     st->flushed = st->n_bwd;
     return BAPIPE_OK;
