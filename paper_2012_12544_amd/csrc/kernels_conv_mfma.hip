@@ -423,6 +423,10 @@ GatherPlan gather_plan(const GatherConv &g)
     // the bottleneck blocks): halve the pixel tile rather than split K, whose fp32 partials cost more
     // than the smaller tile loses (measured on 512-channel 14x14 layers: 73 us against 100 us)
     if (p.bp == 256 && p.bc == 128 && tiles_of(256) < 400) p.bp = 128;
+    // small products (the bottleneck blocks of ResNet: under ~8 GMAC) are bound by the latency of a block's
+    // load - multiply - store chain, not by throughput: many 64-pixel blocks and no split of K were the
+    // fastest choice on every such shape measured (e.g. 1x1 1024->256 at 14x14: 11.5 us against 22.2)
+    if (p.bc == 128 && npix > 64 && (double)npix * g.Co * g.R * g.S * g.Ci < 8e9) p.bp = 64;
     // plenty of 256-pixel tiles and whole 256-channel tiles: one 8-wave block per CU owns 256 x 256, which
     // halves the L2 -> LDS traffic of two independent 256 x 128 blocks (3 % on the 512-channel 28x28 layers)
     if (p.bp == 256 && p.bc == 128 && g.Co % 256 == 0) p.bc = 256;
@@ -778,6 +782,9 @@ WgradPlan wgrad_plan(const ConvShape &c)
     p.bko = c.K > 128 ? 256 : (c.K > 64 ? 128 : 64);
     p.bci = Ntot > 64 ? 128 : 64;
     if (p.bko == 256 && p.bci == 64) p.bko = 128;
+    // small products (under ~8 GMAC, the bottleneck blocks of ResNet) are latency-bound: more, smaller
+    // tiles measured 10-25 % faster than 256-wide ones on every such shape
+    if (p.bko == 256 && (double)c.N * c.P * c.Q * c.K * Ntot < 8e9) p.bko = 128;
     p.tiles_ko = (c.K + p.bko - 1) / p.bko;
     p.tiles_n = (Ntot + p.bci - 1) / p.bci;
     long long npix = (long long)c.N * c.P * c.Q;
