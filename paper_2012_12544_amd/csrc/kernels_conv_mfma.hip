@@ -46,7 +46,8 @@ template <int BP, int BC, int WP, int WC, int BK, int STAGES, bool S1, bool TAPS
 __global__ __launch_bounds__(WP *WC * 64, WP *WC >= 8 ? 1 : 2) void k_gather_mfma(
     const bf16_t *__restrict__ in, const bf16_t *__restrict__ wt, const float *__restrict__ bias,
     bf16_t *out, const bf16_t *__restrict__ gate, int accum, int relu, int is_grad, GatherConv g,
-    int tiles_c, unsigned in_bytes, unsigned wt_bytes, float *__restrict__ part, int kt_per_split)
+    int tiles_c, unsigned in_bytes, unsigned wt_bytes, float *__restrict__ part, int kt_per_split,
+    float *__restrict__ stat_part)
 {
     constexpr int NT = WP * WC * 64, NW = WP * WC;
     constexpr int CPR = BK / 8;              // 16-byte chunks per tile row
@@ -349,6 +350,26 @@ __global__ __launch_bounds__(WP *WC * 64, WP *WC >= 8 ? 1 : 2) void k_gather_mfm
         }
     }
     __syncthreads();
+    // Per-channel sum and sum of squares of the STORED (rounded) values of this pixel tile, for a batch-norm
+    // that follows: stat_part[q][pixel tile][channel], q = 0 sum, 1 squares - the layout the final pass of the
+    // column reductions reads.  One thread per channel walks down the staged tile.
+    if (stat_part) {
+        for (int cc = tid; cc < BC; cc += NT) {
+            const int co = co0 + cc;
+            if (co < g.Co) {
+                const int rows = npix - pix0 < BP ? npix - pix0 : BP;
+                float s1 = 0.0f, s2 = 0.0f;
+                for (int r = 0; r < rows; ++r) {
+                    const float v = __uint_as_float((uint32_t)sO[r * SROW + cc] << 16);
+                    s1 += v;
+                    s2 += v * v;
+                }
+                const int tiles_p = (int)gridDim.x / tiles_c;
+                stat_part[(size_t)tile_p * g.Co + co] = s1;
+                stat_part[((size_t)tiles_p + tile_p) * g.Co + co] = s2;
+            }
+        }
+    }
     constexpr int CH8 = BC / 8;                 // 16-byte units per pixel row
     constexpr int UNITS = BP * CH8 / NT;        // per thread
 #pragma unroll
@@ -445,7 +466,8 @@ GatherPlan gather_plan(const GatherConv &g)
 
 template <int BP, int BC, int WP, int WC, int BK, int STAGES>
 hipError_t launch_gather(const void *in, const void *wt, const float *bias, void *out, int relu, GradEpi epi,
-                         const GatherConv &g, const GatherPlan &plan, void *workspace, hipStream_t s, bool raw = false)
+                         const GatherConv &g, const GatherPlan &plan, void *workspace, hipStream_t s, bool raw = false,
+                         float *stat_part = nullptr)
 {
     constexpr int NT = WP * WC * 64;
     constexpr size_t main_bytes = (size_t)STAGES * (BP + BC) * BK * 2;
@@ -470,7 +492,7 @@ hipError_t launch_gather(const void *in, const void *wt, const float *bias, void
         }                                                                                                         \
         hipLaunchKernelGGL(kfn, grid, dim3(NT), smem, s, (const bf16_t *)in, (const bf16_t *)wt, bias,          \
                            (bf16_t *)out, (const bf16_t *)epi.gate, epi.accum, relu, is_grad, g, tiles_c, in_bytes, \
-                           wt_bytes, part, plan.kt_per_split);                                                    \
+                           wt_bytes, part, plan.kt_per_split, stat_part);                                         \
     } while (0)
     const bool taps_inner = g.Ci % BK == 0 && g.R * g.S <= 32;      // the stride-1 variant keeps a 32-bit tap mask
     if (g.s_in == 1) {
@@ -833,19 +855,28 @@ size_t conv_gather_mfma_workspace(const GatherConv &g)
     return p.splits > 1 ? (size_t)p.splits * g.N * g.Ho * g.Wo * g.Co * sizeof(float) : 0;
 }
 
+int conv_gather_mfma_stat_chunks(const GatherConv &g)
+{
+    if (!conv_gather_mfma_supported(g) || conv3x3_halo_supported(g) || conv3x3_c8_supported(g)) return 0;
+    const GatherPlan p = gather_plan(g);
+    if (p.splits != 1) return 0;
+    return (int)(((long long)g.N * g.Ho * g.Wo + p.bp - 1) / p.bp);
+}
+
 hipError_t conv_gather_mfma(const void *in, const void *wt, const float *bias, void *out, int relu,
-                            GradEpi epi, const GatherConv &g, void *workspace, hipStream_t s)
+                            GradEpi epi, const GatherConv &g, void *workspace, hipStream_t s, float *stat_part)
 {
     if (!conv_gather_mfma_supported(g)) return hipErrorInvalidValue;
+    if (stat_part && conv_gather_mfma_stat_chunks(g) == 0) return hipErrorInvalidValue;
     if ((long long)g.N * g.Ho * g.Wo == 0) return hipSuccess;
     if (conv3x3_halo_supported(g)) return conv3x3_halo_mfma(in, wt, bias, out, relu, epi, g, s);
     if (!epi.gate && !epi.accum && conv3x3_c8_supported(g)) return conv3x3_c8_mfma(in, wt, bias, out, relu, g, s);
     const GatherPlan p = gather_plan(g);
-    if (p.bp == 64) return launch_gather<64, 128, 1, 4, 32, 3>(in, wt, bias, out, relu, epi, g, p, workspace, s);
-    if (p.bc == 64) return launch_gather<256, 64, 4, 1, 32, 3>(in, wt, bias, out, relu, epi, g, p, workspace, s);
-    if (p.bc == 256) return launch_gather<256, 256, 2, 4, 32, 3>(in, wt, bias, out, relu, epi, g, p, workspace, s);
-    if (p.bp == 128) return launch_gather<128, 128, 2, 2, 32, 3>(in, wt, bias, out, relu, epi, g, p, workspace, s);
-    return launch_gather<256, 128, 2, 2, 32, 3>(in, wt, bias, out, relu, epi, g, p, workspace, s);
+    if (p.bp == 64) return launch_gather<64, 128, 1, 4, 32, 3>(in, wt, bias, out, relu, epi, g, p, workspace, s, false, stat_part);
+    if (p.bc == 64) return launch_gather<256, 64, 4, 1, 32, 3>(in, wt, bias, out, relu, epi, g, p, workspace, s, false, stat_part);
+    if (p.bc == 256) return launch_gather<256, 256, 2, 4, 32, 3>(in, wt, bias, out, relu, epi, g, p, workspace, s, false, stat_part);
+    if (p.bp == 128) return launch_gather<128, 128, 2, 2, 32, 3>(in, wt, bias, out, relu, epi, g, p, workspace, s, false, stat_part);
+    return launch_gather<256, 128, 2, 2, 32, 3>(in, wt, bias, out, relu, epi, g, p, workspace, s, false, stat_part);
 }
 
 size_t conv_gather_mfma_raw_workspace(const GatherConv &g)

@@ -1314,11 +1314,21 @@ constexpr int OP_V = 4;
                        1.0f / (float)rows, rows, C)
 
 hipError_t bn_fwd(int dt, const void *x, const float *gamma, const float *beta, float eps, void *y,
-                  float *stats, int relu, int rows, int C, void *workspace, hipStream_t s)
+                  float *stats, int relu, int rows, int C, void *workspace, hipStream_t s, int pre_chunks)
 {
     if (rows <= 0 || C <= 0) return hipSuccess;
     int Vsel = col_vec(dt, C, x, y);
     float *part = (float *)workspace;
+    if (pre_chunks > 0) {                 // statistics partials came with x: final pass and normalisation only
+        hipLaunchKernelGGL(k_bn_stat_final, dim3(final_blocks(C)), dim3(TPB), 0, s, part, pre_chunks, C, rows, eps, stats);
+        DISPATCH_TV(dt, Vsel > 1, {
+            ColPlan p = col_plan(rows, C, V);
+            const int rpb = p.RY * BN_ROWS_PER_THREAD;
+            hipLaunchKernelGGL((k_bn_apply<T, V>), dim3(p.gx, (rows + rpb - 1) / rpb), dim3(TPB), 0, s, (const T *)x,
+                               gamma, beta, stats, (T *)y, relu, rows, C, p);
+        });
+        return hipGetLastError();
+    }
     if (bn_onepass(Vsel, rows, C)) {
         if (dt == DT_F32) BN_FWD_OP(float, OP_R);
         else BN_FWD_OP(bf16_t, OP_R);

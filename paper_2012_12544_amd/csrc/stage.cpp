@@ -65,6 +65,10 @@ struct Layer {
     // the conv output is never stored (fuse_pool = index of that pool layer; fused marks the pool)
     int fuse_pool = -1;
     bool fused = false;
+    // conv directly followed by the batch-norm that is its only reader: the conv kernel leaves the per-tile
+    // statistics partials in the workspace (stat_chunks of them) and the batch-norm skips its first pass
+    int stat_chunks = 0;
+    bool stats_given = false;
     // LSTM: per in-flight micro-batch the slot keeps the gates and cell states (float), the delayed
     // copy of h that the recurrent products read, the buffer shared by the input projection
     // (forward) and the pre-activation gradients (backward) and the cell-gradient carry
@@ -441,6 +445,7 @@ int lstm_backward(bapipe_stage *st, Layer &L, const void *x, const void *dy, voi
 struct FwdCtx {
     int mbid;
     const void *x_direct;
+    bool profiling = false;      // layers are timed one at a time: nothing may rely on what the previous layer left behind
 };
 
 const void *in_ptr(bapipe_stage *st, int t, const FwdCtx &c)
@@ -470,7 +475,8 @@ int layer_forward(bapipe_stage *st, int li, const FwdCtx &c)
             HIPCHK(conv3x3_halo_pool_mfma(a, L.w_work, L.bias, L.d.fuse_relu, st->tptr(P.o, c.mbid),
                                           (uint8_t *)(st->slot(c.mbid) + P.aux_off), g, s));
         } else if (mf)
-            HIPCHK(conv_gather_mfma(a, L.w_work, L.bias, o, L.d.fuse_relu, none, g, st->work, s));
+            HIPCHK(conv_gather_mfma(a, L.w_work, L.bias, o, L.d.fuse_relu, none, g, st->work, s,
+                                    (L.stat_chunks && !c.profiling) ? (float *)st->work : nullptr));
         else
             HIPCHK(conv_gather_direct(dt, a, L.w_work, L.bias, o, L.d.fuse_relu, none, g, s));
         // algorithmic bytes: input and filter read once, output (or pooled output + indices) written once
@@ -506,8 +512,11 @@ int layer_forward(bapipe_stage *st, int li, const FwdCtx &c)
     case BAPIPE_BATCHNORM2D: {
         const Tensor &A = st->tensors[L.a];
         const bool tp = st->tap_begin(BAPIPE_KC_BATCHNORM);
+        // the partials of the producing conv are only there when that conv has just run (not when the
+        // profiler times this layer alone)
+        const int pre = (L.stats_given && !c.profiling) ? st->layers[li - 1].stat_chunks : 0;
         HIPCHK(bn_fwd(dt, a, L.w, L.bias, L.d.eps, o, (float *)(st->slot(c.mbid) + L.aux_off), L.d.fuse_relu,
-                      st->mb * A.H * A.W, A.C, st->work, s));
+                      st->mb * A.H * A.W, A.C, st->work, s, pre));
         st->tap_end(tp, 0.0, 3.0 * A.bytes());                                   // read x twice, write y
         break;
     }
@@ -1014,6 +1023,23 @@ int bapipe_stage_create(const bapipe_layer_desc_t *layers, int n_layers, int mic
             }
             work = w > work ? w : work;
         }
+        if (L.d.kind == BAPIPE_CONV2D && st->dt == DT_BF16 && i + 1 < n_layers && L.o != last_t && L.fuse_pool < 0) {
+            Layer &B = st->layers[i + 1];
+            const Tensor &O = st->tensors[L.o];
+            const GatherConv g = fwd_geom(st, L);
+            const int rows = micro_batch * O.H * O.W;
+            // the one-launch batch-norm of tiny tensors reads x once anyway
+            if (B.d.kind == BAPIPE_BATCHNORM2D && B.a == L.o && O.consumers.size() == 1 && !L.d.fuse_relu &&
+                rows > 2048 && use_mfma_gather(st, g)) {
+                const int chunks = conv_gather_mfma_stat_chunks(g);
+                if (chunks > 0) {
+                    L.stat_chunks = chunks;
+                    B.stats_given = true;
+                    const size_t w = (size_t)2 * chunks * O.C * sizeof(float) + 4 * (size_t)O.C * sizeof(float);
+                    work = w > work ? w : work;
+                }
+            }
+        }
         if (L.d.kind == BAPIPE_CONV2D || L.d.kind == BAPIPE_LINEAR) {
             ConvShape cs = conv_shape(st, L);
             if (L.d.kind == BAPIPE_LINEAR && n_micro > 1 && use_mfma_wgrad(st, cs)) {
@@ -1361,7 +1387,7 @@ int bapipe_profile_layers(bapipe_stage_t *st, int warmup, int iters, bapipe_laye
     HIPCHK(hipEventCreate(&e0));
     HIPCHK(hipEventCreate(&e1));
     int rc = BAPIPE_OK;
-    FwdCtx fc{0, nullptr};
+    FwdCtx fc{0, nullptr, true};
     std::vector<int32_t> zero_labels(st->mb, 0);
     int32_t *labels_dev = (int32_t *)st->work;   // xent reads labels only; no kernel of that layer uses the workspace
     for (int i = 0; i < nl && rc == BAPIPE_OK; ++i) {

@@ -194,7 +194,10 @@ def test_pool_odd_size_and_vector_tail(dtype):
 @pytest.mark.parametrize("c,hw,mb", [(16, (6, 5), 5), (6, (7, 3), 5), (256, (4, 4), 5),
                                      # one-launch kernels (>= 128 channels, <= 2048 rows): one and two rows per
                                      # thread with a ragged tail, exactly at the row limit, just above it
-                                     (128, (9, 7), 5), (136, (25, 11), 6), (256, (16, 16), 8), (128, (41, 10), 5)])
+                                     (128, (9, 7), 5), (136, (25, 11), 6), (256, (16, 16), 8), (128, (41, 10), 5),
+                                     # above 2048 rows the producing conv hands over the statistics partials of its
+                                     # pixel tiles (ragged last tile; more channels than one tile)
+                                     (32, (40, 30), 2), (128, (33, 32), 8), (200, (29, 31), 3)])
 def test_batchnorm_layer(dtype, c, hw, mb):
     # In bf16 a stored value one ulp apart on the two sides can flip a ReLU gate, and one flipped gate moves
     # dx by more than the bound: with hundreds of thousands of gated elements that is no longer rare, so the
