@@ -43,6 +43,8 @@ struct Tensor {
     bool gated = false;    // producer applies a fused ReLU (or is a ReLU layer)
     size_t off = 0;        // byte offset in the stash slot or in the transient arena
     size_t goff = 0;       // byte offset in the gradient arena
+    int galias = -1;       // tensor whose gradient IS this tensor's gradient (an un-gated input of an ADD that
+                           // nobody else reads: the sum's gradient passes through unchanged, no copy is made)
     std::vector<int> consumers;
     size_t bytes() const { return elems * esize; }
 };
@@ -556,6 +558,7 @@ struct BwdCtx {
 void *grad_ptr(bapipe_stage *st, int t, BwdCtx &c)
 {
     int r = st->tensors[t].root;
+    if (st->tensors[r].galias >= 0) return grad_ptr(st, st->tensors[r].galias, c);
     if (r == 0 && c.dx_direct) return c.dx_direct;
     if (r == st->tensors[(int)st->tensors.size() - 1].root && c.dy_direct) return const_cast<void *>(c.dy_direct);
     return st->gptr(t);
@@ -666,12 +669,17 @@ int layer_backward(bapipe_stage *st, int li, BwdCtx &c)
         const void *g = grad_ptr(st, L.o, c);
         const bool tp = st->tap_begin(BAPIPE_KC_ELEMENTWISE);
         double bytes = 0.0;
-        if (a_grad) {
+        if (a_grad && st->tensors[A.root].galias == L.o) {
+            c.written[A.root] = 1;
+        } else if (a_grad) {
             GradEpi e = epi_for(st, L.a, c);
             HIPCHK(grad_copy(dt, g, grad_ptr(st, L.a, c), e, O.elems, s));
             bytes += 2.0 * O.bytes();
         }
-        if (st->tensors[st->tensors[L.b].root].need_grad) {
+        const int rb = st->tensors[L.b].root;
+        if (st->tensors[rb].need_grad && st->tensors[rb].galias == L.o) {
+            c.written[rb] = 1;
+        } else if (st->tensors[rb].need_grad) {
             GradEpi e = epi_for(st, L.b, c);
             HIPCHK(grad_copy(dt, g, grad_ptr(st, L.b, c), e, O.elems, s));
             bytes += 2.0 * O.bytes();
@@ -927,6 +935,15 @@ int bapipe_stage_create(const bapipe_layer_desc_t *layers, int n_layers, int mic
         st->tensors[t].need_grad = ng;
     }
     auto root_of = [&](int t) { return st->tensors[t].root; };
+    // gradient aliasing at ADD layers
+    for (int i = 0; i < n_layers; ++i) {
+        const Layer &L = st->layers[i];
+        if (L.d.kind != BAPIPE_ADD) continue;
+        for (int src : {L.a, L.b}) {
+            Tensor &S = st->tensors[src];
+            if (src != 0 && S.root == src && !S.gated && S.need_grad && S.consumers.size() == 1) S.galias = L.o;
+        }
+    }
     for (int i = 0; i < n_layers; ++i) {
         const Layer &L = st->layers[i];
         Tensor &RA = st->tensors[root_of(L.a)];
