@@ -42,13 +42,15 @@ hipError_t conv_wgrad_direct(int dt, const void *x, const void *dy, float *dw, v
 // ---- bf16 MFMA implicit-GEMM convolution (kernels_conv_mfma.hip)
 bool conv_gather_mfma_supported(const GatherConv &g);
 size_t conv_gather_mfma_workspace(const GatherConv &g);      // split-K partials (0 if K is not split)
+// bn_x / bn_stats (optional, gradient epilogue, with stat_part): the output is the gradient of a batch-norm's
+// output; stat_part then receives the per-tile sums of dy and dy*xhat (xhat from bn_x and the saved mean, 1/std)
 // stat_part (optional): the kernel also leaves, per pixel tile, the per-channel sum and sum of squares of
 // the values it stores - [2][chunks][Co] floats with chunks = conv_gather_mfma_stat_chunks(g) - which is what
 // bn_fwd would otherwise compute in a pass of its own; only where that function returns a non-zero count
 int conv_gather_mfma_stat_chunks(const GatherConv &g);
 hipError_t conv_gather_mfma(const void *in, const void *wt, const float *bias, void *out, int relu,
                             GradEpi epi, const GatherConv &g, void *workspace, hipStream_t s,
-                            float *stat_part = nullptr);
+                            float *stat_part = nullptr, const void *bn_x = nullptr, const float *bn_stats = nullptr);
 // 3x3 / stride 1 / pad 1 with the input halo of a 16x16 output patch resident in LDS
 // (kernels_conv_halo.hip); conv_gather_mfma routes to it when it applies
 bool conv3x3_halo_supported(const GatherConv &g);
@@ -122,9 +124,10 @@ size_t bn_workspace(int rows, int C);
 // the kernel that produced x) and the first pass over x is skipped
 hipError_t bn_fwd(int dt, const void *x, const float *gamma, const float *beta, float eps, void *y,
                   float *stats, int relu, int rows, int C, void *workspace, hipStream_t s, int pre_chunks = 0);
+// pre_chunks > 0: the workspace already holds [2][pre_chunks][C] partial sums of dy and dy*xhat
 hipError_t bn_bwd(int dt, const void *x, const void *dy, const float *gamma, const float *stats,
                   void *dx, float *dgamma, float *dbeta, GradEpi epi, int rows, int C,
-                  void *workspace, hipStream_t s);
+                  void *workspace, hipStream_t s, int pre_chunks = 0);
 
 // p = softmax(z) rows of K classes (float out)
 hipError_t softmax_fwd(int dt, const void *z, float *p, int rows, int K, hipStream_t s);

@@ -47,7 +47,7 @@ __global__ __launch_bounds__(WP *WC * 64, WP *WC >= 8 ? 1 : 2) void k_gather_mfm
     const bf16_t *__restrict__ in, const bf16_t *__restrict__ wt, const float *__restrict__ bias,
     bf16_t *out, const bf16_t *__restrict__ gate, int accum, int relu, int is_grad, GatherConv g,
     int tiles_c, unsigned in_bytes, unsigned wt_bytes, float *__restrict__ part, int kt_per_split,
-    float *__restrict__ stat_part)
+    float *__restrict__ stat_part, const bf16_t *__restrict__ bn_x, const float *__restrict__ bn_stats)
 {
     constexpr int NT = WP * WC * 64, NW = WP * WC;
     constexpr int CPR = BK / 8;              // 16-byte chunks per tile row
@@ -353,7 +353,7 @@ __global__ __launch_bounds__(WP *WC * 64, WP *WC >= 8 ? 1 : 2) void k_gather_mfm
     // Per-channel sum and sum of squares of the STORED (rounded) values of this pixel tile, for a batch-norm
     // that follows: stat_part[q][pixel tile][channel], q = 0 sum, 1 squares - the layout the final pass of the
     // column reductions reads.  One thread per channel walks down the staged tile.
-    if (stat_part) {
+    if (stat_part && !bn_x) {
         for (int cc = tid; cc < BC; cc += NT) {
             const int co = co0 + cc;
             if (co < g.Co) {
@@ -372,6 +372,20 @@ __global__ __launch_bounds__(WP *WC * 64, WP *WC >= 8 ? 1 : 2) void k_gather_mfm
     }
     constexpr int CH8 = BC / 8;                 // 16-byte units per pixel row
     constexpr int UNITS = BP * CH8 / NT;        // per thread
+    static_assert(NT % CH8 == 0, "a thread keeps one channel group through the loop below");
+    // bn_x: the gradient written here is the output gradient of a batch-norm whose input is bn_x and whose
+    // (mean, 1/std) are bn_stats: the per-channel sums of dy and dy*xhat over this pixel tile are taken on
+    // the way out (what the first pass of the batch-norm's backward would compute from HBM)
+    float bs1[8], bs2[8], bmu[8], binv[8];
+    if (bn_x) {
+        const int co = co0 + (tid % CH8) * 8;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            bs1[j] = bs2[j] = 0.0f;
+            bmu[j] = co + j < g.Co ? bn_stats[co + j] : 0.0f;
+            binv[j] = co + j < g.Co ? bn_stats[g.Co + co + j] : 0.0f;
+        }
+    }
 #pragma unroll
     for (int it = 0; it < UNITS; ++it) {
         const int u = tid + it * NT;
@@ -390,8 +404,45 @@ __global__ __launch_bounds__(WP *WC * 64, WP *WC >= 8 ? 1 : 2) void k_gather_mfm
 #pragma unroll
                 for (int j = 0; j < 4; ++j) r[j] = grad_epilogue_pair(v[j], old[j], gt[j], accum != 0, gate != nullptr);
                 *reinterpret_cast<chunk16 *>(dst) = r;
+                if (bn_x) {
+                    const chunk16 xv = *reinterpret_cast<const chunk16 *>(bn_x + (size_t)p * g.Co + co);
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) {
+                        const float gj = __uint_as_float((j & 1) ? (r[j >> 1] & 0xFFFF0000u) : (r[j >> 1] << 16));
+                        const float xj = __uint_as_float((j & 1) ? (xv[j >> 1] & 0xFFFF0000u) : (xv[j >> 1] << 16));
+                        bs1[j] += gj;
+                        bs2[j] += gj * ((xj - bmu[j]) * binv[j]);
+                    }
+                }
             } else {
                 *reinterpret_cast<chunk16 *>(dst) = v;
+            }
+        }
+    }
+    if (bn_x) {
+        // combine the NT / CH8 threads that share a channel group through LDS (the staging tile is free now)
+        constexpr int RG = NT / CH8;
+        static_assert((size_t)RG * BC * 2 * sizeof(float) <= EPI_BYTES, "reduction buffer fits the staging tile");
+        float *red = reinterpret_cast<float *>(smem);                      // [RG][2][BC]
+        __syncthreads();
+        const int rg = tid / CH8, c8i = tid % CH8;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            red[(rg * 2 + 0) * BC + c8i * 8 + j] = bs1[j];
+            red[(rg * 2 + 1) * BC + c8i * 8 + j] = bs2[j];
+        }
+        __syncthreads();
+        for (int cc = tid; cc < BC; cc += NT) {
+            const int co = co0 + cc;
+            if (co < g.Co) {
+                float t1 = 0.0f, t2 = 0.0f;
+                for (int k = 0; k < RG; ++k) {
+                    t1 += red[(k * 2 + 0) * BC + cc];
+                    t2 += red[(k * 2 + 1) * BC + cc];
+                }
+                const int tiles_p = (int)gridDim.x / tiles_c;
+                stat_part[(size_t)tile_p * g.Co + co] = t1;
+                stat_part[((size_t)tiles_p + tile_p) * g.Co + co] = t2;
             }
         }
     }
@@ -467,7 +518,7 @@ GatherPlan gather_plan(const GatherConv &g)
 template <int BP, int BC, int WP, int WC, int BK, int STAGES>
 hipError_t launch_gather(const void *in, const void *wt, const float *bias, void *out, int relu, GradEpi epi,
                          const GatherConv &g, const GatherPlan &plan, void *workspace, hipStream_t s, bool raw = false,
-                         float *stat_part = nullptr)
+                         float *stat_part = nullptr, const void *bn_x = nullptr, const float *bn_stats = nullptr)
 {
     constexpr int NT = WP * WC * 64;
     constexpr size_t main_bytes = (size_t)STAGES * (BP + BC) * BK * 2;
@@ -492,7 +543,7 @@ hipError_t launch_gather(const void *in, const void *wt, const float *bias, void
         }                                                                                                         \
         hipLaunchKernelGGL(kfn, grid, dim3(NT), smem, s, (const bf16_t *)in, (const bf16_t *)wt, bias,          \
                            (bf16_t *)out, (const bf16_t *)epi.gate, epi.accum, relu, is_grad, g, tiles_c, in_bytes, \
-                           wt_bytes, part, plan.kt_per_split, stat_part);                                         \
+                           wt_bytes, part, plan.kt_per_split, stat_part, (const bf16_t *)bn_x, bn_stats);         \
     } while (0)
     const bool taps_inner = g.Ci % BK == 0 && g.R * g.S <= 32;      // the stride-1 variant keeps a 32-bit tap mask
     if (g.s_in == 1) {
@@ -864,19 +915,21 @@ int conv_gather_mfma_stat_chunks(const GatherConv &g)
 }
 
 hipError_t conv_gather_mfma(const void *in, const void *wt, const float *bias, void *out, int relu,
-                            GradEpi epi, const GatherConv &g, void *workspace, hipStream_t s, float *stat_part)
+                            GradEpi epi, const GatherConv &g, void *workspace, hipStream_t s, float *stat_part,
+                            const void *bn_x, const float *bn_stats)
 {
     if (!conv_gather_mfma_supported(g)) return hipErrorInvalidValue;
     if (stat_part && conv_gather_mfma_stat_chunks(g) == 0) return hipErrorInvalidValue;
+    if (bn_x && (!stat_part || !bn_stats || !(epi.gate || epi.accum))) return hipErrorInvalidValue;   // gradient epilogue only
     if ((long long)g.N * g.Ho * g.Wo == 0) return hipSuccess;
     if (conv3x3_halo_supported(g)) return conv3x3_halo_mfma(in, wt, bias, out, relu, epi, g, s);
     if (!epi.gate && !epi.accum && conv3x3_c8_supported(g)) return conv3x3_c8_mfma(in, wt, bias, out, relu, g, s);
     const GatherPlan p = gather_plan(g);
-    if (p.bp == 64) return launch_gather<64, 128, 1, 4, 32, 3>(in, wt, bias, out, relu, epi, g, p, workspace, s, false, stat_part);
-    if (p.bc == 64) return launch_gather<256, 64, 4, 1, 32, 3>(in, wt, bias, out, relu, epi, g, p, workspace, s, false, stat_part);
-    if (p.bc == 256) return launch_gather<256, 256, 2, 4, 32, 3>(in, wt, bias, out, relu, epi, g, p, workspace, s, false, stat_part);
-    if (p.bp == 128) return launch_gather<128, 128, 2, 2, 32, 3>(in, wt, bias, out, relu, epi, g, p, workspace, s, false, stat_part);
-    return launch_gather<256, 128, 2, 2, 32, 3>(in, wt, bias, out, relu, epi, g, p, workspace, s, false, stat_part);
+    if (p.bp == 64) return launch_gather<64, 128, 1, 4, 32, 3>(in, wt, bias, out, relu, epi, g, p, workspace, s, false, stat_part, bn_x, bn_stats);
+    if (p.bc == 64) return launch_gather<256, 64, 4, 1, 32, 3>(in, wt, bias, out, relu, epi, g, p, workspace, s, false, stat_part, bn_x, bn_stats);
+    if (p.bc == 256) return launch_gather<256, 256, 2, 4, 32, 3>(in, wt, bias, out, relu, epi, g, p, workspace, s, false, stat_part, bn_x, bn_stats);
+    if (p.bp == 128) return launch_gather<128, 128, 2, 2, 32, 3>(in, wt, bias, out, relu, epi, g, p, workspace, s, false, stat_part, bn_x, bn_stats);
+    return launch_gather<256, 128, 2, 2, 32, 3>(in, wt, bias, out, relu, epi, g, p, workspace, s, false, stat_part, bn_x, bn_stats);
 }
 
 size_t conv_gather_mfma_raw_workspace(const GatherConv &g)

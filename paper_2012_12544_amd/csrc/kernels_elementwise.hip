@@ -1349,12 +1349,26 @@ hipError_t bn_fwd(int dt, const void *x, const float *gamma, const float *beta, 
 
 hipError_t bn_bwd(int dt, const void *x, const void *dy, const float *gamma, const float *stats, void *dx,
                   float *dgamma, float *dbeta, GradEpi epi, int rows, int C, void *workspace,
-                  hipStream_t s)
+                  hipStream_t s, int pre_chunks)
 {
     if (rows <= 0 || C <= 0) return hipSuccess;
     int Vsel = col_vec(dt, C, x, dy, dx);
     if (!aligned16(epi.gate)) Vsel = 1;
     float *part = (float *)workspace;
+    if (pre_chunks > 0) {                 // the sums over dy came with dy: final pass and the dx pass only
+        float *sums = part + (size_t)2 * pre_chunks * C;
+        hipLaunchKernelGGL(k_bn_bwd_final, dim3(final_blocks(C)), dim3(TPB), 0, s, part, pre_chunks, C, sums, dgamma, dbeta);
+        if (dx) {
+            DISPATCH_TV(dt, Vsel > 1, {
+                ColPlan p = col_plan(rows, C, V);
+                const int rpb = p.RY * BN_ROWS_PER_THREAD;
+                hipLaunchKernelGGL((k_bn_bwd_apply<T, V>), dim3(p.gx, (rows + rpb - 1) / rpb), dim3(TPB), 0, s,
+                                   (const T *)x, (const T *)dy, gamma, stats, sums, (T *)dx, (const T *)epi.gate,
+                                   epi.accum, 1.0f / (float)rows, rows, C, p);
+            });
+        }
+        return hipGetLastError();
+    }
     if (bn_onepass(Vsel, rows, C)) {
         if (dt == DT_F32) BN_BWD_OP(float, OP_R);
         else BN_BWD_OP(bf16_t, OP_R);

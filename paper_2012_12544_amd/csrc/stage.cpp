@@ -16,6 +16,7 @@
 
 #include <cstdarg>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <string>
 #include <vector>
@@ -71,6 +72,10 @@ struct Layer {
     // statistics partials in the workspace (stat_chunks of them) and the batch-norm skips its first pass
     int stat_chunks = 0;
     bool stats_given = false;
+    // conv whose input is the output of the batch-norm right before it (its only reader): the conv's
+    // input-gradient kernel leaves the per-tile sums of dy and dy*xhat for that batch-norm's backward
+    int bnb_chunks = 0;
+    bool bwd_sums_given = false;
     // LSTM: per in-flight micro-batch the slot keeps the gates and cell states (float), the delayed
     // copy of h that the recurrent products read, the buffer shared by the input projection
     // (forward) and the pre-activation gradients (backward) and the cell-gradient carry
@@ -553,6 +558,7 @@ struct BwdCtx {
     const int32_t *labels;
     std::vector<char> written;
     bool profiling = false;        // profiler: run every kernel of the layer now (no deferral)
+    int bn_sums_ready = -1;        // batch-norm layer whose backward sums the last conv left in the workspace
 };
 
 void *grad_ptr(bapipe_stage *st, int t, BwdCtx &c)
@@ -616,7 +622,12 @@ int layer_backward(bapipe_stage *st, int li, BwdCtx &c)
             void *dx = grad_ptr(st, L.a, c);
             const bool mf = use_mfma_gather(st, dg);
             const bool tp = st->tap_begin(mf ? BAPIPE_KC_CONV_GATHER_MFMA : BAPIPE_KC_CONV_DIRECT);
-            if (mf)
+            if (mf && L.bnb_chunks && !c.profiling && (e.gate || e.accum)) {
+                const Layer &B = st->layers[li - 1];
+                HIPCHK(conv_gather_mfma(g, L.w_t, nullptr, dx, 0, e, dg, st->work, s, (float *)st->work,
+                                        st->tptr(B.a, c.mbid), (const float *)(st->slot(c.mbid) + B.aux_off)));
+                c.bn_sums_ready = li - 1;
+            } else if (mf)
                 HIPCHK(conv_gather_mfma(g, L.w_t, nullptr, dx, 0, e, dg, st->work, s));
             else
                 HIPCHK(conv_gather_direct(dt, g, L.w_t, nullptr, dx, 0, e, dg, s));
@@ -659,9 +670,10 @@ int layer_backward(bapipe_stage *st, int li, BwdCtx &c)
             dx = grad_ptr(st, L.a, c);
         }
         const bool tp = st->tap_begin(BAPIPE_KC_BATCHNORM);
+        const int pre = (L.bwd_sums_given && c.bn_sums_ready == li) ? st->layers[li + 1].bnb_chunks : 0;
         HIPCHK(bn_bwd(dt, st->tptr(L.a, c.mbid), grad_ptr(st, L.o, c), L.w,
                       (const float *)(st->slot(c.mbid) + L.aux_off), dx, L.dw, L.db, e, st->mb * A.H * A.W, A.C,
-                      st->work, s));
+                      st->work, s, pre));
         st->tap_end(tp, 0.0, 5.0 * A.bytes());                                   // x, dy twice each; dx once
         break;
     }
@@ -1053,6 +1065,22 @@ int bapipe_stage_create(const bapipe_layer_desc_t *layers, int n_layers, int mic
                     L.stat_chunks = chunks;
                     B.stats_given = true;
                     const size_t w = (size_t)2 * chunks * O.C * sizeof(float) + 4 * (size_t)O.C * sizeof(float);
+                    work = w > work ? w : work;
+                }
+            }
+        }
+        if (L.d.kind == BAPIPE_CONV2D && st->dt == DT_BF16 && i > 0 && L.a == i) {      // input = output of layer i-1
+            Layer &B = st->layers[i - 1];
+            const Tensor &X = st->tensors[L.a];
+            const GatherConv dg = dgrad_geom(st, L);
+            const int rows = micro_batch * X.H * X.W;
+            if (B.d.kind == BAPIPE_BATCHNORM2D && X.root == L.a && X.consumers.size() == 1 && X.need_grad &&
+                st->tensors[st->tensors[B.a].root].need_grad && rows > 2048 && use_mfma_gather(st, dg)) {
+                const int chunks = conv_gather_mfma_stat_chunks(dg);
+                if (chunks > 0) {
+                    L.bnb_chunks = chunks;
+                    B.bwd_sums_given = true;
+                    const size_t w = (size_t)2 * chunks * X.C * sizeof(float) + 4 * (size_t)X.C * sizeof(float);
                     work = w > work ? w : work;
                 }
             }

@@ -212,6 +212,19 @@ def test_batchnorm_layer(dtype, c, hw, mb):
 
 
 @pytest.mark.parametrize("dtype", DT)
+@pytest.mark.parametrize("c,c2,k,hw,mb", [(32, 24, 3, (40, 30), 2), (16, 136, 1, (25, 29), 3), (8, 8, 3, (6, 5), 2)])
+def test_conv_bn_relu_conv_chain(dtype, c, c2, k, hw, mb):
+    """A batch-norm between two convs: above 2048 rows (bf16) its forward statistics come out of the first conv's
+    epilogue and the sums of its backward out of the second conv's input-gradient epilogue."""
+    def build(b):
+        b.conv(c, c, 1, bias=0, src=-1)
+        b.bn(c, relu=1)
+        b.conv(c, c2, k, bias=0)
+    st = single(build, c, hw, dtype, micro_batch=mb)
+    compare_minibatch(st, verbose="conv-bn-conv c%d rows %d" % (c, mb * hw[0] * hw[1]))
+
+
+@pytest.mark.parametrize("dtype", DT)
 def test_residual_block(dtype):
     st = C.resnet50_stage(cin=16, mid3=8, mid4=8, hw=8, n3=2, n4=1, micro_batch=3, n_micro=2, dtype=dtype)
     compare_minibatch(st, verbose="residual blocks")
