@@ -73,6 +73,11 @@ bool wgrad3x3_halo_supported(const ConvShape &c);
 size_t wgrad3x3_halo_workspace(const ConvShape &c);
 hipError_t wgrad3x3_halo_mfma(const void *x, const void *dy, float *dw, float *db, void *workspace,
                               const ConvShape &c, hipStream_t s);
+// weight gradient of a 3x3 / stride 1 / pad 1 conv whose input has 8 channels in memory (the padded RGB stage input)
+bool wgrad3x3_c8_supported(const ConvShape &c);
+size_t wgrad3x3_c8_workspace(const ConvShape &c);
+hipError_t wgrad3x3_c8_mfma(const void *x, const void *dy, float *dw, float *db, void *workspace, const ConvShape &c,
+                            hipStream_t s);
 bool conv_wgrad_mfma_supported(const ConvShape &c);
 size_t conv_wgrad_mfma_workspace(const ConvShape &c);
 // dw += dy^T x over all pixels; db (may be null) += column sums of dy

@@ -696,6 +696,166 @@ __global__ void k_wg_halo_reduce(const float *__restrict__ part, float *dw, floa
     }
 }
 
+// ------------------------------------------------------------------------------------------
+// wgrad of the first layer: 8 (padded) input channels
+// ------------------------------------------------------------------------------------------
+// dw[ko][tap][c] for an input with 8 channels in memory: a 64 x 72 tile per block, next to no arithmetic,
+// so the kernel only has to stream dy once.  Units of 8x16 pixels as above (dy rows and the 10x18 halo
+// of x by buffer_load ... lds, two stages); the four waves split the unit's pixels (32 each) and every
+// wave keeps the whole 64 x 96 tile (72 columns used), the waves' tiles being added through LDS once
+// at the end.  dy fragments come from the transposing LDS read; an x fragment - 8 consecutive pixels
+// of one (tap, channel) column - is gathered with eight 2-byte reads from the plain [pixel][8] halo.
+constexpr int C8W_HALO_ELEMS = 192 * 8;                        // 180 halo pixels, three wave-loads
+constexpr int C8W_STAGE_ELEMS = WG_DY_ELEMS + C8W_HALO_ELEMS;
+constexpr int C8W_LD = 96 + 1;                                 // row of the end-of-block reduction tile
+
+__global__ __launch_bounds__(256, 2) void k_wgrad3x3_c8(const bf16_t *__restrict__ x, const bf16_t *__restrict__ dy,
+                                                        float *__restrict__ part, int N, int H, int W, int K,
+                                                        int units_per_split, unsigned x_bytes, unsigned dy_bytes,
+                                                        int with_bias)
+{
+    constexpr unsigned OOB = 0x80000000u;
+    constexpr int NW = 4;
+    extern __shared__ __align__(16) unsigned char smem[];
+    const lds_addr_of lds_of(smem);
+    uint16_t *stage0 = reinterpret_cast<uint16_t *>(smem);
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int ko0 = blockIdx.x * 64;
+    const int ux = W / UW, uy = H / UH, upi = ux * uy;
+    const int U = N * upi;
+    const int u0 = blockIdx.y * units_per_split;
+    const int u1 = u0 + units_per_split < U ? u0 + units_per_split : U;
+
+    __amdgpu_buffer_rsrc_t xrsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t *>(x), 0, (int)x_bytes, 0x00020000);
+    __amdgpu_buffer_rsrc_t grsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t *>(dy), 0, (int)dy_bytes, 0x00020000);
+
+    unsigned dco[WG_DL];
+    int ddy[WG_DL], ddx[WG_DL];
+#pragma unroll
+    for (int i = 0; i < WG_DL; ++i) {
+        const int slot = (i * NW + wave) * 64 + lane;
+        const int px = slot >> 3, cq = slot & 7;
+        const int c = ((((cq >> 1) ^ wg_swz<64>(px)) << 1) | (cq & 1));
+        ddy[i] = px >> 4;
+        ddx[i] = px & 15;
+        dco[i] = (unsigned)(ko0 + c * 8) * 2u;
+    }
+    const int hr = wave * 64 + lane;                           // halo pixel of this lane (waves 0..2)
+    const int hdy = hr / WH_COLS - 1, hdx = hr % WH_COLS - 1;
+    auto issue_unit = [&](int u, int st) {
+        uint16_t *sd = stage0 + st * C8W_STAGE_ELEMS, *sh = sd + WG_DY_ELEMS;
+        const bool live = u < u1;
+        const int n = u / upi, rem = u - n * upi;
+        const int Y0 = (rem / ux) * UH, X0 = (rem % ux) * UW;
+#pragma unroll
+        for (int i = 0; i < WG_DL; ++i) {
+            unsigned vo = live ? (unsigned)(((n * H + Y0 + ddy[i]) * W + X0 + ddx[i]) * K) * 2u + dco[i] : OOB;
+            dma16(grsrc, lds_of(sd + (i * NW + wave) * 512), vo);
+        }
+        if (wave < 3) {
+            const int y = Y0 + hdy, xx = X0 + hdx;
+            const bool ok = live && hr < WH_PIX && (unsigned)y < (unsigned)H && (unsigned)xx < (unsigned)W;
+            dma16(xrsrc, lds_of(sh + wave * 512), ok ? (unsigned)((n * H + y) * W + xx) * 16u : OOB);
+        }
+    };
+
+    f32x16_t acc[2][3];
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int b = 0; b < 3; ++b)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.0f;
+    float bsum[2] = {0.0f, 0.0f};
+
+    // x fragment addressing: column n = b*32 + (lane & 31) is (tap, channel) = (n / 8, n % 8); the 8 pixels
+    // of a fragment lie in one row of the unit, so they are 8 consecutive halo pixels
+    const int frow = lane & 31, fhalf = lane >> 5;
+    int xoff[3];                                               // element offset of pixel 0 of the unit under the lane's tap
+    bool xin[3];
+#pragma unroll
+    for (int b = 0; b < 3; ++b) {
+        const int nn = b * 32 + frow, tap = nn >> 3, c = nn & 7;
+        xin[b] = nn < 72;
+        xoff[b] = xin[b] ? ((tap / 3) * WH_COLS + tap % 3) * 8 + c : 0;
+    }
+
+    issue_unit(u0, 0);
+    WAIT_LGKMCNT(0);
+    for (int u = u0; u < u1; ++u) {
+        const int st = (u - u0) & 1;
+        WAIT_VMCNT(0);
+        __builtin_amdgcn_s_barrier();
+        issue_unit(u + 1, st ^ 1);
+        const uint16_t *sd = stage0 + st * C8W_STAGE_ELEMS, *sh = sd + WG_DY_ELEMS;
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) {
+            const int k0 = wave * 32 + ks * 16;                // first pixel of this K-step (this wave's 32 pixels)
+            const int p = k0 + 8 * fhalf;                      // first of the lane's 8 pixels: row p / 16, column p % 16
+            const int hbase = ((p >> 4) * WH_COLS + (p & 15)) * 8;
+            bf16x8_t fa[2], fb[3];
+#pragma unroll
+            for (int a = 0; a < 2; ++a) fa[a] = tr_frag<64>(sd, a * 32, k0, lane);
+#pragma unroll
+            for (int b = 0; b < 3; ++b) {
+                chunk16 v = {0u, 0u, 0u, 0u};
+                if (xin[b]) {
+                    const uint16_t *q = sh + hbase + xoff[b];
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) v[j] = (uint32_t)q[16 * j] | ((uint32_t)q[16 * j + 8] << 16);
+                }
+                fb[b] = as_frag(v);
+            }
+            if (with_bias) {
+#pragma unroll
+                for (int a = 0; a < 2; ++a) bsum[a] = frag_sum(fa[a], bsum[a]);
+            }
+#pragma unroll
+            for (int a = 0; a < 2; ++a)
+#pragma unroll
+                for (int b = 0; b < 3; ++b)
+                    acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[a], fb[b], acc[a][b], 0, 0, 0);
+        }
+    }
+    WAIT_VMCNT(0);
+    __syncthreads();
+
+    // add the four waves' tiles in wave order through LDS: red[ko 64][n 96], then the bias sums
+    float *red = reinterpret_cast<float *>(smem);
+    float *bred = red + 64 * C8W_LD;                           // [4 waves][64]
+    for (int w = 0; w < NW; ++w) {
+        if (wave == w) {
+#pragma unroll
+            for (int a = 0; a < 2; ++a)
+#pragma unroll
+                for (int b = 0; b < 3; ++b)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) {
+                        float *q = red + (a * 32 + 8 * (v >> 2) + 4 * fhalf + (v & 3)) * C8W_LD + b * 32 + frow;
+                        *q = w == 0 ? acc[a][b][v] : *q + acc[a][b][v];
+                    }
+        }
+        __syncthreads();
+    }
+    if (with_bias) {
+#pragma unroll
+        for (int a = 0; a < 2; ++a) {
+            const float t = bsum[a] + __shfl_xor(bsum[a], 32, 64);
+            if (fhalf == 0) bred[wave * 64 + a * 32 + frow] = t;
+        }
+        __syncthreads();
+    }
+    const size_t total_w = (size_t)K * 72;
+    float *dst = part + (size_t)blockIdx.y * (total_w + (with_bias ? K : 0));
+    for (int i = tid; i < 64 * 72; i += 256) {
+        const int ko = i / 72, nn = i - ko * 72;
+        dst[(size_t)(ko0 + ko) * 72 + nn] = red[ko * C8W_LD + nn];
+    }
+    if (with_bias && tid < 64) dst[total_w + ko0 + tid] = (bred[tid] + bred[64 + tid]) + (bred[128 + tid] + bred[192 + tid]);
+}
+
 struct WgHaloPlan {
     int tiles, splits, units_per_split;
 };
@@ -763,6 +923,50 @@ hipError_t conv3x3_halo_pool_mfma(const void *in, const void *wt, const float *b
 }  // namespace bapipe
 
 namespace bapipe {
+
+bool wgrad3x3_c8_supported(const ConvShape &c)
+{
+    return c.R == 3 && c.S == 3 && c.stride == 1 && c.pad == 1 && c.H == c.P && c.W == c.Q && c.H % UH == 0 &&
+           c.W % UW == 0 && c.C == 8 && c.K % 64 == 0 && (long long)c.N * c.H * c.W * 16 < (1ll << 31) &&
+           (long long)c.N * c.H * c.W * c.K * 2 < (1ll << 31);
+}
+
+static WgHaloPlan wg_c8_plan(const ConvShape &c)
+{
+    WgHaloPlan p;
+    p.tiles = c.K / 64;
+    const int U = c.N * (c.H / UH) * (c.W / UW);
+    int want = (512 + p.tiles - 1) / p.tiles;
+    if (want > U) want = U;
+    if (want < 1) want = 1;
+    p.units_per_split = (U + want - 1) / want;
+    p.splits = (U + p.units_per_split - 1) / p.units_per_split;
+    return p;
+}
+
+size_t wgrad3x3_c8_workspace(const ConvShape &c)
+{
+    return (size_t)wg_c8_plan(c).splits * ((size_t)c.K * 72 + c.K) * sizeof(float);
+}
+
+hipError_t wgrad3x3_c8_mfma(const void *x, const void *dy, float *dw, float *db, void *workspace, const ConvShape &c,
+                            hipStream_t s)
+{
+    if (!wgrad3x3_c8_supported(c)) return hipErrorInvalidValue;
+    const WgHaloPlan p = wg_c8_plan(c);
+    constexpr size_t stages = (size_t)2 * C8W_STAGE_ELEMS * 2, redb = (size_t)(64 * C8W_LD + 256) * sizeof(float);
+    constexpr size_t smem = stages > redb ? stages : redb;
+    static_assert(smem <= 64 * 1024, "no attribute needed, two blocks per CU");
+    const unsigned x_bytes = (unsigned)((size_t)c.N * c.H * c.W * 16);
+    const unsigned dy_bytes = (unsigned)((size_t)c.N * c.H * c.W * c.K * 2);
+    float *part = (float *)workspace;
+    hipLaunchKernelGGL(k_wgrad3x3_c8, dim3((unsigned)p.tiles, (unsigned)p.splits), dim3(256), smem, s, (const bf16_t *)x,
+                       (const bf16_t *)dy, part, c.N, c.H, c.W, c.K, p.units_per_split, x_bytes, dy_bytes, db ? 1 : 0);
+    const size_t total_w = (size_t)c.K * 72, total = total_w + (db ? c.K : 0);
+    hipLaunchKernelGGL(k_wg_halo_reduce, dim3((unsigned)((total / 4 + 63) / 64)), dim3(256), 0, s, part, dw, db,
+                       total_w, total, p.splits);
+    return hipGetLastError();
+}
 
 bool wgrad3x3_halo_supported(const ConvShape &c)
 {

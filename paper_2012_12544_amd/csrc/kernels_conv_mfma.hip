@@ -962,6 +962,7 @@ bool conv_wgrad_mfma_supported(const ConvShape &c)
 size_t conv_wgrad_mfma_workspace(const ConvShape &c)
 {
     if (wgrad3x3_halo_supported(c)) return wgrad3x3_halo_workspace(c);
+    if (wgrad3x3_c8_supported(c)) return wgrad3x3_c8_workspace(c);
     WgradPlan p = wgrad_plan(c);
     return p.splits == 1 ? 0 : (size_t)p.splits * ((size_t)c.K * c.R * c.S * c.C + c.K) * sizeof(float);
 }
@@ -972,6 +973,7 @@ hipError_t conv_wgrad_mfma(const void *x, const void *dy, float *dw, float *db, 
     if (!conv_wgrad_mfma_supported(c)) return hipErrorInvalidValue;
     if ((long long)c.N * c.P * c.Q == 0) return hipSuccess;
     if (wgrad3x3_halo_supported(c)) return wgrad3x3_halo_mfma(x, dy, dw, db, workspace, c, s);
+    if (wgrad3x3_c8_supported(c)) return wgrad3x3_c8_mfma(x, dy, dw, db, workspace, c, s);
     WgradPlan p = wgrad_plan(c);
     dim3 grid((unsigned)(p.tiles_ko * p.tiles_n), (unsigned)p.splits);
     const int direct = p.splits == 1;
