@@ -517,11 +517,17 @@ __global__ __launch_bounds__(256, 2) void k_wgrad3x3_halo(const bf16_t *__restri
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wk = wave & 1, wn = wave >> 1;                   // 32 output channels x 9 column tiles per wave
     const int cslices = C / 64;
-    const int cs = blockIdx.x % cslices, kt = blockIdx.x / cslices;
+    // The (output-channel, input-channel) tiles of one split read the same dy rows and x halos: number the
+    // blocks so that they run on the same XCD (one L2) at the same time - consecutive block ids go round the
+    // eight XCDs, so each XCD is given a contiguous range of (split, tile) positions
+    const int tiles = (int)gridDim.x;
+    const int pos = xcd_remap((int)(blockIdx.y * gridDim.x + blockIdx.x), tiles * (int)gridDim.y);
+    const int tile = pos % tiles, split = pos / tiles;
+    const int cs = tile % cslices, kt = tile / cslices;
     const int ko0 = kt * 64, ci0 = cs * 64;
     const int ux = W / UW, uy = H / UH, upi = ux * uy;
     const int U = N * upi;
-    const int u0 = blockIdx.y * units_per_split;
+    const int u0 = split * units_per_split;
     const int u1 = u0 + units_per_split < U ? u0 + units_per_split : U;
 
     __amdgpu_buffer_rsrc_t xrsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t *>(x), 0, (int)x_bytes, 0x00020000);
@@ -648,7 +654,7 @@ __global__ __launch_bounds__(256, 2) void k_wgrad3x3_halo(const bf16_t *__restri
     // partial[split][ko][tap][c] followed by the bias partial [split][ko]: a wave writes 32 consecutive
     // c (128 bytes) per row
     const size_t total_w = (size_t)K * 9 * C;
-    float *dst = part + (size_t)blockIdx.y * (total_w + (with_bias ? K : 0));
+    float *dst = part + (size_t)split * (total_w + (with_bias ? K : 0));
     const int col = lane & 31, half = lane >> 5;
     if (do_bias) {
         bsum += __shfl_xor(bsum, 32, 64);

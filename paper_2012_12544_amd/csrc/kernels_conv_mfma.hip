@@ -595,11 +595,16 @@ __global__ __launch_bounds__(WKO *WCI * 64, 2) void k_wgrad_mfma(const bf16_t *_
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wk = wave % WKO, wi = wave / WKO;
-    const int tn = blockIdx.x % tiles_n, tko = blockIdx.x / tiles_n;
+    // The tiles of one pixel split read the same dy and x rows: number the blocks so that a split's tiles run on
+    // one XCD (one L2) - consecutive block ids go round the eight XCDs, so each XCD gets a contiguous range of
+    // (split, tile) positions.  With a single split (or few blocks) this is the identity up to a permutation.
+    const int pos = xcd_remap((int)(blockIdx.y * gridDim.x + blockIdx.x), (int)(gridDim.x * gridDim.y));
+    const int bx = pos % (int)gridDim.x, by = pos / (int)gridDim.x;
+    const int tn = bx % tiles_n, tko = bx / tiles_n;
     const int ko0 = tko * BKO, n0 = tn * BCI;
     const int Ntot = c.R * c.S * c.C;
     const int npix = c.N * c.P * c.Q;
-    const int p_begin = blockIdx.y * pix_per_split;
+    const int p_begin = by * pix_per_split;
     const int p_end = p_begin + pix_per_split < npix ? p_begin + pix_per_split : npix;
     const int KT = (p_end - p_begin + BKP - 1) / BKP;
 
@@ -761,10 +766,10 @@ __global__ __launch_bounds__(WKO *WCI * 64, 2) void k_wgrad_mfma(const bf16_t *_
     WAIT_VMCNT(0);
 
     // partial[split][ko][n]
-    float *dst = part + (size_t)blockIdx.y * split_stride;
+    float *dst = part + (size_t)by * split_stride;
     const int col = lane & 31, half = lane >> 5;
     if (do_bias) {
-        float *bdst = bpart + (size_t)blockIdx.y * split_stride;
+        float *bdst = bpart + (size_t)by * split_stride;
 #pragma unroll
         for (int a = 0; a < TA; ++a) {
             const float t = bsum[a] + __shfl_xor(bsum[a], 32, 64);
