@@ -15,7 +15,7 @@ import sys
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 # kernel class of the library's timing tap -> kernel name fragments
-CLASSES = {"gather": ("k_gather_mfma", "k_conv3x3_halo", "k_conv3x3_c8"), "wgrad": ("k_wgrad_mfma", "k_wgrad3x3_halo"),
+CLASSES = {"gather": ("k_gather_mfma", "k_conv3x3_halo", "k_conv3x3_c8"), "wgrad": ("k_wgrad_mfma", "k_wgrad3x3_halo", "k_wgrad3x3_c8"),
            "direct": ("k_conv_",), "pool": ("k_pool_",), "bn": ("k_bn_",), "eltwise": ("k_grad_copy",)}
 COPY_BYTES = float(1 << 30)
 

@@ -11,7 +11,7 @@ Two kinds of check:
   not gated, because they cannot agree between ANY two implementations that round to bf16 at
   the same points but sum in a different order: a one-ulp difference in a stored activation
   flips ReLU gates / pool arg-max choices a few layers later, each flip moves a gradient by
-  O(1) locally, and the flips compound with depth ("bf16 decision flips").
+  O(1) locally, and the flips compound with depth.
 
 * layer by layer, teacher-forced BY THE ORACLE - the oracle runs the whole stage once and, for
   every conv / linear / batch-norm / pool / loss layer, its input x_l and its gated output
