@@ -107,6 +107,9 @@ hipError_t maxpool_bwd(int dt, const void *dy, const uint8_t *idx, void *dx, Gra
 hipError_t avgpool_fwd(int dt, const void *x, void *y, int N, int H, int W, int C, int kh, int kw, hipStream_t s);
 hipError_t avgpool_bwd(int dt, const void *dy, void *dx, GradEpi epi, int N, int H, int W, int C, int kh, int kw,
                        hipStream_t s);
+// dx[n,h,w,:] (+)= t[n,h/stride,w/stride,:] at multiples of the stride, zero elsewhere (t: [N][Ho][Wo][C])
+hipError_t upsample_grad(int dt, const void *t, void *dx, GradEpi epi, int N, int H, int W, int Ho, int Wo, int C,
+                         int stride, hipStream_t s);
 hipError_t add_fwd(int dt, const void *a, const void *b, void *y, int relu, size_t n, hipStream_t s);
 // dx (+)= dy with the epilogue of grad_out
 hipError_t grad_copy(int dt, const void *dy, void *dx, GradEpi epi, size_t n, hipStream_t s);

@@ -72,6 +72,32 @@ __global__ void k_grad_copy(const T *__restrict__ dy, const T *__restrict__ own_
     reinterpret_cast<vec_t<T, V> *>(dx)[i] = r;
 }
 
+// dx[n,h,w,:] (+)= t[n,h/s,w/s,:] where h and w are multiples of s (and inside t), zero elsewhere: the input
+// gradient of a 1x1 convolution with stride s, whose product with the filter was taken at the strided
+// resolution.  Same epilogue as every gradient write.
+template <class T, int V>
+__global__ void k_upsample_grad(const T *__restrict__ t, T *dx, const T *__restrict__ gate, int accum, int N,
+                                int H, int W, int Ho, int Wo, int CV, int stride)
+{
+    size_t i = (size_t)blockIdx.x * TPB + threadIdx.x;
+    if (i >= (size_t)N * H * W * CV) return;
+    const int cv = (int)(i % CV);
+    size_t r = i / CV;
+    const int w = (int)(r % W);
+    r /= W;
+    const int h = (int)(r % H), n = (int)(r / H);
+    const int p = h / stride, q = w / stride;
+    const bool hit = p * stride == h && q * stride == w && p < Ho && q < Wo;
+    vec_t<T, V> g, old, gt, o;
+    if (hit) g = reinterpret_cast<const vec_t<T, V> *>(t)[(((size_t)n * Ho + p) * Wo + q) * CV + cv];
+    if (accum) old = reinterpret_cast<const vec_t<T, V> *>(dx)[i];
+    if (gate) gt = reinterpret_cast<const vec_t<T, V> *>(gate)[i];
+#pragma unroll
+    for (int j = 0; j < V; ++j)
+        o.e[j] = grad_out<T>(hit ? to_f32(g.e[j]) : 0.0f, accum != 0, old.e[j], gate != nullptr, gt.e[j]);
+    reinterpret_cast<vec_t<T, V> *>(dx)[i] = o;
+}
+
 // ------------------------------------------------------------------ 2x2 stride-2 max-pool
 template <class T, int V>
 __global__ void k_pool_fwd(const T *__restrict__ x, T *__restrict__ y, uint8_t *__restrict__ idx, int N,
@@ -1147,6 +1173,21 @@ hipError_t grad_copy(int dt, const void *dy, void *dx, GradEpi epi, size_t n, hi
         size_t nv = n / V;
         hipLaunchKernelGGL((k_grad_copy<T, V>), dim3(blocks_for(nv)), dim3(TPB), 0, s, (const T *)dy,
                            (const T *)nullptr, (T *)dx, (const T *)epi.gate, epi.accum, nv);
+    });
+    return hipGetLastError();
+}
+
+hipError_t upsample_grad(int dt, const void *t, void *dx, GradEpi epi, int N, int H, int W, int Ho, int Wo, int C,
+                         int stride, hipStream_t s)
+{
+    if (stride < 1 || (long long)(Ho - 1) * stride >= H || (long long)(Wo - 1) * stride >= W) return hipErrorInvalidValue;
+    const size_t n = (size_t)N * H * W * C;
+    if (n == 0) return hipSuccess;
+    const int Vw = dt == DT_F32 ? 4 : 8;
+    const bool vec = C % Vw == 0 && aligned16(t) && aligned16(dx) && aligned16(epi.gate);
+    DISPATCH_TV(dt, vec, {
+        hipLaunchKernelGGL((k_upsample_grad<T, V>), dim3(blocks_for(n / V)), dim3(TPB), 0, s, (const T *)t, (T *)dx,
+                           (const T *)epi.gate, epi.accum, N, H, W, Ho, Wo, C / V, stride);
     });
     return hipGetLastError();
 }

@@ -76,6 +76,10 @@ struct Layer {
     // input-gradient kernel leaves the per-tile sums of dy and dy*xhat for that batch-norm's backward
     int bnb_chunks = 0;
     bool bwd_sums_given = false;
+    // 1x1 conv with a stride: its input gradient is non-zero only at multiples of the stride, so the product
+    // with the filter is taken at the output's resolution into the workspace (at up_off) and spread from there
+    bool strided_1x1 = false;
+    size_t up_off = 0;
     // LSTM: per in-flight micro-batch the slot keeps the gates and cell states (float), the delayed
     // copy of h that the recurrent products read, the buffer shared by the input projection
     // (forward) and the pre-activation gradients (backward) and the cell-gradient carry
@@ -622,7 +626,14 @@ int layer_backward(bapipe_stage *st, int li, BwdCtx &c)
             void *dx = grad_ptr(st, L.a, c);
             const bool mf = use_mfma_gather(st, dg);
             const bool tp = st->tap_begin(mf ? BAPIPE_KC_CONV_GATHER_MFMA : BAPIPE_KC_CONV_DIRECT);
-            if (mf && L.bnb_chunks && !c.profiling && (e.gate || e.accum)) {
+            if (mf && L.strided_1x1) {
+                GatherConv dense = dg;                       // dy as the image, one output pixel per dy pixel
+                dense.Ho = dg.Hi; dense.Wo = dg.Wi; dense.s_in = 1;
+                GradEpi none{nullptr, 0};
+                void *tmp = st->work + L.up_off;
+                HIPCHK(conv_gather_mfma(g, L.w_t, nullptr, tmp, 0, none, dense, st->work, s));
+                HIPCHK(upsample_grad(dt, tmp, dx, e, dg.N, dg.Ho, dg.Wo, dg.Hi, dg.Wi, dg.Co, L.d.stride, s));
+            } else if (mf && L.bnb_chunks && !c.profiling && (e.gate || e.accum)) {
                 const Layer &B = st->layers[li - 1];
                 HIPCHK(conv_gather_mfma(g, L.w_t, nullptr, dx, 0, e, dg, st->work, s, (float *)st->work,
                                         st->tptr(B.a, c.mbid), (const float *)(st->slot(c.mbid) + B.aux_off)));
@@ -1083,6 +1094,19 @@ int bapipe_stage_create(const bapipe_layer_desc_t *layers, int n_layers, int mic
                     const size_t w = (size_t)2 * chunks * X.C * sizeof(float) + 4 * (size_t)X.C * sizeof(float);
                     work = w > work ? w : work;
                 }
+            }
+        }
+        if (L.d.kind == BAPIPE_CONV2D && st->dt == DT_BF16 && L.d.kh == 1 && L.d.kw == 1 && L.d.stride > 1 && L.d.pad == 0 &&
+            st->tensors[st->tensors[L.a].root].need_grad) {
+            const GatherConv dg = dgrad_geom(st, L);
+            GatherConv dense = dg;
+            dense.Ho = dg.Hi; dense.Wo = dg.Wi; dense.s_in = 1;
+            if (use_mfma_gather(st, dg) && use_mfma_gather(st, dense)) {
+                L.strided_1x1 = true;
+                L.bnb_chunks = 0;
+                L.up_off = align_up(conv_gather_mfma_workspace(dense));
+                const size_t w = L.up_off + align_up((size_t)dense.N * dense.Ho * dense.Wo * dense.Co * es);
+                work = w > work ? w : work;
             }
         }
         if (L.d.kind == BAPIPE_CONV2D || L.d.kind == BAPIPE_LINEAR) {
