@@ -349,6 +349,18 @@ __global__ __launch_bounds__(WP *WC * 64, WP *WC >= 8 ? 1 : 2) void k_gather_mfm
             }
         }
     }
+    // gradient epilogue: the ReLU-gate rows of the thread's first units are requested now, so that they travel
+    // while the staging tile is being completed instead of after the barrier
+    constexpr int GUNITS = BP * (BC / 8) / NT, GPRE = GUNITS < 8 ? GUNITS : 8;
+    chunk16 gpre[GPRE];
+    if (is_grad && gate) {
+#pragma unroll
+        for (int it = 0; it < GPRE; ++it) {
+            const int u = tid + it * NT;
+            const int p = pix0 + u / (BC / 8), co = co0 + (u % (BC / 8)) * 8;
+            gpre[it] = (p < npix && co < g.Co) ? *reinterpret_cast<const chunk16 *>(gate + (size_t)p * g.Co + co) : zero16;
+        }
+    }
     __syncthreads();
     // Per-channel sum and sum of squares of the STORED (rounded) values of this pixel tile, for a batch-norm
     // that follows: stat_part[q][pixel tile][channel], q = 0 sum, 1 squares - the layout the final pass of the
@@ -400,7 +412,7 @@ __global__ __launch_bounds__(WP *WC * 64, WP *WC >= 8 ? 1 : 2) void k_gather_mfm
             if (is_grad) {
                 chunk16 old = zero16, gt = zero16, r;
                 if (accum) old = *reinterpret_cast<const chunk16 *>(dst);
-                if (gate) gt = *reinterpret_cast<const chunk16 *>(gate + (size_t)p * g.Co + co);
+                if (gate) gt = it < GPRE ? gpre[it < GPRE ? it : 0] : *reinterpret_cast<const chunk16 *>(gate + (size_t)p * g.Co + co);
 #pragma unroll
                 for (int j = 0; j < 4; ++j) r[j] = grad_epilogue_pair(v[j], old[j], gt[j], accum != 0, gate != nullptr);
                 *reinterpret_cast<chunk16 *>(dst) = r;
