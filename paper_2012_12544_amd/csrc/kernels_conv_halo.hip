@@ -262,6 +262,19 @@ __global__ __launch_bounds__(256, 2) void k_conv3x3_halo(const bf16_t *__restric
             }
         }
     }
+    // BC = 128 had no registers for the early gate request above: its gate rows are requested here, where the
+    // accumulators are dead, so that they travel while the staging tile is completed
+    constexpr int GLATE = GPRE == 0 ? UNITS : 0;
+    chunk16 glate[GLATE > 0 ? GLATE : 1];
+    if (GLATE > 0 && is_grad && gate) {
+#pragma unroll
+        for (int it = 0; it < GLATE; ++it) {
+            const int u = tid + it * 256;
+            const int pj = u / CH8, c8i = u % CH8;
+            const size_t p = (size_t)(n * H + Y0 + (pj >> 4)) * W + X0 + (pj & 15);
+            glate[it] = *reinterpret_cast<const chunk16 *>(gate + p * Co + co0 + c8i * 8);
+        }
+    }
     __syncthreads();
     if (pool_out) {
         // fused 2x2 stride-2 max-pool: the patch holds 8x8 complete windows; the conv output itself
@@ -323,6 +336,8 @@ __global__ __launch_bounds__(256, 2) void k_conv3x3_halo(const bf16_t *__restric
             if (accum) old = *reinterpret_cast<const chunk16 *>(dst);
             if (it < GPRE)
                 gt = gpre[it];
+            else if (it < GLATE && gate)
+                gt = glate[it < GLATE ? it : 0];
             else if (gate)
                 gt = *reinterpret_cast<const chunk16 *>(gate + p * Co + co);
 #pragma unroll
