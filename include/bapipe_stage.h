@@ -145,6 +145,22 @@ int bapipe_stage_forward(bapipe_stage_t *st, int mb_id, const void *x_dev, void 
 int bapipe_stage_backward(bapipe_stage_t *st, int mb_id, const void *dy_dev_or_labels,
                           void *dx_dev);
 
+/* bapipe_stage_backward for callers that must not allocate device memory while they run (code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): same arguments,
+ * same schedule rules, same results bit for bit, but the kernels' workspace (split-K partial
+ * sums of the weight-gradient and linear-layer GEMMs, column-reduction partials of batch-norm and
+ * bias gradients, the dense product of a strided 1x1 input gradient) is a statically allocated
+ * device array of BAPIPE_STATIC_SCRATCH_BYTES inside the library instead of the workspace the
+ * handle obtained from its allocator.  The call allocates and frees nothing on the device.  Every
+ * GPU the library runs on holds one copy of the array until the process ends, and all handles on
+ * a GPU share it: two calls that overlap in time on one GPU (different streams or threads) race
+ * on it; calls on one stream are ordered and safe.  The current HIP device must be the stage's.
+ * E_UNSUPPORTED (nothing enqueued) if the stage's kernels need more workspace than the array
+ * holds; otherwise the errors of bapipe_stage_backward. */
+#define BAPIPE_STATIC_SCRATCH_BYTES (64u << 20)
+int bapipe_stage_backward_static(bapipe_stage_t *st, int mb_id, const void *dy_dev_or_labels,
+                                 void *dx_dev);
+
 /* Weight update after the M backward passes of the mini-batch (Sec. III-B-1): plain SGD
  * w <- w - lr * g on the fp32 masters (weights memory is 2w, Table I: no optimiser state),
  * refresh of the working copies, zeroing of the accumulators, and reset of the micro-batch

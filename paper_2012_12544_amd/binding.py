@@ -17,9 +17,11 @@ STATUS_NAMES = ["OK", "E_INVALID", "E_SHAPE", "E_ORDER", "E_OOM", "E_DEVICE", "E
 FP32, BF16 = 0, 1
 NCHW, NHWC = 0, 1
 SCHED_1F1B, SCHED_1F1B_SO = 0, 1
+STATIC_SCRATCH_BYTES = 64 << 20
 
 EXPORTS = [
-    "bapipe_stage_create", "bapipe_stage_forward", "bapipe_stage_backward", "bapipe_stage_step",
+    "bapipe_stage_create", "bapipe_stage_forward", "bapipe_stage_backward", "bapipe_stage_backward_static",
+    "bapipe_stage_step",
     "bapipe_profile_layers", "bapipe_profile_sweep", "bapipe_stage_set_params", "bapipe_stage_get_params",
     "bapipe_stage_get_grads", "bapipe_stage_get_pool_indices", "bapipe_stage_get_loss",
     "bapipe_stage_stash_bytes", "bapipe_last_error", "bapipe_stage_destroy",
@@ -79,6 +81,7 @@ def load():
     lib.bapipe_stage_create.argtypes = [ct.POINTER(LayerDesc), i32, i32, i32, ct.POINTER(StageOpts), ct.POINTER(vp)]
     lib.bapipe_stage_forward.argtypes = [vp, i32, vp, vp]
     lib.bapipe_stage_backward.argtypes = [vp, i32, vp, vp]
+    lib.bapipe_stage_backward_static.argtypes = [vp, i32, vp, vp]
     lib.bapipe_stage_step.argtypes = [vp, ct.c_float]
     lib.bapipe_profile_layers.argtypes = [vp, i32, i32, ct.POINTER(LayerProfile), i32, ct.POINTER(i32)]
     fp = ct.POINTER(ct.c_float)
@@ -163,6 +166,10 @@ def bapipe_stage_forward(h, mb_id, x_ptr, y_ptr):
 
 def bapipe_stage_backward(h, mb_id, dy_or_labels_ptr, dx_ptr):
     _check(load().bapipe_stage_backward(h, mb_id, dy_or_labels_ptr, dx_ptr), h)
+
+
+def bapipe_stage_backward_static(h, mb_id, dy_or_labels_ptr, dx_ptr):
+    _check(load().bapipe_stage_backward_static(h, mb_id, dy_or_labels_ptr, dx_ptr), h)
 
 
 def bapipe_stage_step(h, lr):

@@ -18,6 +18,7 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <string>
 #include <vector>
 
@@ -757,6 +758,39 @@ int flush_deferred(bapipe_stage *st)
 
 }  // namespace
 
+// ---------------------------------------------------------------- statically allocated workspace
+// Workspace of bapipe_stage_backward_static: lives in the code object, one copy per GPU that loads the
+// library, held until the process ends.  `scratch` itself is only a host-side stand-in for the symbol;
+// the device address of each GPU's copy comes from hipGetSymbolAddress, once per device, and only that
+// pointer is ever handed to a kernel.
+static __device__ __align__(256) unsigned char scratch[BAPIPE_STATIC_SCRATCH_BYTES];
+
+namespace {
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+char *g_scratch_ptr[kMaxDevices] = {};
+
+// device address of the current device's copy of `scratch` (looked up on the first call per device)
+hipError_t static_scratch(char **out)
+{
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        g_scratch_ptr[dev] = (char *)p;
+    }
+    *out = g_scratch_ptr[dev];
+    return hipSuccess;
+}
+
+}  // namespace
+
 // ======================================================================== C ABI
 extern "C" {
 
@@ -1279,6 +1313,23 @@ int bapipe_stage_backward(bapipe_stage_t *st, int mb_id, const void *dy_dev_or_l
     if (c.labels) st->loss_valid[mb_id] = 1;
     st->n_bwd++;
     return BAPIPE_OK;
+}
+
+int bapipe_stage_backward_static(bapipe_stage_t *st, int mb_id, const void *dy_dev_or_labels, void *dx_dev)
+{
+    if (!st) return BAPIPE_E_INVALID;
+    if (st->work_bytes > (size_t)BAPIPE_STATIC_SCRATCH_BYTES)
+        return st->fail(BAPIPE_E_UNSUPPORTED, "backward_static: the stage's kernels need %zu bytes of workspace, the static one holds %zu",
+                        st->work_bytes, (size_t)BAPIPE_STATIC_SCRATCH_BYTES);
+    char *ws = nullptr;
+    HIPCHK(static_scratch(&ws));
+    // every kernel of the backward pass writes its partial results before a later kernel of the same pass reads
+    // them (no atomics, nothing accumulates in the workspace), so what the previous call left there needs no clearing
+    char *own = st->work;
+    st->work = ws;
+    const int rc = bapipe_stage_backward(st, mb_id, dy_dev_or_labels, dx_dev);
+    st->work = own;
+    return rc;
 }
 
 int bapipe_stage_step(bapipe_stage_t *st, float lr)

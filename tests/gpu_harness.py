@@ -91,7 +91,7 @@ class GpuStage:
         self.stream.synchronize()
         return from_dev(y, self.out_shape(), self.layout)
 
-    def backward(self, mb, dy_or_labels, want_dx=True):
+    def backward(self, mb, dy_or_labels, want_dx=True, static=False):
         if self.is_loss:
             g = torch.from_numpy(np.ascontiguousarray(dy_or_labels, np.int32)).to(DEV)
         else:
@@ -100,7 +100,8 @@ class GpuStage:
         if self.stage["need_input_grad"] and want_dx:
             dx = torch.empty(int(np.prod(self.in_shape())), dtype=tdtype(self.stage), device=DEV)
         torch.cuda.synchronize()
-        B.bapipe_stage_backward(self.h, mb, g.data_ptr(), None if dx is None else dx.data_ptr())
+        entry = B.bapipe_stage_backward_static if static else B.bapipe_stage_backward
+        entry(self.h, mb, g.data_ptr(), None if dx is None else dx.data_ptr())
         self.stream.synchronize()
         return None if dx is None else from_dev(dx, self.in_shape(), self.layout)
 
