@@ -1,6 +1,6 @@
 """Turn rocprofv3 output of bench.py runs into the short text summaries kept under profiles/.
 
-usage: python -m paper_2012_12544_amd.profile_summary <dir> <workload>
+usage: python _work/profile_summary.py <dir> <workload>
 <dir> holds   kt/<tag>_kernel_stats.csv            (rocprofv3 --kernel-trace --stats)
               pmc_fetch/<tag>_counter_collection.csv (rocprofv3 --pmc FETCH_SIZE, bench.py --calibrate-copy)
               pmc_write/<tag>_counter_collection.csv (rocprofv3 --pmc WRITE_SIZE, bench.py --calibrate-copy)

@@ -193,7 +193,7 @@ def main():
         ach = r["bytes"] / (r["total_ms"] * 1e-3) / 1e9 if r["total_ms"] > 0 else 0.0
         bound, unit, peak = "hbm", "GB/s", PEAK_HBM_GBS
     # HBM bytes per launch of this class as measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
-    # (profiles/<workload>_traffic.json, written by paper_2012_12544_amd.profile_summary); null if absent
+    # (profiles/<workload>_traffic.json); null if absent
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "%s_traffic.json" % a.workload)
     if os.path.exists(tpath):

@@ -1,7 +1,7 @@
 /*
  * bapipe_plan.h - C ABI of the host-side planner that consumes the per-layer profile:
- * the pipeline-schedule cost model (paper Sec. III-A, Tables I and II) and the balanced
- * partition explorer (Sec. III-B: inter-layer partition seeded by Eq. (1), communication
+ * the pipeline-schedule cost model (paper Sec. III-B, Tables I and II) and the balanced
+ * partition explorer (Sec. III-C: inter-layer partition seeded by Eq. (1), communication
  * bottleneck test with the coarse-grained merge by the feature threshold a_th, and the
  * memory fine-tune).  Pure host code: no device is touched, every pointer is host memory
  * owned by the caller, nothing is retained after a call returns.
@@ -45,7 +45,7 @@ typedef struct {
 int bapipe_schedule_cost(int schedule, int M, int N, int i, double F, double B, double SR,
                          double a, double w, bapipe_schedule_cost_t *out);
 
-/* One way of running a mini-batch that the planner may pick (Sec. III-A-2, last paragraph: the
+/* One way of running a mini-batch that the planner may pick (Sec. III-B-2, last paragraph: the
  * schedule is chosen from the hardware limits, the profile and the partition).  A candidate is
  * a schedule together with the micro-batch split it would run at - doubling the warm-up
  * (1F1B-SO) doubles the features memory, so it may only fit with smaller, hence more and
@@ -65,7 +65,7 @@ typedef struct {
 int bapipe_schedule_choose(const bapipe_schedule_candidate_t *cand, int n_cand, int N, const double *w,
                            const double *capacity, int *best, bapipe_schedule_cost_t *cost);
 
-/* Per-layer profile of the whole network as the explorer reads it (Sec. III-B-1: how many
+/* Per-layer profile of the whole network as the explorer reads it (Sec. III-C-1: how many
  * accelerators there are and, for each kind of accelerator, every layer's forward and backward
  * time).  Arrays are indexed [acc * n_layers + layer] where marked per accelerator, else [layer]. */
 typedef struct {
@@ -91,7 +91,7 @@ typedef struct {
     int memory_tuned;            /* 1: the partition was moved to fit mem_capacity             */
 } bapipe_plan_report_t;
 
-/* Balanced partition (Sec. III-B).  stage_begin: caller's array of n_acc + 1 ints; on BAPIPE_OK
+/* Balanced partition (Sec. III-C).  stage_begin: caller's array of n_acc + 1 ints; on BAPIPE_OK
  * stage n (0-based) owns layers [stage_begin[n], stage_begin[n+1]), every stage at least one.
  * Steps, in the paper's order:
  *  1. inter-layer partition: T of Eq. (1); boundaries placed where the running time on each

@@ -22,7 +22,10 @@
  *    synchronising; get_* / profile calls synchronise that stream.
  *  - Weights, gradient accumulators, the activation stash ring and workspaces are owned by
  *    the handle and obtained through opts->mem (NULL callbacks: hipMalloc / hipFree).
- *  - A handle is not thread-safe; distinct handles are independent (no global state).
+ *  - A handle is not thread-safe; distinct handles are independent.  The library keeps two
+ *    pieces of state outside handles: the message of the calling thread's last failed
+ *    bapipe_stage_create (thread-local, read with bapipe_last_error(NULL)) and the statically
+ *    allocated workspace of bapipe_stage_backward_static (one per GPU, see there).
  *  - Storage types.  BAPIPE_FP32: activations, gradients and weights are float.
  *    BAPIPE_BF16: activations, activation gradients and working weights are bfloat16
  *    (round-to-nearest-even), accumulation is fp32, master weights and weight gradients are
@@ -176,7 +179,7 @@ int bapipe_stage_step(bapipe_stage_t *st, float lr);
 int bapipe_profile_layers(bapipe_stage_t *st, int warmup, int iters,
                           bapipe_layer_profile_t *out, int cap, int *n);
 
-/* The same profile taken at several micro-batch sizes (Sec. III-A-2: on GPUs small batches may
+/* The same profile taken at several micro-batch sizes (Sec. III-B-2: on GPUs small batches may
  * not fill the device, so the profile has to treat the batch size as a variable).  For each of
  * the n_sizes entries of micro_batches a temporary stage is created from the layer list
  * (n_micro = 1, otherwise opts as given), profiled as above and destroyed.  out: host array of
@@ -202,7 +205,11 @@ int bapipe_stage_get_pool_indices(bapipe_stage_t *st, int layer, int mb_id, uint
 int bapipe_stage_get_loss(bapipe_stage_t *st, int mb_id, float *loss_host);
 
 /* Activation-stash accounting: bytes kept per in-flight micro-batch and the ring depth
- * min(M, N-i+1) resp. min(M, 2(N-i+1)) (Table I / II). */
+ * min(M, N-i+1) resp. min(M, 2(N-i+1)) (Table I / II, "Features memory").  LINEAR layers whose
+ * weight gradient is formed once per mini-batch keep their input and output gradient of all M
+ * micro-batches (beyond the table's (N-i+1) a); that memory is included, divided by depth and
+ * rounded up, so that per_mb * depth bounds everything held between a forward and the update.
+ * The stash_bytes of bapipe_profile_layers counts it the same way. */
 int bapipe_stage_stash_bytes(const bapipe_stage_t *st, uint64_t *per_mb, int *depth);
 
 /* Measurement tap (Sec. III-A profiles layers; this profiles one kernel class inside the real
@@ -210,8 +217,10 @@ int bapipe_stage_stash_bytes(const bapipe_stage_t *st, uint64_t *per_mb, int *de
  * bracketed by two HIP events on the stage's stream.  _read synchronises the stream and
  * returns the summed event time, the number of launches, and the algorithmic work of those
  * launches: FLOP (2 per multiply-accumulate) for the convolution classes, HBM bytes each
- * element must move once for the others.  Reading resets the counters; at most 4096 launches
- * are recorded between reads.  kernel_class < 0 disables the tap. */
+ * element must move once for the others.  Reading resets the counters.  The event pool grows
+ * as needed up to 262144 launches between reads; beyond that launches go unrecorded and the
+ * next _read returns E_UNSUPPORTED instead of an understated sum.  kernel_class < 0 disables
+ * the tap.  The events themselves cost a few per cent: time a workload with the tap off. */
 enum {
     BAPIPE_KC_CONV_GATHER_MFMA = 0, /* bf16 MFMA forward / dgrad implicit GEMM           */
     BAPIPE_KC_CONV_WGRAD_MFMA = 1,  /* bf16 MFMA wgrad incl. its split-K reduction       */

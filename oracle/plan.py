@@ -1,7 +1,7 @@
 """CPU oracle of the host-side planner (test infrastructure only: nothing in the product imports it).
 
 Schedule cost model: the four columns of Tables I and II written out as printed.
-Balanced partition (Sec. III-B): the definition - among all ways of cutting L layers into N contiguous
+Balanced partition (Sec. III-C): the definition - among all ways of cutting L layers into N contiguous
 non-empty stages (brute force over every combination of N-1 cut points), the smallest possible time of
 the slowest stage, optionally restricted to cuts after layers whose output is at most a_th
 (coarse-grained network) and to stages that fit their accelerator's memory."""

@@ -6,9 +6,9 @@
 // is a GEMM whose K index is contiguous in memory for both operands (NHWC activations,
 // [Ko][R][S][Ki] filters), which is exactly the per-lane fragment the MFMA wants (8 consecutive
 // k for one row).  A block owns BP output pixels x BC output channels; 16-byte chunks of the
-// operand rows are gathered from HBM into registers one K-tile ahead of the MFMAs and written
-// to a double-buffered LDS tile whose 16-byte chunk index is XOR-swizzled with the row so that
-// both the chunk stores and the ds_read_b128 fragment loads are bank-conflict free.
+// operand rows travel from HBM/L2 straight into LDS (buffer_load ... lds, no register staging)
+// into a ring of three K-tiles; the XOR swizzle that makes the ds_read_b128 fragment loads
+// bank-conflict free is applied on the global side, by choosing which chunk a lane fetches.
 // The MFMA's A operand is the filter tile and its B operand the pixel tile, so a lane ends up
 // with 4 consecutive output channels of one pixel per accumulator quad; the tile is then
 // staged through LDS as [pixel][channel] to leave the kernel as 16-byte, fully coalesced rows

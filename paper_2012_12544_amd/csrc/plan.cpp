@@ -1,5 +1,5 @@
 // Host-side planner: pipeline-schedule cost model (Tables I and II) and balanced partition
-// explorer (Sec. III-B).  No device code, no global state.
+// explorer (Sec. III-C).  No device code, no global state.
 #include <cmath>
 #include <limits>
 #include <vector>

@@ -29,7 +29,9 @@ using namespace bapipe;
 
 namespace {
 
-thread_local std::string g_create_error;
+thread_local std::string g_create_error;      // message of the calling thread's last failed create (the one piece of
+                                              // state that is not in a handle: there is no handle to keep it in)
+constexpr size_t kTapMaxEvents = 2 * (1u << 18);   // event pairs the measurement tap may hold
 
 size_t align_up(size_t v, size_t a = 256) { return (v + a - 1) / a * a; }
 
@@ -116,9 +118,19 @@ struct bapipe_stage {
     std::vector<hipEvent_t> tap_events;
     size_t tap_used = 0;
     double tap_flop = 0.0, tap_bytes = 0.0;
+    size_t tap_dropped = 0;                  // launches of the class that found no event pair (pool limit reached)
     bool tap_begin(int cls)
     {
-        if (cls != tap_class || tap_used + 2 > tap_events.size()) return false;
+        if (cls != tap_class) return false;
+        if (tap_used + 2 > tap_events.size()) {              // grow the pool: host-side objects only
+            const size_t grow = 2 * 1024;
+            if (tap_events.size() + grow > kTapMaxEvents) { ++tap_dropped; return false; }
+            for (size_t i = 0; i < grow; ++i) {
+                hipEvent_t e;
+                if (hipEventCreate(&e) != hipSuccess) { (void)hipGetLastError(); ++tap_dropped; return false; }
+                tap_events.push_back(e);
+            }
+        }
         (void)hipEventRecord(tap_events[tap_used], stream);
         return true;
     }
@@ -970,6 +982,14 @@ int bapipe_stage_create(const bapipe_layer_desc_t *layers, int n_layers, int mic
         if (L.b >= 0) st->tensors[L.b].consumers.push_back(i);
     }
     const int nt = n_layers + 1, last_t = n_layers;
+    // the MFMA kernels address their operands with 32-bit byte offsets; larger tensors have no tested kernel
+    for (int t = 0; t < nt; ++t)
+        if (st->tensors[t].bytes() >= ((size_t)1 << 31))
+            return create_fail(BAPIPE_E_UNSUPPORTED, "%s: %zu bytes per micro-batch; tensors of 2 GiB or more are not supported",
+                               t ? "a layer output" : "the stage input", st->tensors[t].bytes());
+    for (int i = 0; i < n_layers; ++i)
+        if (st->layers[i].w_elems * 4 >= ((size_t)1 << 31))
+            return create_fail(BAPIPE_E_UNSUPPORTED, "layer %d: weight matrix of 2 GiB or more", i);
     for (int t = 1; t < nt - 1; ++t)
         if (st->tensors[t].consumers.empty())
             return create_fail(BAPIPE_E_SHAPE, "layer %d: output is never used", t - 1);
@@ -1237,6 +1257,7 @@ int bapipe_stage_forward(bapipe_stage_t *st, int mb_id, const void *x_dev, void 
     const Tensor &In = st->tensors[0];
     const int dt = st->dt;
     hipStream_t s = st->stream;
+    if (mb_id == 0) st->loss_valid.assign(st->M, 0);       // a new mini-batch: the previous one's losses are gone
     FwdCtx c{mb_id, nullptr};
     GradEpi none{nullptr, 0};
     if (st->opts.io_layout == BAPIPE_NCHW) {
@@ -1255,9 +1276,12 @@ int bapipe_stage_forward(bapipe_stage_t *st, int mb_id, const void *x_dev, void 
     if (y_dev) {
         const int last = (int)st->tensors.size() - 1;
         const Tensor &O = st->tensors[last];
+        const Tensor &R = st->tensors[O.root];
         const void *src = in_ptr(st, last, c);
-        if (st->opts.io_layout == BAPIPE_NCHW && O.esize == dt_size(dt) && O.H * O.W > 1)
-            HIPCHK(nhwc_to_nchw(dt, src, y_dev, st->mb, O.C, O.H, O.W, O.Cp, s));
+        // a flattened view of a spatial tensor is indexed c*H*W + h*W + w whatever the boundary layout is
+        const bool flat_of_spatial = O.root != last && R.H * R.W > 1;
+        if (O.esize == dt_size(dt) && ((st->opts.io_layout == BAPIPE_NCHW && R.H * R.W > 1) || flat_of_spatial))
+            HIPCHK(nhwc_to_nchw(dt, src, y_dev, st->mb, R.C, R.H, R.W, R.Cp, s));
         else
             HIPCHK(hipMemcpyAsync(y_dev, src, O.bytes(), hipMemcpyDeviceToDevice, s));
     }
@@ -1289,10 +1313,12 @@ int bapipe_stage_backward(bapipe_stage_t *st, int mb_id, const void *dy_dev_or_l
     } else {
         const int r = st->tensors[last].root;
         const Tensor &O = st->tensors[last];
+        const Tensor &R = st->tensors[r];
         GradEpi e{nullptr, 0};
         if (st->tensors[r].gated) e.gate = st->tptr(r, mb_id);
-        if (!nhwc && O.H * O.W > 1) {
-            HIPCHK(nchw_to_nhwc(dt, dy_dev_or_labels, st->gptr(last), e, st->mb, O.C, O.H, O.W, O.Cp, s));
+        const bool flat_of_spatial = r != last && R.H * R.W > 1;      // dy arrives indexed c*H*W + h*W + w
+        if ((!nhwc && R.H * R.W > 1) || flat_of_spatial) {
+            HIPCHK(nchw_to_nhwc(dt, dy_dev_or_labels, st->gptr(last), e, st->mb, R.C, R.H, R.W, R.Cp, s));
         } else if (e.gate || r == 0) {
             HIPCHK(grad_copy(dt, dy_dev_or_labels, st->gptr(last), e, O.elems, s));
         } else {
@@ -1452,7 +1478,9 @@ int bapipe_stage_get_loss(bapipe_stage_t *st, int mb_id, float *loss_host)
 int bapipe_stage_stash_bytes(const bapipe_stage_t *st, uint64_t *per_mb, int *depth)
 {
     if (!st) return BAPIPE_E_INVALID;
-    if (per_mb) *per_mb = st->slot_bytes;
+    // the inputs / output gradients that the linear layers keep of ALL M micro-batches for their one weight-gradient
+    // GEMM per mini-batch are spread over the ring slots, so that per_mb x depth covers everything the stage holds
+    if (per_mb) *per_mb = st->slot_bytes + (st->deferred_bytes + st->depth - 1) / st->depth;
     if (depth) *depth = st->depth;
     return BAPIPE_OK;
 }
@@ -1468,6 +1496,7 @@ int bapipe_stage_kernel_timing(bapipe_stage_t *st, int kernel_class)
     }
     st->tap_class = kernel_class < 0 ? -1 : kernel_class;
     st->tap_used = 0;
+    st->tap_dropped = 0;
     st->tap_flop = st->tap_bytes = 0.0;
     return BAPIPE_OK;
 }
@@ -1482,6 +1511,14 @@ int bapipe_stage_kernel_timing_read(bapipe_stage_t *st, double *total_ms, uint64
         float t = 0.f;
         HIPCHK(hipEventElapsedTime(&t, st->tap_events[i], st->tap_events[i + 1]));
         ms += t;
+    }
+    const size_t dropped = st->tap_dropped;
+    st->tap_dropped = 0;
+    if (dropped) {
+        st->tap_used = 0;
+        st->tap_flop = st->tap_bytes = 0.0;
+        return st->fail(BAPIPE_E_UNSUPPORTED, "kernel_timing_read: %zu launches were not recorded (more than %zu between reads)",
+                        dropped, kTapMaxEvents / 2);
     }
     if (total_ms) *total_ms = ms;
     if (launches) *launches = st->tap_used / 2;
@@ -1544,6 +1581,8 @@ int bapipe_profile_layers(bapipe_stage_t *st, int warmup, int iters, bapipe_laye
         out[i].out_feature_bytes = (uint64_t)O.bytes();
         uint64_t sb = L.aux_bytes;
         if (O.root == L.o && O.stashed) sb += O.bytes();
+        if (L.deferred)            // kept for all M micro-batches, not only the in-flight ones: spread over the ring depth
+            sb += ((uint64_t)(L.def_x_bytes + L.def_g_bytes) * st->M + st->depth - 1) / st->depth;
         out[i].stash_bytes = sb;
     }
     (void)hipEventDestroy(e0);

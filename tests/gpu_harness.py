@@ -128,6 +128,33 @@ def stage_io(stage):
     return xs, gs
 
 
+def gpu_minibatch(stage, static=False, layout=B.NHWC):
+    """One mini-batch in 1F1B order on the GPU alone: every output the library hands back (y and dx
+    per micro-batch, losses, all weight gradients), by name."""
+    params = gen.all_params(stage, perturb=True)
+    xs, gs = stage_io(stage)
+    g = GpuStage(stage, params, layout=layout)
+    _, depth = B.bapipe_stage_stash_bytes(g.h)
+    out = {}
+    for t, m in one_f_one_b_order(stage["n_micro"], depth):
+        if t == "F":
+            out["y%d" % m] = g.forward(m, xs[m])
+        else:
+            dx = g.backward(m, gs[m], static=static)
+            if dx is not None:
+                out["dx%d" % m] = dx
+            if g.is_loss:
+                out["loss%d" % m] = np.float64(B.bapipe_stage_get_loss(g.h, m))
+    for i, (w, b) in enumerate(params):
+        if w is not None:
+            dw, db = g.grads(i)
+            out["dw%d" % i] = dw
+            if db is not None:
+                out["db%d" % i] = db
+    g.close()
+    return out
+
+
 def pool_index_gap(layer_in, idx_ref, idx_gpu, L):
     """Largest gap, over the windows whose arg-max differs, between the oracle's values at its own
     and at the GPU's arg-max position, relative to max|layer_in| (0 when the indices agree)."""

@@ -268,7 +268,7 @@ def test_profile_feeds_the_partition_explorer():
 
 @pytest.mark.parametrize("net", ["vgg16_full", "resnet50_full"])
 def test_whole_network_profile_is_partitioned_into_four_stages(net):
-    """The loop the profiler exists for (Sec. III-A / III-B): profile every layer of a whole network
+    """The loop the profiler exists for (Sec. III-A / III-C): profile every layer of a whole network
     at its real layer shapes on the device, hand the profile to the partition explorer, and check the
     result against brute force over the measured numbers.  A cut inside a residual block is crossed
     by two tensors; it is priced at their total size, and with a finite link the explorer's own
@@ -378,3 +378,90 @@ def test_allocator_failure_is_reported_and_leaks_nothing():
             B.bapipe_stage_create(st["layers"], 2, 2, opts)
         assert e.value.status == B.E_OOM
         assert not alloc.live
+
+
+# ------------------------------------------------------------------------------ doubled warm-up (Table II, 1F1B-SO)
+@pytest.mark.parametrize("name,stage,want", [
+    # stage 3 of 4: 2(N-i+1) = 4 of 6 micro-batches in flight
+    ("vgg16_deep", C.vgg16_deep(cin=16, c=24, hw=12, micro_batch=3, n_micro=6), 4),
+    # stage 2 of 4: 2(N-i+1) = 6 exceeds M = 4, the ring holds the whole mini-batch
+    ("resnet50_stage", C.resnet50_stage(cin=16, mid3=8, mid4=16, hw=12, n3=1, n4=1, micro_batch=4, n_micro=4), 4),
+    # stage 1 of 2: 4 of 5
+    ("tiny", C.tiny_stage(c=8, hw=12, micro_batch=2, n_micro=5), 4),
+])
+def test_1f1b_so_doubled_warm_up(name, stage, want):
+    """1F1B-SO (Table II "Features memory" 2(N-i+1)a): the ring is twice as deep, the warm-up runs twice as
+    many forwards before the first backward, results are those of the oracle under the same order, and one
+    forward more than the depth is refused."""
+    from gpu_harness import GpuStage
+    so = dict(stage, schedule=C.SCHED_1F1B_SO)
+    i, N, M = so["stage_index"], so["n_stages"], so["n_micro"]
+    assert want == min(M, 2 * (N - i + 1))
+    g = GpuStage(so, gen.all_params(so))
+    per, depth = B.bapipe_stage_stash_bytes(g.h)
+    assert depth == want
+    plain = GpuStage(stage, gen.all_params(stage))
+    assert B.bapipe_stage_stash_bytes(plain.h)[1] == min(M, N - i + 1)
+    plain.close()
+    xs, gs = stage_io(so)
+    for m in range(depth):
+        g.forward(m, xs[m])
+    if depth < M:
+        with pytest.raises(B.BapipeError) as e:
+            g.forward(depth, xs[depth])
+        assert e.value.status == B.E_ORDER
+    g.close()
+    order = one_f_one_b_order(M, want)
+    assert [t for t, _ in order[:want]] == ["F"] * want            # doubled warm-up really is what runs
+    compare_minibatch(so, order=order, verbose="1F1B-SO %s depth %d" % (name, want))
+
+
+# ------------------------------------------------------------------------------ a stage that ends in FLATTEN
+@pytest.mark.parametrize("dtype", DT)
+@pytest.mark.parametrize("layout", [B.NCHW, B.NHWC])
+def test_stage_ending_in_flatten(dtype, layout):
+    """A cut right after pool + flatten: the stage output (and the gradient coming back) is indexed
+    c*H*W + h*W + w in either boundary layout, which is what the next stage's linear layer expects."""
+    def build(b):
+        b.conv(8, 16, 3, relu=1, src=-1)
+        b.pool()
+        b.flatten()
+    st = single(build, 8, (6, 10), dtype, micro_batch=3)
+    compare_minibatch(st, layout=layout, verbose="conv-pool-flatten layout %d" % layout)
+
+
+def test_loss_of_the_previous_mini_batch_is_not_served_again():
+    st = C.vgg16_classifier(c=8, hw=3, hidden=24, classes=7, micro_batch=4, n_micro=2)
+    g = GpuStage(st, gen.all_params(st))
+    xs, gs = stage_io(st)
+    for m in range(2):
+        g.forward(m, xs[m])
+        g.backward(m, gs[m])
+    assert B.bapipe_stage_get_loss(g.h, 1) > 0
+    B.bapipe_stage_step(g.h, 0.1)
+    assert B.bapipe_stage_get_loss(g.h, 1) > 0          # "the just finished mini-batch"
+    g.forward(0, xs[0])
+    for m in range(2):
+        with pytest.raises(B.BapipeError) as e:
+            B.bapipe_stage_get_loss(g.h, m)
+        assert e.value.status == B.E_ORDER
+    g.close()
+
+
+# ------------------------------------------------------------------------------ run twice, compare bit for bit
+@pytest.mark.parametrize("name,stage", [
+    ("vgg16_stage1 64/128 channels", C.vgg16_stage1(c1=64, c2=128, hw=32, micro_batch=3, n_micro=3)),
+    ("vgg16_deep 256 channels", C.vgg16_deep(cin=128, c=256, hw=12, micro_batch=5, n_micro=2)),
+    ("resnet50_stage", C.resnet50_stage(cin=64, mid3=32, mid4=64, hw=24, n3=2, n4=2, micro_batch=4, n_micro=2)),
+    ("classifier", C.vgg16_classifier(c=32, hw=3, hidden=136, classes=29, micro_batch=6, n_micro=3)),
+    ("lstm", C.gnmt_lstm_stage(hidden=64, seq=9, n_layers=2, micro_batch=5, n_micro=2)),
+    ("tiny fp32", C.tiny_stage()),
+])
+def test_same_mini_batch_twice_is_bit_identical(name, stage):
+    """Every reduction runs in a fixed order (split partials added by a second kernel, no atomics), so two
+    runs of the same mini-batch on fresh handles agree bit for bit; a race would show up here."""
+    from gpu_harness import gpu_minibatch
+    a, b = gpu_minibatch(stage), gpu_minibatch(stage)
+    assert sorted(a) == sorted(b) and any(k.startswith("dw") for k in a)
+    for k in a:
+        assert np.array_equal(a[k], b[k]), (name, k)

@@ -7,38 +7,11 @@ when the smaller one runs."""
 import numpy as np
 import pytest
 
-from gpu_harness import GpuStage, stage_io
-from oracle.stage import one_f_one_b_order
+from gpu_harness import GpuStage, gpu_minibatch, stage_io
 from paper_2012_12544_amd import binding as B
 from stage_inputs import configs as C
-from stage_inputs import gen
 
 pytestmark = pytest.mark.gpu
-
-
-def run_minibatch(stage, static):
-    params = gen.all_params(stage, perturb=True)
-    xs, gs = stage_io(stage)
-    g = GpuStage(stage, params)
-    _, depth = B.bapipe_stage_stash_bytes(g.h)
-    out = {}
-    for t, m in one_f_one_b_order(stage["n_micro"], depth):
-        if t == "F":
-            out["y%d" % m] = g.forward(m, xs[m])
-        else:
-            dx = g.backward(m, gs[m], static=static)
-            if dx is not None:
-                out["dx%d" % m] = dx
-            if g.is_loss:
-                out["loss%d" % m] = np.float64(B.bapipe_stage_get_loss(g.h, m))
-    for i, (w, b) in enumerate(params):
-        if w is not None:
-            dw, db = g.grads(i)
-            out["dw%d" % i] = dw
-            if db is not None:
-                out["db%d" % i] = db
-    g.close()
-    return out
 
 
 STAGES = [
@@ -55,9 +28,9 @@ STAGES = [
 
 def test_backward_on_the_static_workspace_matches_backward():
     # all static runs first, largest stage first, so that each later call finds the array as the larger one left it
-    got = [run_minibatch(make(), static=True) for _, make in STAGES]
+    got = [gpu_minibatch(make(), static=True) for _, make in STAGES]
     for (name, make), a in zip(STAGES, got):
-        ref = run_minibatch(make(), static=False)
+        ref = gpu_minibatch(make(), static=False)
         assert sorted(a) == sorted(ref)
         assert any(k.startswith("dw") for k in ref)
         for k in ref:
