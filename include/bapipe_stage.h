@@ -148,6 +148,24 @@ int bapipe_stage_forward(bapipe_stage_t *st, int mb_id, const void *x_dev, void 
 int bapipe_stage_backward(bapipe_stage_t *st, int mb_id, const void *dy_dev_or_labels,
                           void *dx_dev);
 
+/* Overlap of forward and backward passes.  In the 1F1B steady state the forward pass of one
+ * micro-batch and the backward pass of an earlier one alternate (Sec. III-B-1) and do not depend
+ * on each other: they touch different ring slots, and weights only change in the update.  By
+ * default the library still runs them one after the other, on opts->hip_stream.  With a second
+ * stream (caller-owned, same device, default priority) every backward pass is enqueued on it
+ * instead, so that its kernels run beside those of later forward passes and fill the idle compute
+ * units each kernel leaves while it ramps up and drains.  The library orders the two streams with
+ * events: backward(m) starts after forward(m); forward(m + depth), which reuses the ring slot of
+ * micro-batch m, after backward(m); bapipe_stage_step after the last backward pass; the get_* /
+ * set_* calls synchronise both streams.  Results are the same bit for bit.  What changes for the
+ * caller: dx_dev and the loss of a micro-batch are complete when the BACKWARD stream has run the
+ * pass, and dy_dev_or_labels must be complete on (or before) that stream.  A stage with a ring of
+ * depth 1 cannot overlap anything and only pays for the event hand-overs.
+ * hip_stream_backward = NULL (or opts->hip_stream) returns to one stream.  Only between
+ * mini-batches (after create or step), else E_ORDER.  The first call with a stream allocates a
+ * second kernel workspace and 2 M events through opts->mem / HIP: E_OOM, E_DEVICE. */
+int bapipe_stage_set_backward_stream(bapipe_stage_t *st, void *hip_stream_backward);
+
 /* bapipe_stage_backward for callers that must not allocate device memory while they run (code
  * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): same arguments,
  * same schedule rules, same results bit for bit, but the kernels' workspace (split-K partial
@@ -233,6 +251,14 @@ enum {
 int bapipe_stage_kernel_timing(bapipe_stage_t *st, int kernel_class);
 int bapipe_stage_kernel_timing_read(bapipe_stage_t *st, double *total_ms, uint64_t *launches,
                                     double *flop, double *bytes);
+
+/* Measured ceilings of the current device, for reporting kernel throughput against what this very
+ * GPU reaches beside its published peaks (Sec. III-A lists each accelerator's computing power and
+ * memory bandwidth among the hardware constraints the framework takes as input): a register-resident
+ * bf16 MFMA loop with no memory traffic (TFLOP/s, 2 per multiply-accumulate) and a streaming copy of
+ * 256 MiB (GB/s, bytes read + bytes written).  Allocates 0.5 GiB of device memory for the duration
+ * of the call, runs on hip_stream and synchronises it.  E_OOM / E_DEVICE on failure. */
+int bapipe_measure_peaks(void *hip_stream, double *mfma_bf16_tflops, double *copy_gbs);
 
 /* Message of the last failed call on this handle (or of the last failed create when st is
  * NULL); valid until the next call on the same handle. */

@@ -161,6 +161,8 @@ class OracleStage:
                 give(L["src0"], dz.reshape(a.shape))
                 continue
             g = G.pop(i)
+            if self.trace is not None:
+                self.trace[(mb, i)]["gout"] = g      # total gradient of this layer's output, before its own gate
             if L["fuse_relu"] and k in (C.CONV2D, C.BATCHNORM2D, C.ADD, C.LINEAR):
                 g = ops.relu_bwd(outs[i].reshape(g.shape), g)
             if self.trace is not None:

@@ -21,11 +21,12 @@ STATIC_SCRATCH_BYTES = 64 << 20
 
 EXPORTS = [
     "bapipe_stage_create", "bapipe_stage_forward", "bapipe_stage_backward", "bapipe_stage_backward_static",
+    "bapipe_stage_set_backward_stream",
     "bapipe_stage_step",
     "bapipe_profile_layers", "bapipe_profile_sweep", "bapipe_stage_set_params", "bapipe_stage_get_params",
     "bapipe_stage_get_grads", "bapipe_stage_get_pool_indices", "bapipe_stage_get_loss",
     "bapipe_stage_stash_bytes", "bapipe_last_error", "bapipe_stage_destroy",
-    "bapipe_stage_kernel_timing", "bapipe_stage_kernel_timing_read",
+    "bapipe_stage_kernel_timing", "bapipe_stage_kernel_timing_read", "bapipe_measure_peaks",
     "bapipe_schedule_cost", "bapipe_schedule_choose", "bapipe_partition",
 ]
 PLAN_1F1B_AS, PLAN_FBP_AS, PLAN_1F1B_SNO, PLAN_1F1B_SO = range(4)
@@ -82,6 +83,7 @@ def load():
     lib.bapipe_stage_forward.argtypes = [vp, i32, vp, vp]
     lib.bapipe_stage_backward.argtypes = [vp, i32, vp, vp]
     lib.bapipe_stage_backward_static.argtypes = [vp, i32, vp, vp]
+    lib.bapipe_stage_set_backward_stream.argtypes = [vp, vp]
     lib.bapipe_stage_step.argtypes = [vp, ct.c_float]
     lib.bapipe_profile_layers.argtypes = [vp, i32, i32, ct.POINTER(LayerProfile), i32, ct.POINTER(i32)]
     fp = ct.POINTER(ct.c_float)
@@ -94,6 +96,7 @@ def load():
     lib.bapipe_stage_kernel_timing.argtypes = [vp, i32]
     lib.bapipe_stage_kernel_timing_read.argtypes = [vp, ct.POINTER(ct.c_double), ct.POINTER(ct.c_uint64),
                                                     ct.POINTER(ct.c_double), ct.POINTER(ct.c_double)]
+    lib.bapipe_measure_peaks.argtypes = [vp, ct.POINTER(ct.c_double), ct.POINTER(ct.c_double)]
     lib.bapipe_last_error.argtypes = [vp]
     lib.bapipe_last_error.restype = ct.c_char_p
     lib.bapipe_stage_destroy.argtypes = [vp]
@@ -172,6 +175,10 @@ def bapipe_stage_backward_static(h, mb_id, dy_or_labels_ptr, dx_ptr):
     _check(load().bapipe_stage_backward_static(h, mb_id, dy_or_labels_ptr, dx_ptr), h)
 
 
+def bapipe_stage_set_backward_stream(h, stream):
+    _check(load().bapipe_stage_set_backward_stream(h, stream), h)
+
+
 def bapipe_stage_step(h, lr):
     _check(load().bapipe_stage_step(h, lr), h)
 
@@ -248,6 +255,13 @@ def bapipe_stage_kernel_timing_read(h):
     ms, n, fl, by = ct.c_double(0), ct.c_uint64(0), ct.c_double(0), ct.c_double(0)
     _check(load().bapipe_stage_kernel_timing_read(h, ct.byref(ms), ct.byref(n), ct.byref(fl), ct.byref(by)), h)
     return dict(total_ms=ms.value, launches=n.value, flop=fl.value, bytes=by.value)
+
+
+def bapipe_measure_peaks(stream=0):
+    """(bf16 MFMA TFLOP/s of a register-resident loop, GB/s of a streaming copy) on the current device."""
+    tf, gb = ct.c_double(0), ct.c_double(0)
+    _check(load().bapipe_measure_peaks(stream, ct.byref(tf), ct.byref(gb)))
+    return tf.value, gb.value
 
 
 def bapipe_stage_destroy(h):

@@ -9,7 +9,7 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libbapipe_stage.so")
 SOURCES = ["stage.cpp", "plan.cpp", "kernels_elementwise.hip", "kernels_conv_direct.hip", "kernels_conv_mfma.hip",
-           "kernels_conv_halo.hip"]
+           "kernels_conv_halo.hip", "probe_peaks.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-x", "hip",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wall", "-Wno-unused-function"]

@@ -101,6 +101,13 @@ struct bapipe_stage {
     int mb = 0, M = 0, depth = 0;
     float loss_scale = 0.f;
     hipStream_t stream = nullptr;
+    // with a backward stream (bapipe_stage_set_backward_stream) the backward passes run beside the forward passes of
+    // later micro-batches: stream_f / work_f are the handle's own stream and workspace, stream_b / work_b those of the
+    // backward passes, `stream` / `work` whichever the pass being enqueued uses.  Events order the two:
+    // forward m -> backward m (its features), backward m -> forward m + depth (which reuses its ring slot)
+    hipStream_t stream_f = nullptr, stream_b = nullptr;
+    char *work_f = nullptr, *work_b = nullptr;
+    std::vector<hipEvent_t> ev_fwd, ev_bwd;
     // arenas
     char *params = nullptr, *stash = nullptr, *transient = nullptr, *grads = nullptr, *work = nullptr;
     char *deferred = nullptr;
@@ -193,6 +200,13 @@ int create_fail(int code, const char *fmt, ...)
     va_end(ap);
     g_create_error = buf;
     return code;
+}
+
+hipError_t sync_streams(bapipe_stage *st)
+{
+    hipError_t e = hipStreamSynchronize(st->stream);
+    if (e == hipSuccess && st->stream_b) e = hipStreamSynchronize(st->stream_b);
+    return e;
 }
 
 bool has_params(int kind)
@@ -754,6 +768,8 @@ int flush_deferred(bapipe_stage *st)
 {
     const int n = st->n_bwd - st->flushed;
     if (n <= 0) return BAPIPE_OK;
+    // the copies these GEMMs read were enqueued by the backward passes, possibly on their own stream
+    if (st->stream_b) HIPCHK(hipStreamWaitEvent(st->stream, st->ev_bwd[st->n_bwd - 1], 0));
     for (auto &L : st->layers) {
         if (!L.deferred) continue;
         ConvShape cs = conv_shape(st, L);
@@ -812,6 +828,10 @@ void bapipe_stage_destroy(bapipe_stage_t *st)
 {
     if (!st) return;
     (void)hipStreamSynchronize(st->stream);
+    if (st->stream_b) (void)hipStreamSynchronize(st->stream_b);          // the caller's stream: not destroyed here
+    for (hipEvent_t e : st->ev_fwd) if (e) (void)hipEventDestroy(e);
+    for (hipEvent_t e : st->ev_bwd) if (e) (void)hipEventDestroy(e);
+    st->dev_free(st->work_b);
     st->dev_free(st->params);
     st->dev_free(st->stash);
     st->dev_free(st->transient);
@@ -1216,6 +1236,8 @@ int bapipe_stage_create(const bapipe_layer_desc_t *layers, int n_layers, int mic
     st->work = (char *)st->dev_alloc(st->work_bytes);
     st->losses = (float *)st->dev_alloc(sizeof(float) * n_micro);
     if (defb) st->deferred = (char *)st->dev_alloc(defb);
+    st->stream_f = st->stream;
+    st->work_f = st->work;
     if (!st->params || !st->stash || !st->transient || !st->grads || !st->work || !st->losses || (defb && !st->deferred))
         return create_fail(BAPIPE_E_OOM, "device allocation failed (params %zu, stash %zu x %d, transient %zu, grads %zu, work %zu bytes)",
                            st->params_bytes, st->slot_bytes, st->depth, st->transient_bytes, st->grads_bytes, st->work_bytes);
@@ -1258,6 +1280,7 @@ int bapipe_stage_forward(bapipe_stage_t *st, int mb_id, const void *x_dev, void 
     const int dt = st->dt;
     hipStream_t s = st->stream;
     if (mb_id == 0) st->loss_valid.assign(st->M, 0);       // a new mini-batch: the previous one's losses are gone
+    if (st->stream_b && mb_id >= st->depth) HIPCHK(hipStreamWaitEvent(s, st->ev_bwd[mb_id - st->depth], 0));
     FwdCtx c{mb_id, nullptr};
     GradEpi none{nullptr, 0};
     if (st->opts.io_layout == BAPIPE_NCHW) {
@@ -1285,6 +1308,7 @@ int bapipe_stage_forward(bapipe_stage_t *st, int mb_id, const void *x_dev, void 
         else
             HIPCHK(hipMemcpyAsync(y_dev, src, O.bytes(), hipMemcpyDeviceToDevice, s));
     }
+    if (st->stream_b) HIPCHK(hipEventRecord(st->ev_fwd[mb_id], s));
     st->n_fwd++;
     return BAPIPE_OK;
 }
@@ -1296,7 +1320,13 @@ int bapipe_stage_backward(bapipe_stage_t *st, int mb_id, const void *dy_dev_or_l
         return st->fail(BAPIPE_E_ORDER, "backward: expected micro-batch %d (forwarded so far: %d), got %d", st->n_bwd, st->n_fwd, mb_id);
     const int nl = (int)st->layers.size(), last = nl;
     const int dt = st->dt;
+    struct Lane {           // the backward pass runs on its own stream and workspace when there is one
+        bapipe_stage *st;
+        explicit Lane(bapipe_stage *s_) : st(s_) { if (st->stream_b) { st->stream = st->stream_b; st->work = st->work_b; } }
+        ~Lane() { st->stream = st->stream_f; st->work = st->work_f; }
+    } lane(st);
     hipStream_t s = st->stream;
+    if (st->stream_b) HIPCHK(hipStreamWaitEvent(s, st->ev_fwd[mb_id], 0));
     const bool nhwc = st->opts.io_layout == BAPIPE_NHWC;
     BwdCtx c;
     c.mbid = mb_id;
@@ -1337,7 +1367,37 @@ int bapipe_stage_backward(bapipe_stage_t *st, int mb_id, const void *dy_dev_or_l
             HIPCHK(nhwc_to_nchw(dt, st->gptr(0), dx_dev, st->mb, In.C, In.H, In.W, In.Cp, s));
     }
     if (c.labels) st->loss_valid[mb_id] = 1;
+    if (st->stream_b) HIPCHK(hipEventRecord(st->ev_bwd[mb_id], s));
     st->n_bwd++;
+    return BAPIPE_OK;
+}
+
+int bapipe_stage_set_backward_stream(bapipe_stage_t *st, void *hip_stream_backward)
+{
+    if (!st) return BAPIPE_E_INVALID;
+    if (st->n_fwd != 0 || st->n_bwd != 0)
+        return st->fail(BAPIPE_E_ORDER, "set_backward_stream: only between mini-batches (after create or step)");
+    HIPCHK(sync_streams(st));
+    hipStream_t sb = (hipStream_t)hip_stream_backward;
+    if (!sb || sb == st->stream_f) {
+        st->stream_b = nullptr;                   // workspace and events stay for the next time
+        return BAPIPE_OK;
+    }
+    if (!st->work_b) {
+        st->work_b = (char *)st->dev_alloc(st->work_bytes);
+        if (!st->work_b) return st->fail(BAPIPE_E_OOM, "set_backward_stream: %zu bytes of workspace", st->work_bytes);
+    }
+    if (st->ev_fwd.empty()) {
+        std::vector<hipEvent_t> ev(2 * (size_t)st->M, nullptr);
+        for (auto &e : ev)
+            if (hipEventCreateWithFlags(&e, hipEventDisableTiming) != hipSuccess) {
+                for (hipEvent_t d : ev) if (d) (void)hipEventDestroy(d);
+                return st->fail(BAPIPE_E_DEVICE, "set_backward_stream: hipEventCreate failed");
+            }
+        st->ev_fwd.assign(ev.begin(), ev.begin() + st->M);
+        st->ev_bwd.assign(ev.begin() + st->M, ev.end());
+    }
+    st->stream_b = sb;
     return BAPIPE_OK;
 }
 
@@ -1351,10 +1411,13 @@ int bapipe_stage_backward_static(bapipe_stage_t *st, int mb_id, const void *dy_d
     HIPCHK(static_scratch(&ws));
     // every kernel of the backward pass writes its partial results before a later kernel of the same pass reads
     // them (no atomics, nothing accumulates in the workspace), so what the previous call left there needs no clearing
-    char *own = st->work;
-    st->work = ws;
+    char *own_f = st->work_f, *own_b = st->work_b;
+    st->work = st->work_f = ws;
+    if (st->work_b) st->work_b = ws;
     const int rc = bapipe_stage_backward(st, mb_id, dy_dev_or_labels, dx_dev);
-    st->work = own;
+    st->work_f = own_f;
+    st->work_b = own_b;
+    st->work = own_f;
     return rc;
 }
 
@@ -1363,6 +1426,7 @@ int bapipe_stage_step(bapipe_stage_t *st, float lr)
     if (!st) return BAPIPE_E_INVALID;
     if (st->n_bwd != st->M)
         return st->fail(BAPIPE_E_ORDER, "step: %d of %d backward passes done", st->n_bwd, st->M);
+    if (st->stream_b) HIPCHK(hipStreamWaitEvent(st->stream, st->ev_bwd[st->M - 1], 0));
     {
         int rc = flush_deferred(st);
         if (rc != BAPIPE_OK) return rc;
@@ -1385,7 +1449,7 @@ int bapipe_stage_set_params(bapipe_stage_t *st, int layer, const float *w_host, 
     if (layer < 0 || layer >= (int)st->layers.size() || !st->layers[layer].w_elems)
         return st->fail(BAPIPE_E_INVALID, "set_params: layer %d has no parameters", layer);
     Layer &L = st->layers[layer];
-    HIPCHK(hipStreamSynchronize(st->stream));
+    HIPCHK(sync_streams(st));
     if (w_host) {
         if (L.d.kind == BAPIPE_BATCHNORM2D) {
             HIPCHK(hipMemcpy(L.w, w_host, L.w_elems * 4, hipMemcpyHostToDevice));
@@ -1394,7 +1458,7 @@ int bapipe_stage_set_params(bapipe_stage_t *st, int layer, const float *w_host, 
             to_internal(L, w_host, tmp.data());
             HIPCHK(hipMemcpy(L.w, tmp.data(), L.w_elems * 4, hipMemcpyHostToDevice));
             HIPCHK(refresh_work(st, L));
-            HIPCHK(hipStreamSynchronize(st->stream));
+            HIPCHK(sync_streams(st));
         }
     }
     if (b_host) {
@@ -1414,7 +1478,7 @@ static int get_vectors(bapipe_stage_t *st, int layer, float *w_host, float *b_ho
         int rc = flush_deferred(st);
         if (rc != BAPIPE_OK) return rc;
     }
-    HIPCHK(hipStreamSynchronize(st->stream));
+    HIPCHK(sync_streams(st));
     if (w_host) {
         const float *src = grads ? L.dw : L.w;
         if (L.d.kind == BAPIPE_BATCHNORM2D) {
@@ -1453,7 +1517,7 @@ int bapipe_stage_get_pool_indices(bapipe_stage_t *st, int layer, int mb_id, uint
     const Tensor &O = st->tensors[L.o];
     // NHWC on the device -> NCHW for the caller, through the workspace if it is large enough
     std::vector<uint8_t> tmp(O.elems);
-    HIPCHK(hipStreamSynchronize(st->stream));
+    HIPCHK(sync_streams(st));
     HIPCHK(hipMemcpy(tmp.data(), st->slot(mb_id) + L.aux_off, O.elems, hipMemcpyDeviceToHost));
     const int N = st->mb, C = O.C, H = O.H, W = O.W;
     for (int n = 0; n < N; ++n)
@@ -1470,7 +1534,7 @@ int bapipe_stage_get_loss(bapipe_stage_t *st, int mb_id, float *loss_host)
     if (st->layers.back().d.kind != BAPIPE_SOFTMAX_XENT) return st->fail(BAPIPE_E_ORDER, "get_loss: stage has no loss layer");
     if (mb_id < 0 || mb_id >= st->M || !st->loss_valid[mb_id])
         return st->fail(BAPIPE_E_ORDER, "get_loss: micro-batch %d has not been backwarded", mb_id);
-    HIPCHK(hipStreamSynchronize(st->stream));
+    HIPCHK(sync_streams(st));
     HIPCHK(hipMemcpy(loss_host, st->losses + mb_id, sizeof(float), hipMemcpyDeviceToHost));
     return BAPIPE_OK;
 }
@@ -1489,7 +1553,7 @@ int bapipe_stage_kernel_timing(bapipe_stage_t *st, int kernel_class)
 {
     if (!st) return BAPIPE_E_INVALID;
     if (kernel_class >= BAPIPE_KC_COUNT) return st->fail(BAPIPE_E_INVALID, "kernel_timing: class %d", kernel_class);
-    HIPCHK(hipStreamSynchronize(st->stream));
+    HIPCHK(sync_streams(st));
     if (kernel_class >= 0 && st->tap_events.empty()) {
         st->tap_events.resize(2 * 4096);
         for (auto &e : st->tap_events) HIPCHK(hipEventCreate(&e));
@@ -1505,7 +1569,7 @@ int bapipe_stage_kernel_timing_read(bapipe_stage_t *st, double *total_ms, uint64
                                     double *bytes)
 {
     if (!st) return BAPIPE_E_INVALID;
-    HIPCHK(hipStreamSynchronize(st->stream));
+    HIPCHK(sync_streams(st));
     double ms = 0.0;
     for (size_t i = 0; i + 1 < st->tap_used; i += 2) {
         float t = 0.f;

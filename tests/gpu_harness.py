@@ -48,7 +48,8 @@ def rel_err(got, ref):
 
 
 class GpuStage:
-    def __init__(self, stage, params, layout=B.NHWC, loss_scale=0.0, use_torch_alloc=True, stream=None):
+    def __init__(self, stage, params, layout=B.NHWC, loss_scale=0.0, use_torch_alloc=True, stream=None,
+                 backward_stream=False):
         self.stage = stage
         self.layout = layout
         self.alloc = B.TorchAllocator(DEV) if use_torch_alloc else None
@@ -63,6 +64,10 @@ class GpuStage:
                 B.bapipe_stage_set_params(self.h, i, w, b)
         self.keep = []
         self.is_loss = gen.ends_in_loss(stage)
+        self.bstream = None
+        if backward_stream:                       # backward passes on a stream of their own, beside later forwards
+            self.bstream = torch.cuda.Stream(device=DEV)
+            B.bapipe_stage_set_backward_stream(self.h, self.bstream.cuda_stream)
 
     def close(self):
         if self.h is not None:
@@ -88,7 +93,7 @@ class GpuStage:
         y = torch.empty(n, dtype=torch.float32 if self.is_loss else tdtype(self.stage), device=DEV)
         torch.cuda.synchronize()
         B.bapipe_stage_forward(self.h, mb, x.data_ptr(), y.data_ptr())
-        self.stream.synchronize()
+        torch.cuda.synchronize()
         return from_dev(y, self.out_shape(), self.layout)
 
     def backward(self, mb, dy_or_labels, want_dx=True, static=False):
@@ -102,7 +107,7 @@ class GpuStage:
         torch.cuda.synchronize()
         entry = B.bapipe_stage_backward_static if static else B.bapipe_stage_backward
         entry(self.h, mb, g.data_ptr(), None if dx is None else dx.data_ptr())
-        self.stream.synchronize()
+        torch.cuda.synchronize()
         return None if dx is None else from_dev(dx, self.in_shape(), self.layout)
 
     def grads(self, i):
@@ -128,12 +133,16 @@ def stage_io(stage):
     return xs, gs
 
 
-def gpu_minibatch(stage, static=False, layout=B.NHWC):
+def gpu_minibatch(stage, static=False, layout=B.NHWC, backward_stream=False, eager_sync=True):
     """One mini-batch in 1F1B order on the GPU alone: every output the library hands back (y and dx
-    per micro-batch, losses, all weight gradients), by name."""
+    per micro-batch, losses, all weight gradients), by name.  eager_sync=False enqueues the whole
+    mini-batch without waiting in between (inputs uploaded beforehand), so that passes really overlap
+    when there is a backward stream."""
     params = gen.all_params(stage, perturb=True)
     xs, gs = stage_io(stage)
-    g = GpuStage(stage, params, layout=layout)
+    g = GpuStage(stage, params, layout=layout, backward_stream=backward_stream)
+    if not eager_sync:
+        return _minibatch_enqueued_at_once(stage, g, params, xs, gs, static)
     _, depth = B.bapipe_stage_stash_bytes(g.h)
     out = {}
     for t, m in one_f_one_b_order(stage["n_micro"], depth):
@@ -145,6 +154,43 @@ def gpu_minibatch(stage, static=False, layout=B.NHWC):
                 out["dx%d" % m] = dx
             if g.is_loss:
                 out["loss%d" % m] = np.float64(B.bapipe_stage_get_loss(g.h, m))
+    for i, (w, b) in enumerate(params):
+        if w is not None:
+            dw, db = g.grads(i)
+            out["dw%d" % i] = dw
+            if db is not None:
+                out["db%d" % i] = db
+    g.close()
+    return out
+
+
+def _minibatch_enqueued_at_once(stage, g, params, xs, gs, static):
+    M = stage["n_micro"]
+    _, depth = B.bapipe_stage_stash_bytes(g.h)
+    dxs = [to_dev(stage, x, g.layout) for x in xs]
+    if g.is_loss:
+        dgs = [torch.from_numpy(np.ascontiguousarray(v, np.int32)).to(DEV) for v in gs]
+    else:
+        dgs = [to_dev(stage, v, g.layout) for v in gs]
+    n_out = int(np.prod(g.out_shape()))
+    ys = [torch.empty(n_out, dtype=torch.float32 if g.is_loss else tdtype(stage), device=DEV) for _ in range(M)]
+    need_dx = bool(stage["need_input_grad"])
+    dxo = [torch.empty(int(np.prod(g.in_shape())), dtype=tdtype(stage), device=DEV) if need_dx else None for _ in range(M)]
+    torch.cuda.synchronize()
+    entry = B.bapipe_stage_backward_static if static else B.bapipe_stage_backward
+    for t, m in one_f_one_b_order(M, depth):
+        if t == "F":
+            B.bapipe_stage_forward(g.h, m, dxs[m].data_ptr(), ys[m].data_ptr())
+        else:
+            entry(g.h, m, dgs[m].data_ptr(), dxo[m].data_ptr() if need_dx else None)
+    torch.cuda.synchronize()
+    out = {}
+    for m in range(M):
+        out["y%d" % m] = from_dev(ys[m], g.out_shape(), g.layout)
+        if need_dx:
+            out["dx%d" % m] = from_dev(dxo[m], g.in_shape(), g.layout)
+        if g.is_loss:
+            out["loss%d" % m] = np.float64(B.bapipe_stage_get_loss(g.h, m))
     for i, (w, b) in enumerate(params):
         if w is not None:
             dw, db = g.grads(i)
@@ -170,15 +216,18 @@ def pool_index_gap(layer_in, idx_ref, idx_gpu, L):
 
 
 def compare_minibatch(stage, layout=B.NHWC, perturb=True, order=None, lr=0.05, check_pool=True,
-                      tol=None, verbose=None):
+                      tol=None, verbose=None, dx_where_output_gates_agree=False, backward_stream=False):
     """Full parity of one mini-batch: y, dx per micro-batch, pool indices, loss, every weight
     gradient after M micro-batches and the updated weights after step.  Returns the worst
-    relative errors by tensor name."""
+    relative errors by tensor name.
+    dx_where_output_gates_agree: for stages of 1x1 layers ending in a fused ReLU (a pixel's input
+    gradient depends on that pixel's gates only): dx is compared at the pixels where the two sides'
+    output gates (y > 0) agree in every channel, and the share of disagreeing gates is bounded."""
     tol = TOL[stage["dtype"]] if tol is None else tol
     params = gen.all_params(stage, perturb=perturb)
     xs, gs = stage_io(stage)
     orc = OracleStage(stage, params)
-    gpu = GpuStage(stage, params, layout=layout)
+    gpu = GpuStage(stage, params, layout=layout, backward_stream=backward_stream)
     M = stage["n_micro"]
     order = order or one_f_one_b_order(M, orc.depth)
     per, depth = B.bapipe_stage_stash_bytes(gpu.h)
@@ -187,11 +236,16 @@ def compare_minibatch(stage, layout=B.NHWC, perturb=True, order=None, lr=0.05, c
     bf16 = stage["dtype"] == C.BF16
     pools = [i for i, L in enumerate(stage["layers"]) if L["kind"] == C.MAXPOOL2D]
     exact_pool = True
+    gate_ok = {}
     for t, m in order:
         if t == "F":
             y_ref = orc.forward(m, xs[m])
             y = gpu.forward(m, xs[m])
             errs["y%d" % m] = rel_err(y, y_ref)
+            if dx_where_output_gates_agree:
+                flipped = (y > 0) != (y_ref > 0)
+                assert np.mean(flipped) <= 1e-3, ("ReLU gates differ too often", m, float(np.mean(flipped)))
+                gate_ok[m] = ~np.any(flipped, axis=1)                # [n, h, w]
             if check_pool:
                 for li in pools:
                     ir, ig = orc.pool_indices(m, li), gpu.pool_indices(li, m)
@@ -200,20 +254,28 @@ def compare_minibatch(stage, layout=B.NHWC, perturb=True, order=None, lr=0.05, c
                         exact_pool = False
                         src = stage["layers"][li]["src0"]
                         xin = orc.stash[m][0] if src < 0 else orc.stash[m][1][src]
-                        # End to end the pool inputs of the two sides are only equal within the value
-                        # tolerance, so the arg-max is unique only up to that: where the indices differ
-                        # the oracle's two candidates must be closer than twice the tolerance the
-                        # tensor itself is held to.  (With identical inputs the indices are bit-exact:
-                        # see the pool-only stages in test_gpu_stage.py.)
+                        # End to end the pool inputs of the two sides are only equal up to the error the tensors
+                        # themselves show, so the arg-max is unique only up to that: where the indices differ the
+                        # oracle's two candidates must be no further apart than twice the error measured on this
+                        # micro-batch's output (at least one bf16 rounding step of the largest value), and such
+                        # windows must be rare.  (With identical inputs the indices are bit-exact: see the pool-only
+                        # stages in test_gpu_stage.py.)
                         gap, frac = pool_index_gap(xin, ir, ig, stage["layers"][li]), float(np.mean(ir != ig))
                         if verbose:
                             print("   pool layer %d mb %d: %.2e of windows differ, worst gap %.2e of max" % (li, m, frac, gap), flush=True)
-                        assert gap <= 2 * tol, ("pool arg-max differs beyond a tie", li, m, gap)
-                        assert frac < (1e-2 if bf16 else 1e-5), frac
+                        bound = max(2 * errs["y%d" % m], 2.0 ** -7) if bf16 else 1e-6
+                        assert gap <= bound, ("pool arg-max differs beyond a tie", li, m, gap, bound)
+                        assert frac <= (1e-3 if bf16 else 1e-5), frac
         else:
             dx_ref = orc.backward(m, gs[m])
             dx = gpu.backward(m, gs[m])
-            if dx_ref is not None:
+            if dx_ref is not None and dx_where_output_gates_agree:
+                assert dx.shape[2:] == gate_ok[m].shape[1:]
+                keep = np.broadcast_to(gate_ok[m][:, None], dx.shape)
+                errs["dx%d" % m] = float(np.max(np.abs(dx - dx_ref)[keep]) / np.max(np.abs(dx_ref)))
+                if verbose:
+                    print("   mb %d: dx compared at %.4f of the pixels" % (m, float(np.mean(gate_ok[m]))), flush=True)
+            elif dx_ref is not None:
                 errs["dx%d" % m] = rel_err(dx, dx_ref)
             if gpu.is_loss:
                 l_ref, l = orc.loss[m], B.bapipe_stage_get_loss(gpu.h, m)
