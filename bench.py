@@ -4,8 +4,8 @@
 A "step" is one mini-batch of the workload: M forward and M backward passes in 1F1B order
 (depth warm-up forwards, alternate B/F, drain) followed by the weight update, all enqueued
 through the C ABI without waiting in between - forward passes and the update on one HIP stream,
-backward passes on a second one (--streams 2, the default; the library orders them with events)
-so that they overlap the forward passes of later micro-batches; inputs and upstream gradients of
+backward passes on a second one and their weight-gradient kernels on a third (--streams 3, the
+default; the library orders them with events), so that independent kernels share the chip; inputs and upstream gradients of
 all M micro-batches are seeded synthetic tensors resident in HBM before the timed region.
 
 Prints ONE JSON line for the headline workload (default: VGG-16 stage 1): samples/s (value), ms per
@@ -103,10 +103,15 @@ class Workload:
         self.order = one_f_one_b(self.M, self.depth)
         # backward passes on a stream of their own, beside the forward passes of later micro-batches; a ring of
         # depth 1 leaves nothing to overlap
-        self.bstream = torch.cuda.Stream(device=dev) if streams == 2 and self.depth >= 2 else None
-        self.streams = 2 if self.bstream is not None else 1
-        if self.bstream is not None:
-            B.bapipe_stage_set_backward_stream(self.h, self.bstream.cuda_stream)
+        self.bstream = torch.cuda.Stream(device=dev) if streams >= 2 and self.depth >= 2 else None
+        self.wstream = torch.cuda.Stream(device=dev) if streams >= 3 and self.bstream is not None else None
+        self.streams = 1 + (self.bstream is not None) + (self.wstream is not None)
+        self.set_streams(True)
+
+    def set_streams(self, on):
+        bs = self.bstream.cuda_stream if on and self.bstream is not None else None
+        ws = self.wstream.cuda_stream if on and self.wstream is not None else None
+        self.B.bapipe_stage_set_streams(self.h, bs, ws)
 
     def step(self, lr=0.01):
         B, h = self.B, self.h
@@ -141,7 +146,7 @@ class Workload:
         # one stream for these steps: with kernels of two streams sharing the chip the event pair around a launch
         # would time both
         torch.cuda.synchronize()
-        B.bapipe_stage_set_backward_stream(h, None)
+        self.set_streams(False)
         names = dict(gather=B.KC_CONV_GATHER_MFMA, wgrad=B.KC_CONV_WGRAD_MFMA, direct=B.KC_CONV_DIRECT,
                      pool=B.KC_POOL, bn=B.KC_BATCHNORM, eltwise=B.KC_ELEMENTWISE)
         if tap == "auto":      # one untimed step per candidate, pick the class with the largest share
@@ -164,8 +169,7 @@ class Workload:
         ms = e0.elapsed_time(e1)
         r = B.bapipe_stage_kernel_timing_read(h)
         B.bapipe_stage_kernel_timing(h, -1)
-        if self.bstream is not None:
-            B.bapipe_stage_set_backward_stream(h, self.bstream.cuda_stream)
+        self.set_streams(self.streams > 1)
         sec = r["total_ms"] * 1e-3
         mfma_meas, copy_meas = peaks
         other = None
@@ -226,8 +230,9 @@ def main():
     ap.add_argument("--workload", default="vgg16_stage1", choices=sorted(C.FULL))
     ap.add_argument("--tap", default="auto", help="kernel class for the roofline tap: auto|gather|wgrad|direct|pool|bn|eltwise")
     ap.add_argument("--tap-steps", type=int, default=3, help="extra steps run under the event tap for the roofline object")
-    ap.add_argument("--streams", type=int, default=2, choices=[1, 2],
-                    help="2: backward passes on their own stream beside later forward passes (where the ring is deeper than 1)")
+    ap.add_argument("--streams", type=int, default=3, choices=[1, 2, 3],
+                    help="2: backward passes on their own stream beside later forward passes (where the ring is deeper "
+                         "than 1); 3: also their weight-gradient kernels on a stream of their own")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-per-config", action="store_true", help="time only the headline workload")
     ap.add_argument("--no-peaks", action="store_true", help="skip the measured-peak microbenchmarks")
@@ -306,13 +311,13 @@ def main():
                 # both ways: a stage whose kernels are a few microseconds long can lose more to the event hand-overs
                 # between the streams than the overlap returns
                 torch.cuda.synchronize()
-                B.bapipe_stage_set_backward_stream(wl.h, None)
+                wl.set_streams(False)
                 o_ms, o_steps, _ = wl.timed(steps, 1)
                 one = round(o_ms / steps, 4)
                 if o_ms < t_ms:
                     t_ms, t_steps, wl.streams = o_ms, o_steps, 1
                 else:
-                    B.bapipe_stage_set_backward_stream(wl.h, wl.bstream.cuda_stream)
+                    wl.set_streams(True)
             rec = wl.summary(t_ms, t_steps, steps)
             if wl.bstream is not None:
                 rec["ms_per_step_one_stream"] = one

@@ -148,23 +148,34 @@ int bapipe_stage_forward(bapipe_stage_t *st, int mb_id, const void *x_dev, void 
 int bapipe_stage_backward(bapipe_stage_t *st, int mb_id, const void *dy_dev_or_labels,
                           void *dx_dev);
 
-/* Overlap of forward and backward passes.  In the 1F1B steady state the forward pass of one
- * micro-batch and the backward pass of an earlier one alternate (Sec. III-B-1) and do not depend
- * on each other: they touch different ring slots, and weights only change in the update.  By
- * default the library still runs them one after the other, on opts->hip_stream.  With a second
- * stream (caller-owned, same device, default priority) every backward pass is enqueued on it
- * instead, so that its kernels run beside those of later forward passes and fill the idle compute
- * units each kernel leaves while it ramps up and drains.  The library orders the two streams with
- * events: backward(m) starts after forward(m); forward(m + depth), which reuses the ring slot of
- * micro-batch m, after backward(m); bapipe_stage_step after the last backward pass; the get_* /
- * set_* calls synchronise both streams.  Results are the same bit for bit.  What changes for the
- * caller: dx_dev and the loss of a micro-batch are complete when the BACKWARD stream has run the
- * pass, and dy_dev_or_labels must be complete on (or before) that stream.  A stage with a ring of
- * depth 1 cannot overlap anything and only pays for the event hand-overs.
- * hip_stream_backward = NULL (or opts->hip_stream) returns to one stream.  Only between
- * mini-batches (after create or step), else E_ORDER.  The first call with a stream allocates a
- * second kernel workspace and 2 M events through opts->mem / HIP: E_OOM, E_DEVICE. */
-int bapipe_stage_set_backward_stream(bapipe_stage_t *st, void *hip_stream_backward);
+/* Overlap of independent work on further streams.  By default every kernel is enqueued on
+ * opts->hip_stream, one after the other.  Two kinds of work do not depend on each other:
+ *  - In the 1F1B steady state the forward pass of one micro-batch and the backward pass of an
+ *    earlier one alternate (Sec. III-B-1): they touch different ring slots, and weights only
+ *    change in the update.  With hip_stream_backward every backward pass is enqueued on that
+ *    stream instead, beside the forward passes of later micro-batches.
+ *  - Inside a backward pass a layer's weight gradient needs the layer's output gradient and its
+ *    stashed input, nothing the remaining input-gradient kernels produce.  With
+ *    hip_stream_wgrad the weight-gradient kernels of conv layers are enqueued on that stream,
+ *    beside the input-gradient chain.
+ * Kernels of different streams share the compute units, so each fills what the others leave
+ * idle while they ramp up, drain, or wait for memory.  Both streams are caller-owned, on the
+ * stage's device, of default priority, and distinct from each other and from opts->hip_stream;
+ * either may be NULL (that kind of work then stays where it was).  The library orders the streams
+ * with events: backward(m) starts after forward(m); forward(m + depth), which reuses the ring
+ * slot of micro-batch m, after backward(m); a weight-gradient kernel after the kernels that
+ * complete its layer's output gradient; the backward pass's own stream waits for the pass's
+ * weight-gradient kernels before the pass counts as complete; bapipe_stage_step runs after the
+ * last backward pass; get_* / set_* / profile calls synchronise all streams.  Results are the same
+ * bit for bit.  What changes for the caller: dx_dev and the loss of a micro-batch are complete
+ * when the stream of the BACKWARD passes has run the pass, and dy_dev_or_labels must be complete
+ * on (or before) that stream and stay untouched until then.  A stage with a ring of depth 1
+ * cannot overlap passes and only pays for the event hand-overs of a backward stream.
+ * bapipe_stage_backward_static keeps its weight-gradient kernels on the pass's stream (there is
+ * one static workspace).  Only between mini-batches (after create or step), else E_ORDER.  The
+ * first use of each stream allocates one more kernel workspace through opts->mem and a few
+ * events: E_OOM, E_DEVICE.  E_INVALID if hip_stream_wgrad equals one of the other streams. */
+int bapipe_stage_set_streams(bapipe_stage_t *st, void *hip_stream_backward, void *hip_stream_wgrad);
 
 /* bapipe_stage_backward for callers that must not allocate device memory while they run (code
  * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): same arguments,

@@ -21,7 +21,7 @@ STATIC_SCRATCH_BYTES = 64 << 20
 
 EXPORTS = [
     "bapipe_stage_create", "bapipe_stage_forward", "bapipe_stage_backward", "bapipe_stage_backward_static",
-    "bapipe_stage_set_backward_stream",
+    "bapipe_stage_set_streams",
     "bapipe_stage_step",
     "bapipe_profile_layers", "bapipe_profile_sweep", "bapipe_stage_set_params", "bapipe_stage_get_params",
     "bapipe_stage_get_grads", "bapipe_stage_get_pool_indices", "bapipe_stage_get_loss",
@@ -83,7 +83,7 @@ def load():
     lib.bapipe_stage_forward.argtypes = [vp, i32, vp, vp]
     lib.bapipe_stage_backward.argtypes = [vp, i32, vp, vp]
     lib.bapipe_stage_backward_static.argtypes = [vp, i32, vp, vp]
-    lib.bapipe_stage_set_backward_stream.argtypes = [vp, vp]
+    lib.bapipe_stage_set_streams.argtypes = [vp, vp, vp]
     lib.bapipe_stage_step.argtypes = [vp, ct.c_float]
     lib.bapipe_profile_layers.argtypes = [vp, i32, i32, ct.POINTER(LayerProfile), i32, ct.POINTER(i32)]
     fp = ct.POINTER(ct.c_float)
@@ -175,8 +175,8 @@ def bapipe_stage_backward_static(h, mb_id, dy_or_labels_ptr, dx_ptr):
     _check(load().bapipe_stage_backward_static(h, mb_id, dy_or_labels_ptr, dx_ptr), h)
 
 
-def bapipe_stage_set_backward_stream(h, stream):
-    _check(load().bapipe_stage_set_backward_stream(h, stream), h)
+def bapipe_stage_set_streams(h, backward_stream, wgrad_stream):
+    _check(load().bapipe_stage_set_streams(h, backward_stream, wgrad_stream), h)
 
 
 def bapipe_stage_step(h, lr):

@@ -101,11 +101,18 @@ struct bapipe_stage {
     int mb = 0, M = 0, depth = 0;
     float loss_scale = 0.f;
     hipStream_t stream = nullptr;
-    // with a backward stream (bapipe_stage_set_backward_stream) the backward passes run beside the forward passes of
+    // with a backward stream (bapipe_stage_set_streams) the backward passes run beside the forward passes of
     // later micro-batches: stream_f / work_f are the handle's own stream and workspace, stream_b / work_b those of the
     // backward passes, `stream` / `work` whichever the pass being enqueued uses.  Events order the two:
     // forward m -> backward m (its features), backward m -> forward m + depth (which reuses its ring slot)
     hipStream_t stream_f = nullptr, stream_b = nullptr;
+    // with a weight-gradient stream the wgrad kernels of a backward pass run beside its input-gradient kernels (they
+    // only need the layer's output gradient, marked by ev_g, and stashed features); the pass's own stream waits for
+    // them at the end of the pass (ev_w_end), so "pass complete" keeps covering them
+    hipStream_t stream_w = nullptr;
+    char *work_w = nullptr;
+    hipEvent_t ev_g = nullptr, ev_w_end = nullptr;
+    bool w_used = false;
     char *work_f = nullptr, *work_b = nullptr;
     std::vector<hipEvent_t> ev_fwd, ev_bwd;
     // arenas
@@ -126,9 +133,11 @@ struct bapipe_stage {
     size_t tap_used = 0;
     double tap_flop = 0.0, tap_bytes = 0.0;
     size_t tap_dropped = 0;                  // launches of the class that found no event pair (pool limit reached)
-    bool tap_begin(int cls)
+    hipStream_t tap_stream = nullptr;        // stream of the launch being bracketed
+    bool tap_begin(int cls, hipStream_t on = nullptr)
     {
         if (cls != tap_class) return false;
+        tap_stream = on ? on : stream;
         if (tap_used + 2 > tap_events.size()) {              // grow the pool: host-side objects only
             const size_t grow = 2 * 1024;
             if (tap_events.size() + grow > kTapMaxEvents) { ++tap_dropped; return false; }
@@ -138,13 +147,13 @@ struct bapipe_stage {
                 tap_events.push_back(e);
             }
         }
-        (void)hipEventRecord(tap_events[tap_used], stream);
+        (void)hipEventRecord(tap_events[tap_used], tap_stream);
         return true;
     }
     void tap_end(bool on, double flop, double bytes)
     {
         if (!on) return;
-        (void)hipEventRecord(tap_events[tap_used + 1], stream);
+        (void)hipEventRecord(tap_events[tap_used + 1], tap_stream);
         tap_used += 2;
         tap_flop += flop;
         tap_bytes += bytes;
@@ -206,6 +215,7 @@ hipError_t sync_streams(bapipe_stage *st)
 {
     hipError_t e = hipStreamSynchronize(st->stream);
     if (e == hipSuccess && st->stream_b) e = hipStreamSynchronize(st->stream_b);
+    if (e == hipSuccess && st->stream_w) e = hipStreamSynchronize(st->stream_w);
     return e;
 }
 
@@ -634,9 +644,19 @@ int layer_backward(bapipe_stage *st, int li, BwdCtx &c)
             HIPCHK(hipMemcpyAsync(L.def_g + (size_t)c.mbid * L.def_g_bytes, g, L.def_g_bytes, hipMemcpyDeviceToDevice, s));
         } else {
             const bool mf = use_mfma_wgrad(st, cs);
-            const bool tp = st->tap_begin(mf ? BAPIPE_KC_CONV_WGRAD_MFMA : BAPIPE_KC_CONV_DIRECT);
+            const bool side = mf && st->stream_w && !c.profiling;
+            hipStream_t ws = s;
+            char *wwork = st->work;
+            if (side) {                                   // g is complete on the backward stream at this point
+                HIPCHK(hipEventRecord(st->ev_g, s));
+                HIPCHK(hipStreamWaitEvent(st->stream_w, st->ev_g, 0));
+                ws = st->stream_w;
+                wwork = st->work_w;
+                st->w_used = true;
+            }
+            const bool tp = st->tap_begin(mf ? BAPIPE_KC_CONV_WGRAD_MFMA : BAPIPE_KC_CONV_DIRECT, ws);
             if (mf)
-                HIPCHK(conv_wgrad_mfma(x, g, L.dw, L.db, st->work, cs, s));      // bias gradient rides along
+                HIPCHK(conv_wgrad_mfma(x, g, L.dw, L.db, wwork, cs, ws));      // bias gradient rides along
             else
                 HIPCHK(conv_wgrad_direct(dt, x, g, L.dw, st->work, cs, s));
             st->tap_end(tp, flop, (double)A.bytes() + O.bytes() + 8.0 * L.w_elems);   // x, dy read; fp32 dw read and written
@@ -832,6 +852,10 @@ void bapipe_stage_destroy(bapipe_stage_t *st)
     for (hipEvent_t e : st->ev_fwd) if (e) (void)hipEventDestroy(e);
     for (hipEvent_t e : st->ev_bwd) if (e) (void)hipEventDestroy(e);
     st->dev_free(st->work_b);
+    if (st->stream_w) (void)hipStreamSynchronize(st->stream_w);
+    if (st->ev_g) (void)hipEventDestroy(st->ev_g);
+    if (st->ev_w_end) (void)hipEventDestroy(st->ev_w_end);
+    st->dev_free(st->work_w);
     st->dev_free(st->params);
     st->dev_free(st->stash);
     st->dev_free(st->transient);
@@ -1367,37 +1391,51 @@ int bapipe_stage_backward(bapipe_stage_t *st, int mb_id, const void *dy_dev_or_l
             HIPCHK(nhwc_to_nchw(dt, st->gptr(0), dx_dev, st->mb, In.C, In.H, In.W, In.Cp, s));
     }
     if (c.labels) st->loss_valid[mb_id] = 1;
+    if (st->w_used) {                                   // the pass is complete when its weight-gradient kernels are
+        HIPCHK(hipEventRecord(st->ev_w_end, st->stream_w));
+        HIPCHK(hipStreamWaitEvent(s, st->ev_w_end, 0));
+        st->w_used = false;
+    }
     if (st->stream_b) HIPCHK(hipEventRecord(st->ev_bwd[mb_id], s));
     st->n_bwd++;
     return BAPIPE_OK;
 }
 
-int bapipe_stage_set_backward_stream(bapipe_stage_t *st, void *hip_stream_backward)
+int bapipe_stage_set_streams(bapipe_stage_t *st, void *hip_stream_backward, void *hip_stream_wgrad)
 {
     if (!st) return BAPIPE_E_INVALID;
     if (st->n_fwd != 0 || st->n_bwd != 0)
-        return st->fail(BAPIPE_E_ORDER, "set_backward_stream: only between mini-batches (after create or step)");
+        return st->fail(BAPIPE_E_ORDER, "set_streams: only between mini-batches (after create or step)");
     HIPCHK(sync_streams(st));
-    hipStream_t sb = (hipStream_t)hip_stream_backward;
-    if (!sb || sb == st->stream_f) {
-        st->stream_b = nullptr;                   // workspace and events stay for the next time
-        return BAPIPE_OK;
-    }
-    if (!st->work_b) {
+    hipStream_t sb = (hipStream_t)hip_stream_backward, sw = (hipStream_t)hip_stream_wgrad;
+    if (sb == st->stream_f) sb = nullptr;
+    if (sw && (sw == st->stream_f || sw == sb))
+        return st->fail(BAPIPE_E_INVALID, "set_streams: the weight-gradient stream must differ from the other streams");
+    // workspaces and events are created on first use and stay for the next time
+    if (sb && !st->work_b) {
         st->work_b = (char *)st->dev_alloc(st->work_bytes);
-        if (!st->work_b) return st->fail(BAPIPE_E_OOM, "set_backward_stream: %zu bytes of workspace", st->work_bytes);
+        if (!st->work_b) return st->fail(BAPIPE_E_OOM, "set_streams: %zu bytes of workspace", st->work_bytes);
     }
-    if (st->ev_fwd.empty()) {
+    if (sw && !st->work_w) {
+        st->work_w = (char *)st->dev_alloc(st->work_bytes);
+        if (!st->work_w) return st->fail(BAPIPE_E_OOM, "set_streams: %zu bytes of workspace", st->work_bytes);
+    }
+    if (sb && st->ev_fwd.empty()) {
         std::vector<hipEvent_t> ev(2 * (size_t)st->M, nullptr);
         for (auto &e : ev)
             if (hipEventCreateWithFlags(&e, hipEventDisableTiming) != hipSuccess) {
                 for (hipEvent_t d : ev) if (d) (void)hipEventDestroy(d);
-                return st->fail(BAPIPE_E_DEVICE, "set_backward_stream: hipEventCreate failed");
+                return st->fail(BAPIPE_E_DEVICE, "set_streams: hipEventCreate failed");
             }
         st->ev_fwd.assign(ev.begin(), ev.begin() + st->M);
         st->ev_bwd.assign(ev.begin() + st->M, ev.end());
     }
+    if (sw && !st->ev_g) {
+        HIPCHK(hipEventCreateWithFlags(&st->ev_g, hipEventDisableTiming));
+        HIPCHK(hipEventCreateWithFlags(&st->ev_w_end, hipEventDisableTiming));
+    }
     st->stream_b = sb;
+    st->stream_w = sw;
     return BAPIPE_OK;
 }
 
@@ -1412,9 +1450,12 @@ int bapipe_stage_backward_static(bapipe_stage_t *st, int mb_id, const void *dy_d
     // every kernel of the backward pass writes its partial results before a later kernel of the same pass reads
     // them (no atomics, nothing accumulates in the workspace), so what the previous call left there needs no clearing
     char *own_f = st->work_f, *own_b = st->work_b;
+    hipStream_t own_w = st->stream_w;
     st->work = st->work_f = ws;
     if (st->work_b) st->work_b = ws;
+    st->stream_w = nullptr;              // one array: the weight-gradient kernels of this pass stay on the pass's stream
     const int rc = bapipe_stage_backward(st, mb_id, dy_dev_or_labels, dx_dev);
+    st->stream_w = own_w;
     st->work_f = own_f;
     st->work_b = own_b;
     st->work = own_f;

@@ -49,7 +49,7 @@ def rel_err(got, ref):
 
 class GpuStage:
     def __init__(self, stage, params, layout=B.NHWC, loss_scale=0.0, use_torch_alloc=True, stream=None,
-                 backward_stream=False):
+                 backward_stream=False, wgrad_stream=False):
         self.stage = stage
         self.layout = layout
         self.alloc = B.TorchAllocator(DEV) if use_torch_alloc else None
@@ -64,10 +64,14 @@ class GpuStage:
                 B.bapipe_stage_set_params(self.h, i, w, b)
         self.keep = []
         self.is_loss = gen.ends_in_loss(stage)
-        self.bstream = None
-        if backward_stream:                       # backward passes on a stream of their own, beside later forwards
+        self.bstream = self.wstream = None
+        if backward_stream:       # backward passes, and their weight-gradient kernels, on streams of their own
             self.bstream = torch.cuda.Stream(device=DEV)
-            B.bapipe_stage_set_backward_stream(self.h, self.bstream.cuda_stream)
+            self.wstream = torch.cuda.Stream(device=DEV) if backward_stream != "no wgrad stream" else None
+            B.bapipe_stage_set_streams(self.h, self.bstream.cuda_stream, None if self.wstream is None else self.wstream.cuda_stream)
+        elif wgrad_stream:
+            self.wstream = torch.cuda.Stream(device=DEV)
+            B.bapipe_stage_set_streams(self.h, None, self.wstream.cuda_stream)
 
     def close(self):
         if self.h is not None:
@@ -133,14 +137,14 @@ def stage_io(stage):
     return xs, gs
 
 
-def gpu_minibatch(stage, static=False, layout=B.NHWC, backward_stream=False, eager_sync=True):
+def gpu_minibatch(stage, static=False, layout=B.NHWC, backward_stream=False, eager_sync=True, wgrad_stream=False):
     """One mini-batch in 1F1B order on the GPU alone: every output the library hands back (y and dx
     per micro-batch, losses, all weight gradients), by name.  eager_sync=False enqueues the whole
     mini-batch without waiting in between (inputs uploaded beforehand), so that passes really overlap
     when there is a backward stream."""
     params = gen.all_params(stage, perturb=True)
     xs, gs = stage_io(stage)
-    g = GpuStage(stage, params, layout=layout, backward_stream=backward_stream)
+    g = GpuStage(stage, params, layout=layout, backward_stream=backward_stream, wgrad_stream=wgrad_stream)
     if not eager_sync:
         return _minibatch_enqueued_at_once(stage, g, params, xs, gs, static)
     _, depth = B.bapipe_stage_stash_bytes(g.h)

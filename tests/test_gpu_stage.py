@@ -469,7 +469,7 @@ def test_same_mini_batch_twice_is_bit_identical(name, stage):
         assert np.array_equal(a[k], b[k]), (name, k)
 
 
-# ------------------------------------------------------------------------------ backward passes on a second stream
+# ------------------------------------------------------------------------------ overlap on further streams
 OVERLAP_STAGES = [
     ("vgg16_stage1 64/128 channels", lambda: C.vgg16_stage1(c1=64, c2=128, hw=32, micro_batch=3, n_micro=6)),      # depth 4
     ("vgg16_deep 256 channels", lambda: C.vgg16_deep(cin=128, c=256, hw=12, micro_batch=5, n_micro=4)),            # depth 2
@@ -480,36 +480,41 @@ OVERLAP_STAGES = [
 
 
 @pytest.mark.parametrize("name,make", OVERLAP_STAGES)
-def test_backward_stream_gives_the_same_results_bit_for_bit(name, make):
-    """A whole mini-batch enqueued at once with the backward passes on their own stream (they overlap the forward
-    passes of later micro-batches, ring slots are reused) against the same mini-batch on one stream."""
+def test_further_streams_give_the_same_results_bit_for_bit(name, make):
+    """A whole mini-batch enqueued at once with the backward passes and their weight-gradient kernels on streams of
+    their own (passes overlap the forward passes of later micro-batches, ring slots are reused) against the same
+    mini-batch on one stream; also each stream alone, and the static-workspace entry point."""
     from gpu_harness import gpu_minibatch
     ref = gpu_minibatch(make())
-    for static in (False, True):
-        got = gpu_minibatch(make(), backward_stream=True, eager_sync=False, static=static)
+    for kw in (dict(backward_stream=True), dict(backward_stream=True, static=True), dict(backward_stream="no wgrad stream"),
+               dict(wgrad_stream=True)):
+        got = gpu_minibatch(make(), eager_sync=False, **kw)
         assert sorted(got) == sorted(ref)
         for k in ref:
-            assert np.array_equal(got[k], ref[k]), (name, static, k)
+            assert np.array_equal(got[k], ref[k]), (name, kw, k)
 
 
-def test_backward_stream_against_the_oracle_and_its_call_rules():
+def test_further_streams_against_the_oracle_and_their_call_rules():
     st = C.resnet50_stage(cin=16, mid3=8, mid4=16, hw=12, n3=2, n4=2, micro_batch=4, n_micro=4)
-    compare_minibatch(st, backward_stream=True, verbose="two streams, resnet blocks")
-    compare_minibatch(C.vgg16_stage1(c1=16, c2=24, hw=20, micro_batch=3, n_micro=5), backward_stream=True, verbose="two streams, vgg stage 1")
+    compare_minibatch(st, backward_stream=True, verbose="three streams, resnet blocks")
+    compare_minibatch(C.vgg16_stage1(c1=16, c2=24, hw=20, micro_batch=3, n_micro=5), backward_stream=True, verbose="three streams, vgg stage 1")
     import torch
     g = GpuStage(st, gen.all_params(st))
-    side = torch.cuda.Stream(device="cuda:0")
+    side, side2 = torch.cuda.Stream(device="cuda:0"), torch.cuda.Stream(device="cuda:0")
     xs, gs = stage_io(st)
     g.forward(0, xs[0])
     with pytest.raises(B.BapipeError) as e:                      # not in the middle of a mini-batch
-        B.bapipe_stage_set_backward_stream(g.h, side.cuda_stream)
+        B.bapipe_stage_set_streams(g.h, side.cuda_stream, None)
     assert e.value.status == B.E_ORDER
     g.backward(0, gs[0])
     for m in range(1, 4):
         g.forward(m, xs[m])
         g.backward(m, gs[m])
     B.bapipe_stage_step(g.h, 0.1)
-    B.bapipe_stage_set_backward_stream(g.h, side.cuda_stream)    # between mini-batches: on, off, on again
-    B.bapipe_stage_set_backward_stream(g.h, None)
-    B.bapipe_stage_set_backward_stream(g.h, side.cuda_stream)
+    with pytest.raises(B.BapipeError) as e:                      # the two streams must differ
+        B.bapipe_stage_set_streams(g.h, side.cuda_stream, side.cuda_stream)
+    assert e.value.status == B.E_INVALID
+    B.bapipe_stage_set_streams(g.h, side.cuda_stream, side2.cuda_stream)    # between mini-batches: on, off, on again
+    B.bapipe_stage_set_streams(g.h, None, None)
+    B.bapipe_stage_set_streams(g.h, side.cuda_stream, None)
     g.close()
