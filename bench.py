@@ -71,9 +71,9 @@ def cpu_baseline(stage, sample):
 class Workload:
     """One stage created through the C ABI with its seeded inputs resident in HBM."""
 
-    def __init__(self, name, torch, B, dev="cuda:0", streams=2):
+    def __init__(self, name, torch, B, dev="cuda:0", streams=3, **shape):
         self.name, self.torch, self.B = name, torch, B
-        self.stage = stage = C.FULL[name]()
+        self.stage = stage = C.FULL[name](**shape)
         self.M, self.mb = stage["n_micro"], stage["micro_batch"]
         tdt = torch.bfloat16 if stage["dtype"] == C.BF16 else torch.float32
         is_loss = gen.ends_in_loss(stage)
@@ -233,6 +233,8 @@ def main():
     ap.add_argument("--streams", type=int, default=3, choices=[1, 2, 3],
                     help="2: backward passes on their own stream beside later forward passes (where the ring is deeper "
                          "than 1); 3: also their weight-gradient kernels on a stream of their own")
+    ap.add_argument("--micro-batch", type=int, default=0, help="override the workload's micro-batch size (a different workload: say so)")
+    ap.add_argument("--n-micro", type=int, default=0, help="override the workload's number of micro-batches per mini-batch")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-per-config", action="store_true", help="time only the headline workload")
     ap.add_argument("--no-peaks", action="store_true", help="skip the measured-peak microbenchmarks")
@@ -258,7 +260,12 @@ def main():
     if not a.no_peaks:
         peaks = B.bapipe_measure_peaks(torch.cuda.current_stream().cuda_stream)
 
-    w = Workload(a.workload, torch, B, dev, a.streams)
+    shape = {}
+    if a.micro_batch:
+        shape["micro_batch"] = a.micro_batch
+    if a.n_micro:
+        shape["n_micro"] = a.n_micro
+    w = Workload(a.workload, torch, B, dev, a.streams, **shape)
     stage = w.stage
 
     if a.profile_layers:

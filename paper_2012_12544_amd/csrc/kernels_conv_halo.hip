@@ -886,7 +886,11 @@ WgHaloPlan wg_halo_plan(const ConvShape &c)
     WgHaloPlan p;
     p.tiles = (c.K / 64) * (c.C / 64);
     const int U = c.N * (c.H / UH) * (c.W / UW);
-    int want = (512 + p.tiles - 1) / p.tiles;
+    // One block per compute unit: every block writes a full fp32 copy of its tile, so the traffic of the partial
+    // sums grows with the block count (at 512 blocks it was a ninth of the first VGG stage's HBM bytes), and a
+    // second block per unit made the kernel only 5 % faster on its own; beside kernels of other streams fewer,
+    // longer blocks are the better neighbour.
+    int want = (256 + p.tiles - 1) / p.tiles;
     if (want > U) want = U;
     if (want < 1) want = 1;
     p.units_per_split = (U + want - 1) / want;
@@ -957,7 +961,11 @@ static WgHaloPlan wg_c8_plan(const ConvShape &c)
     WgHaloPlan p;
     p.tiles = c.K / 64;
     const int U = c.N * (c.H / UH) * (c.W / UW);
-    int want = (512 + p.tiles - 1) / p.tiles;
+    // One block per compute unit: every block writes a full fp32 copy of its tile, so the traffic of the partial
+    // sums grows with the block count (at 512 blocks it was a ninth of the first VGG stage's HBM bytes), and a
+    // second block per unit made the kernel only 5 % faster on its own; beside kernels of other streams fewer,
+    // longer blocks are the better neighbour.
+    int want = (256 + p.tiles - 1) / p.tiles;
     if (want > U) want = U;
     if (want < 1) want = 1;
     p.units_per_split = (U + want - 1) / want;

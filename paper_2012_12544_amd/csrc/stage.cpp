@@ -644,7 +644,9 @@ int layer_backward(bapipe_stage *st, int li, BwdCtx &c)
             HIPCHK(hipMemcpyAsync(L.def_g + (size_t)c.mbid * L.def_g_bytes, g, L.def_g_bytes, hipMemcpyDeviceToDevice, s));
         } else {
             const bool mf = use_mfma_wgrad(st, cs);
-            const bool side = mf && st->stream_w && !c.profiling;
+            // a layer without an input gradient ends the pass's kernel chain: its weight gradient would only delay
+            // the end of the pass from the other stream
+            const bool side = mf && st->stream_w && !c.profiling && a_grad;
             hipStream_t ws = s;
             char *wwork = st->work;
             if (side) {                                   // g is complete on the backward stream at this point
