@@ -22,15 +22,28 @@ __device__ __forceinline__ int swz8(int row) { return (row >> 1) & 7; }
 
 constexpr int PATCH = 16, HALO = 18, HPIX = HALO * HALO;       // 324 halo pixels
 constexpr int HL = 11;                                          // halo wave-loads per wave (44 x 64 slots >= 2592)
-constexpr int HALO_ELEMS = HL * 4 * 64 * 8;                     // bf16 elements reserved for the halo tile
+// Per output-channel tile width.  128 channels: filter steps of 32 input channels through a ring of three 8 KB
+// stages, two blocks per CU (the 128 accumulator registers of a lane leave no room for a third).  64 channels:
+// steps of 32 channels too (4 KB stages), a ring of two, and exactly the 41 wave-loads that hold halo pixels, so
+// that a block needs 50.4 KB of LDS (40 allocation granules of 1280 bytes) and at most 168 registers and THREE
+// blocks share a CU: these layers have little arithmetic per block (one 64-channel slice), a block spends most of
+// its life fetching its halo and storing its patch, and the third block is what overlaps that.  Measured on the
+// 64 -> 64 layer at 224 x 224: forward 171 -> 155 us, forward + pool 180 -> 142 us, input gradient 240 -> 207 us.
+template <int BC> struct halo_cfg {
+    static constexpr int KS = 32;                                  // input channels per filter step
+    static constexpr int WS = BC == 64 ? 2 : 3;                    // ring stages
+    static constexpr int LOADS = BC == 64 ? 41 : HL * 4;           // wave-loads that hold halo pixels (41 x 64 slots >= 2592)
+    static constexpr int ELEMS = LOADS * 64 * 8;                   // bf16 elements reserved for the halo tile
+    static constexpr int BLOCKS_PER_CU = BC == 64 ? 3 : 2;
+};
 
-// Filter tiles stream through a ring of three 8 KB stages: one "step" is one tap x KS input channels
-// (KS = 64 for BC = 64, 32 for BC = 128), i.e. NSUB = KS/16 MFMA sub-steps.  The taps of a slice are
+// Filter tiles stream through the ring: one "step" is one tap x KS = 32 input channels, i.e. NSUB = 2 MFMA
+// sub-steps, and a stage holds BC x 32 filter values.  The taps of a slice are
 // unrolled, so ring slots, halo rows and swizzles are compile-time or precomputed per tap: a fragment
 // read costs at most one XOR.  Fragments are double-buffered in registers and the barrier that
 // publishes the next filter tile sits before the last sub-step of a step, as in the gather kernel.
 template <int BC>
-__global__ __launch_bounds__(256, 2) void k_conv3x3_halo(const bf16_t *__restrict__ in, const bf16_t *__restrict__ wt,
+__global__ __launch_bounds__(256, halo_cfg<BC>::BLOCKS_PER_CU) void k_conv3x3_halo(const bf16_t *__restrict__ in, const bf16_t *__restrict__ wt,
                                                          const float *__restrict__ bias, bf16_t *out,
                                                          const bf16_t *__restrict__ gate, int accum, int relu,
                                                          int is_grad, int N, int H, int W, int Ci, int Co,
@@ -38,18 +51,19 @@ __global__ __launch_bounds__(256, 2) void k_conv3x3_halo(const bf16_t *__restric
                                                          bf16_t *__restrict__ pool_out, uint8_t *__restrict__ pool_idx)
 {
     constexpr int NW = 4;
-    constexpr int KS = BC == 64 ? 64 : 32;     // input channels per filter step tile
+    constexpr int KS = halo_cfg<BC>::KS;       // input channels per filter step tile
+    constexpr int HALO_LOADS = halo_cfg<BC>::LOADS, HALO_ELEMS = halo_cfg<BC>::ELEMS;
     constexpr int NSUB = KS / 16;              // MFMA sub-steps per step
     constexpr int SPT = 64 / KS;               // steps per tap and 64-channel slice
     constexpr int SPS = 9 * SPT;               // steps per slice (a multiple of WS)
-    constexpr int WS = 3;                      // ring stages
-    constexpr int WT_ELEMS = BC * KS;          // 4096 elements = 8 KB
+    constexpr int WS = halo_cfg<BC>::WS;       // ring stages
+    constexpr int WT_ELEMS = BC * KS;          // 4096 elements = 8 KB (2048 = 4 KB for 64 channels x 32)
     constexpr int CPR = KS / 8;                // 16-byte chunks per filter-tile row
-    constexpr int WLD = 2;                     // filter wave-loads per wave and step (512 slots / 64 / 4)
+    constexpr int WLD = WT_ELEMS / 8 / 256;    // filter wave-loads per wave and step (512 or 256 slots / 64 / 4)
     constexpr int TC = BC / 32, TP = 2;        // wave tile: BC channels x 64 pixels
     constexpr int SROW = BC + 4;
     constexpr unsigned OOB = 0x80000000u;
-    static_assert(WT_ELEMS == 4096 && SPS % WS == 0, "ring layout");
+    static_assert((WT_ELEMS == 4096 || WT_ELEMS == 2048) && SPS % WS == 0, "ring layout");
 
     extern __shared__ __align__(16) unsigned char smem[];
     const lds_addr_of lds_of(smem);
@@ -85,7 +99,7 @@ __global__ __launch_bounds__(256, 2) void k_conv3x3_halo(const bf16_t *__restric
             const int y = Y0 - 1 + hy, x = X0 - 1 + hx;
             const bool ok = hr < HPIX && (unsigned)y < (unsigned)H && (unsigned)x < (unsigned)W;
             unsigned vo = ok ? ((unsigned)((n * H + y) * W + x) * (unsigned)Ci + (unsigned)(slice * 64 + c * 8)) * 2u : OOB;
-            dma16(xrsrc, lds_of(halo + (i * NW + wave) * 512), vo);
+            if (i * NW + wave < HALO_LOADS) dma16(xrsrc, lds_of(halo + (i * NW + wave) * 512), vo);
         }
     };
     // filter tile rows are KS elements long; chunk index XORed with swz8(row) (KS = 64) or bits 2..3 of
@@ -162,7 +176,7 @@ __global__ __launch_bounds__(256, 2) void k_conv3x3_halo(const bf16_t *__restric
     // under the main loop instead of after the last MFMA
     constexpr int CH8 = BC / 8;
     constexpr int UNITS = 256 * CH8 / 256;
-    constexpr int GPRE = BC == 64 ? 8 : 0;        // BC = 128 has no registers to spare for it
+    constexpr int GPRE = 0;                       // (an early request of the gate rows needs 32 registers nobody has)
     const chunk16 zero16 = {0u, 0u, 0u, 0u};
     chunk16 gpre[GPRE > 0 ? GPRE : 1];
 #pragma unroll
@@ -353,10 +367,10 @@ template <int BC>
 hipError_t launch_halo(const void *in, const void *wt, const float *bias, void *out, int relu, GradEpi epi,
                        const GatherConv &g, void *pool_out, uint8_t *pool_idx, hipStream_t s)
 {
-    constexpr size_t ring_bytes = (size_t)HALO_ELEMS * 2 + 3 * 8192;
+    constexpr size_t ring_bytes = (size_t)halo_cfg<BC>::ELEMS * 2 + halo_cfg<BC>::WS * (size_t)BC * halo_cfg<BC>::KS * 2;
     constexpr size_t smem = ring_bytes + BC * sizeof(float);
     static_assert((size_t)256 * (BC + 4) * 2 <= ring_bytes, "epilogue staging fits");
-    static_assert(smem <= 80 * 1024, "two blocks per CU");
+    static_assert((smem + 1279) / 1280 * halo_cfg<BC>::BLOCKS_PER_CU <= 128, "blocks per CU (LDS is handed out in 1280-byte granules)");
     auto kfn = k_conv3x3_halo<BC>;
     static bool attr_set = false;
     if (!attr_set && smem > 64 * 1024) {
