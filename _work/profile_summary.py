@@ -28,7 +28,11 @@ def is_copy(name, value):
 
 def short(name):
     name = name.replace("bapipe::(anonymous namespace)::", "").replace("bapipe::", "").replace("(anonymous namespace)::", "")
-    return name if name.startswith("void at::") else name.split("(")[0]
+    if name.startswith("void at::"):
+        return name
+    import re
+    m = re.search(r"\bk_\w+(<[^(]*>)?", name)
+    return (m.group(0) if m else name.split("(")[0]) or name[:60]
 
 
 def one(pattern):
