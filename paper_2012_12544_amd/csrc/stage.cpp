@@ -50,6 +50,9 @@ struct Tensor {
     int galias = -1;       // tensor whose gradient IS this tensor's gradient (an un-gated input of an ADD that
                            // nobody else reads: the sum's gradient passes through unchanged, no copy is made)
     std::vector<int> consumers;
+    // Input / output gradient of a linear layer whose weight gradient is deferred: the tensor (its gradient) lives
+    // in that layer's per-mini-batch buffer, one copy per micro-batch, so that nothing has to be copied there.
+    char *mb_store = nullptr, *gmb_store = nullptr;
     size_t bytes() const { return elems * esize; }
 };
 
@@ -193,6 +196,7 @@ struct bapipe_stage {
     void *tptr(int t, int mbid)
     {
         const Tensor &T = tensors[tensors[t].root];
+        if (T.mb_store) return T.mb_store + (size_t)mbid * T.bytes();
         return (T.stashed ? slot(mbid) : transient) + T.off;
     }
     void *gptr(int t) { return grads + tensors[tensors[t].root].goff; }
@@ -608,6 +612,7 @@ void *grad_ptr(bapipe_stage *st, int t, BwdCtx &c)
     if (st->tensors[r].galias >= 0) return grad_ptr(st, st->tensors[r].galias, c);
     if (r == 0 && c.dx_direct) return c.dx_direct;
     if (r == st->tensors[(int)st->tensors.size() - 1].root && c.dy_direct) return const_cast<void *>(c.dy_direct);
+    if (st->tensors[r].gmb_store) return st->tensors[r].gmb_store + (size_t)c.mbid * st->tensors[r].bytes();
     return st->gptr(t);
 }
 
@@ -640,8 +645,11 @@ int layer_backward(bapipe_stage *st, int li, BwdCtx &c)
         const double flop = conv_flop(fwd_geom(st, L), L.d.cin);
         bool bias_done = false;
         if (L.deferred && !c.profiling) {
-            HIPCHK(hipMemcpyAsync(L.def_x + (size_t)c.mbid * L.def_x_bytes, x, L.def_x_bytes, hipMemcpyDeviceToDevice, s));
-            HIPCHK(hipMemcpyAsync(L.def_g + (size_t)c.mbid * L.def_g_bytes, g, L.def_g_bytes, hipMemcpyDeviceToDevice, s));
+            // nothing to copy where the tensor already lives in the layer's buffer
+            char *xk = L.def_x + (size_t)c.mbid * L.def_x_bytes, *gk = L.def_g + (size_t)c.mbid * L.def_g_bytes;
+            if (x != xk) HIPCHK(hipMemcpyAsync(xk, x, L.def_x_bytes, hipMemcpyDeviceToDevice, s));
+            if (g != gk) HIPCHK(hipMemcpyAsync(gk, g, L.def_g_bytes, hipMemcpyDeviceToDevice, s));
+            bias_done = true;                             // the column sums of dy ride along in the deferred GEMM
         } else {
             const bool mf = use_mfma_wgrad(st, cs);
             // a layer without an input gradient ends the pass's kernel chain: its weight gradient would only delay
@@ -799,7 +807,7 @@ int flush_deferred(bapipe_stage *st)
         const char *x = L.def_x + (size_t)st->flushed * L.def_x_bytes;
         const char *g = L.def_g + (size_t)st->flushed * L.def_g_bytes;
         const bool tp = st->tap_begin(BAPIPE_KC_CONV_WGRAD_MFMA);
-        HIPCHK(conv_wgrad_mfma(x, g, L.dw, nullptr, st->work, cs, st->stream));
+        HIPCHK(conv_wgrad_mfma(x, g, L.dw, L.db, st->work, cs, st->stream));
         st->tap_end(tp, conv_flop(fwd_geom(st, L), L.d.cin) * n, (double)n * (L.def_x_bytes + L.def_g_bytes) + 8.0 * L.w_elems);
     }
     st->flushed = st->n_bwd;
@@ -1273,6 +1281,12 @@ int bapipe_stage_create(const bapipe_layer_desc_t *layers, int n_layers, int mic
             if (L.deferred) {
                 L.def_x = st->deferred + off; off += align_up(L.def_x_bytes * n_micro);
                 L.def_g = st->deferred + off; off += align_up(L.def_g_bytes * n_micro);
+                Tensor &RA = st->tensors[root_of(L.a)];
+                if (RA.stashed && !RA.mb_store && RA.bytes() == L.def_x_bytes) RA.mb_store = L.def_x;
+                const int ro = root_of(L.o);
+                Tensor &RO = st->tensors[ro];
+                if (ro != 0 && ro != root_of(last_t) && RO.galias < 0 && RO.need_grad && !RO.gmb_store && RO.bytes() == L.def_g_bytes)
+                    RO.gmb_store = L.def_g;
             }
     }
     for (int i = 0; i < n_layers; ++i) {
