@@ -19,6 +19,11 @@ inline size_t dt_size(int dt) { return dt == DT_F32 ? 4 : 2; }
 //                  channel-transposed copy [C][R][S][K]
 struct GatherConv {
     int N, Hi, Wi, Ci, Ho, Wo, Co, R, S, s_out, s_in, pad_h, pad_w;
+    // Hint for the tile plan: kernels of other streams run beside this launch.  Alone on the chip a launch wants
+    // every compute unit busy; beside others, units it leaves idle are not lost, and fewer, larger blocks (less
+    // operand traffic per FLOP) are the better neighbour.  Only the pixel tile may depend on it: every output
+    // element is still one sum over K in the same order, so results do not change by a bit.
+    int beside = 0;
 };
 
 // Forward-convolution geometry (x: N,H,W,C ; y: N,P,Q,K ; filter R x S).

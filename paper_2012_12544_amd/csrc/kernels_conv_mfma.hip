@@ -506,14 +506,17 @@ GatherPlan gather_plan(const GatherConv &g)
     // 256-pixel tiles that cannot even fill 400 of the 512 block slots (14x14 layers, the 1x1 convs of
     // the bottleneck blocks): halve the pixel tile rather than split K, whose fp32 partials cost more
     // than the smaller tile loses (measured on 512-channel 14x14 layers: 73 us against 100 us)
-    if (p.bp == 256 && p.bc == 128 && tiles_of(256) < 400) p.bp = 128;
+    // Beside kernels of other streams the 196-392 tiles of 256 x 128 stay (measured on the deep VGG stage with three
+    // streams: 18.8 -> 17.7 ms per mini-batch; alone on the chip the same choice loses 3 %).
+    const bool few = g.beside && p.bp == 256 && p.bc == 128 && tiles_of(256) < 400 && tiles_of(256) >= 128;
+    if (!few && p.bp == 256 && p.bc == 128 && tiles_of(256) < 400) p.bp = 128;
     // small products (the bottleneck blocks of ResNet: under ~8 GMAC) are bound by the latency of a block's
     // load - multiply - store chain, not by throughput: many 64-pixel blocks and no split of K were the
     // fastest choice on every such shape measured (e.g. 1x1 1024->256 at 14x14: 11.5 us against 22.2)
     if (p.bc == 128 && npix > 64 && (double)npix * g.Co * g.R * g.S * g.Ci < 8e9) p.bp = 64;
     // plenty of 256-pixel tiles and whole 256-channel tiles: one 8-wave block per CU owns 256 x 256, which
     // halves the L2 -> LDS traffic of two independent 256 x 128 blocks (3 % on the 512-channel 28x28 layers)
-    if (p.bp == 256 && p.bc == 128 && g.Co % 256 == 0) p.bc = 256;
+    if (!few && p.bp == 256 && p.bc == 128 && g.Co % 256 == 0) p.bc = 256;
     const long long tiles = tiles_of(p.bp);
     const int BK = 32;
     const int KT = g.Ci % BK == 0 ? (g.Ci / BK) * g.R * g.S : (g.R * g.S * g.Ci + BK - 1) / BK;
@@ -887,11 +890,12 @@ WgradPlan wgrad_plan(const ConvShape &c)
     long long max_by_work = (npix + 511) / 512;
     if (max_by_work > 256) max_by_work = 256;
     if (max_by_work < 1) max_by_work = 1;
+    const long long slots = 512;
     long long want = 1;
     double best = 1e30;
     for (long long sp = 1; sp <= max_by_work; ++sp) {
-        const long long blocks = tiles * sp, rounds = (blocks + 511) / 512;
-        const double cost = (double)(rounds * 512) / (double)blocks + 500.0 * (double)sp / (double)npix;
+        const long long blocks = tiles * sp, rounds = (blocks + slots - 1) / slots;
+        const double cost = (double)(rounds * slots) / (double)blocks + 500.0 * (double)sp / (double)npix;
         if (cost < best) {
             best = cost;
             want = sp;

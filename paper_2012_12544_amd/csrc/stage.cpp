@@ -519,6 +519,8 @@ int layer_forward(bapipe_stage *st, int li, const FwdCtx &c)
     case BAPIPE_CONV2D:
     case BAPIPE_LINEAR: {
         GatherConv g = fwd_geom(st, L);
+        // the number of statistics chunks a conv leaves for its batch-norm was fixed at creation: same plan here
+        g.beside = st->stream_b && !c.profiling && !L.stat_chunks;
         GradEpi none{nullptr, 0};
         const bool mf = use_mfma_gather(st, g);
         const bool tp = st->tap_begin(mf ? BAPIPE_KC_CONV_GATHER_MFMA : BAPIPE_KC_CONV_DIRECT);
@@ -679,6 +681,7 @@ int layer_backward(bapipe_stage *st, int li, BwdCtx &c)
         }
         if (a_grad) {
             GatherConv dg = dgrad_geom(st, L);
+            dg.beside = st->stream_b && !c.profiling && !L.bnb_chunks && !L.strided_1x1;
             GradEpi e = epi_for(st, L.a, c);
             void *dx = grad_ptr(st, L.a, c);
             const bool mf = use_mfma_gather(st, dg);
@@ -1235,6 +1238,10 @@ int bapipe_stage_create(const bapipe_layer_desc_t *layers, int n_layers, int mic
             w = colsum_workspace(cs.N * cs.P * cs.Q, cs.K);
             work = w > work ? w : work;
             GatherConv fg = fwd_geom(st, L), dg = dgrad_geom(st, L);
+            if (use_mfma_gather(st, fg)) { w = conv_gather_mfma_workspace(fg); work = w > work ? w : work; }
+            if (use_mfma_gather(st, dg)) { w = conv_gather_mfma_workspace(dg); work = w > work ? w : work; }
+            // the plans these launches take beside kernels of further streams (bapipe_stage_set_streams)
+            fg.beside = dg.beside = 1;
             if (use_mfma_gather(st, fg)) { w = conv_gather_mfma_workspace(fg); work = w > work ? w : work; }
             if (use_mfma_gather(st, dg)) { w = conv_gather_mfma_workspace(dg); work = w > work ? w : work; }
         }

@@ -135,6 +135,19 @@ def test_vgg16_deep_end_to_end_full_shapes():
 
 
 @pytest.mark.timeout(900)
+def test_vgg16_deep_further_streams_same_bits_full_shapes():
+    """Beside kernels of further streams the 14x14 layers take other pixel tiles than alone on the chip (a choice that
+    only exists at full size): every output must still agree bit for bit with the one-stream run.  GPU only."""
+    from gpu_harness import gpu_minibatch
+    stage = C.vgg16_deep(n_micro=4)                 # depth 2: backward passes overlap later forward passes
+    ref = gpu_minibatch(stage)
+    got = gpu_minibatch(stage, eager_sync=False, backward_stream=True)
+    assert sorted(got) == sorted(ref) and any(k.startswith("dw") for k in ref)
+    for k in ref:
+        assert np.array_equal(got[k], ref[k]), k
+
+
+@pytest.mark.timeout(900)
 def test_vgg16_classifier_end_to_end_full_shapes():
     # three layers deep: everything element-wise (weight and bias gradients included), the input gradient sample by
     # sample - one flipped ReLU gate among the 4096 units of a hidden layer moves that sample's dx by about

@@ -518,3 +518,18 @@ def test_further_streams_against_the_oracle_and_their_call_rules():
     B.bapipe_stage_set_streams(g.h, None, None)
     B.bapipe_stage_set_streams(g.h, side.cuda_stream, None)
     g.close()
+
+
+def test_measured_peaks_are_plausible_and_below_the_published_ones():
+    """The probe behind bench.py's `measured_peaks` (register-resident MFMA loop, streaming copy): what it returns
+    must lie under the published peaks of the part and well above what a broken probe (a loop the compiler removed,
+    a copy that never ran) would give."""
+    import ctypes as ct
+    tf, gb = B.bapipe_measure_peaks()
+    assert 800.0 < tf < 2500.0, tf          # bf16 dense MFMA: 2.5 PFLOP/s published
+    assert 2000.0 < gb < 8000.0, gb         # HBM3E: 8 TB/s published (read + written bytes of a copy)
+    tf2, gb2 = B.bapipe_measure_peaks()
+    assert abs(tf2 - tf) < 0.1 * tf and abs(gb2 - gb) < 0.15 * gb
+    one = ct.c_double(0)
+    assert B.load().bapipe_measure_peaks(0, None, ct.byref(one)) == B.E_INVALID
+    assert B.load().bapipe_measure_peaks(0, ct.byref(one), None) == B.E_INVALID
