@@ -3,7 +3,7 @@
 // 64 / 128 channels), where the generic gather kernel is bound by L1/L2 traffic because every
 // input pixel is fetched again for each of the 9 taps.
 //
-// A block owns a 16x16 patch of output pixels x BC output channels.  The 18x18 input halo of one
+// A block owns a 16x16 patch of output pixels x 64 output channels.  The 18x18 input halo of one
 // 64-channel slice is brought into LDS ONCE (buffer_load ... lds, zero fill outside the image) and
 // all 9 taps read their shifted views of it: the B fragment of tap (r,s) for patch pixel (y,x) is
 // simply halo pixel (y+r, x+s).  Only the filter tile of the current tap streams through a small
@@ -22,19 +22,22 @@ __device__ __forceinline__ int swz8(int row) { return (row >> 1) & 7; }
 
 constexpr int PATCH = 16, HALO = 18, HPIX = HALO * HALO;       // 324 halo pixels
 constexpr int HL = 11;                                          // halo wave-loads per wave (44 x 64 slots >= 2592)
-// Per output-channel tile width.  128 channels: filter steps of 32 input channels through a ring of three 8 KB
-// stages, two blocks per CU (the 128 accumulator registers of a lane leave no room for a third).  64 channels:
-// steps of 32 channels too (4 KB stages), a ring of two, and exactly the 41 wave-loads that hold halo pixels, so
-// that a block needs 50.4 KB of LDS (40 allocation granules of 1280 bytes) and at most 168 registers and THREE
-// blocks share a CU: these layers have little arithmetic per block (one 64-channel slice), a block spends most of
-// its life fetching its halo and storing its patch, and the third block is what overlaps that.  Measured on the
-// 64 -> 64 layer at 224 x 224: forward 171 -> 155 us, forward + pool 180 -> 142 us, input gradient 240 -> 207 us.
-template <int BC> struct halo_cfg {
+// A block's tile is 64 output channels wide, whatever the layer's width (a 128-channel layer is two tiles that
+// load the same halo): filter steps of 32 input channels (4 KB stages) through a ring of two, and exactly the 41
+// wave-loads that hold halo pixels, so that a block needs 50.4 KB of LDS (40 allocation granules of 1280 bytes)
+// and at most 168 registers and THREE blocks share a CU.  A block has little arithmetic per byte it moves (one
+// 64-channel slice per halo), spends much of its life fetching its halo and storing its patch, and the third
+// block is what overlaps that.  128-channel tiles (128 accumulator registers per lane, two blocks per CU) were the
+// first design for the 128-channel layers and lost to this one once it had its third block: whole first VGG stage
+// on one stream 9.90 -> 9.41 ms per mini-batch.  Measured on the 64 -> 64 layer at 224 x 224 against two blocks
+// per CU: forward 171 -> 155 us, forward + pool 180 -> 142 us, input gradient 240 -> 207 us.
+struct halo_cfg {
+    static constexpr int BC = 64;                                  // output channels per block
     static constexpr int KS = 32;                                  // input channels per filter step
-    static constexpr int WS = BC == 64 ? 2 : 3;                    // ring stages
-    static constexpr int LOADS = BC == 64 ? 41 : HL * 4;           // wave-loads that hold halo pixels (41 x 64 slots >= 2592)
+    static constexpr int WS = 2;                                   // ring stages
+    static constexpr int LOADS = 41;                               // wave-loads that hold halo pixels (41 x 64 slots >= 2592)
     static constexpr int ELEMS = LOADS * 64 * 8;                   // bf16 elements reserved for the halo tile
-    static constexpr int BLOCKS_PER_CU = BC == 64 ? 3 : 2;
+    static constexpr int BLOCKS_PER_CU = 3;
 };
 
 // Filter tiles stream through the ring: one "step" is one tap x KS = 32 input channels, i.e. NSUB = 2 MFMA
@@ -42,28 +45,27 @@ template <int BC> struct halo_cfg {
 // unrolled, so ring slots, halo rows and swizzles are compile-time or precomputed per tap: a fragment
 // read costs at most one XOR.  Fragments are double-buffered in registers and the barrier that
 // publishes the next filter tile sits before the last sub-step of a step, as in the gather kernel.
-template <int BC>
-__global__ __launch_bounds__(256, halo_cfg<BC>::BLOCKS_PER_CU) void k_conv3x3_halo(const bf16_t *__restrict__ in, const bf16_t *__restrict__ wt,
+__global__ __launch_bounds__(256, halo_cfg::BLOCKS_PER_CU) void k_conv3x3_halo(const bf16_t *__restrict__ in, const bf16_t *__restrict__ wt,
                                                          const float *__restrict__ bias, bf16_t *out,
                                                          const bf16_t *__restrict__ gate, int accum, int relu,
                                                          int is_grad, int N, int H, int W, int Ci, int Co,
                                                          unsigned in_bytes, unsigned wt_bytes,
                                                          bf16_t *__restrict__ pool_out, uint8_t *__restrict__ pool_idx)
 {
-    constexpr int NW = 4;
-    constexpr int KS = halo_cfg<BC>::KS;       // input channels per filter step tile
-    constexpr int HALO_LOADS = halo_cfg<BC>::LOADS, HALO_ELEMS = halo_cfg<BC>::ELEMS;
+    constexpr int NW = 4, BC = halo_cfg::BC;
+    constexpr int KS = halo_cfg::KS;           // input channels per filter step tile
+    constexpr int HALO_LOADS = halo_cfg::LOADS, HALO_ELEMS = halo_cfg::ELEMS;
     constexpr int NSUB = KS / 16;              // MFMA sub-steps per step
     constexpr int SPT = 64 / KS;               // steps per tap and 64-channel slice
     constexpr int SPS = 9 * SPT;               // steps per slice (a multiple of WS)
-    constexpr int WS = halo_cfg<BC>::WS;       // ring stages
-    constexpr int WT_ELEMS = BC * KS;          // 4096 elements = 8 KB (2048 = 4 KB for 64 channels x 32)
+    constexpr int WS = halo_cfg::WS;           // ring stages
+    constexpr int WT_ELEMS = BC * KS;          // 2048 elements = 4 KB
     constexpr int CPR = KS / 8;                // 16-byte chunks per filter-tile row
-    constexpr int WLD = WT_ELEMS / 8 / 256;    // filter wave-loads per wave and step (512 or 256 slots / 64 / 4)
+    constexpr int WLD = WT_ELEMS / 8 / 256;    // filter wave-loads per wave and step (256 slots / 64 / 4)
     constexpr int TC = BC / 32, TP = 2;        // wave tile: BC channels x 64 pixels
     constexpr int SROW = BC + 4;
     constexpr unsigned OOB = 0x80000000u;
-    static_assert((WT_ELEMS == 4096 || WT_ELEMS == 2048) && SPS % WS == 0, "ring layout");
+    static_assert(WT_ELEMS == 2048 && KS == 32 && SPS % WS == 0, "ring layout");
 
     extern __shared__ __align__(16) unsigned char smem[];
     const lds_addr_of lds_of(smem);
@@ -102,9 +104,9 @@ __global__ __launch_bounds__(256, halo_cfg<BC>::BLOCKS_PER_CU) void k_conv3x3_ha
             if (i * NW + wave < HALO_LOADS) dma16(xrsrc, lds_of(halo + (i * NW + wave) * 512), vo);
         }
     };
-    // filter tile rows are KS elements long; chunk index XORed with swz8(row) (KS = 64) or bits 2..3 of
-    // the row (KS = 32) so that the fragment reads are conflict free
-    auto wswz = [](int row) { return KS == 64 ? ((row >> 1) & 7) : ((row >> 2) & 3); };
+    // filter tile rows are KS = 32 elements long; chunk index XORed with bits 2..3 of the row so that the
+    // fragment reads are conflict free
+    auto wswz = [](int row) { return (row >> 2) & 3; };
     unsigned woff[WLD];
 #pragma unroll
     for (int i = 0; i < WLD; ++i) {
@@ -171,28 +173,10 @@ __global__ __launch_bounds__(256, halo_cfg<BC>::BLOCKS_PER_CU) void k_conv3x3_ha
 #pragma unroll
     for (int st = 0; st < WS; ++st) issue_w(0, st);
 
-    // gradient epilogue: the ReLU gate of the first GPRE output rows of this thread is requested now
-    // (behind the halo and the first filter tiles, which the MFMAs need first), so the loads complete
-    // under the main loop instead of after the last MFMA
     constexpr int CH8 = BC / 8;
     constexpr int UNITS = 256 * CH8 / 256;
-    constexpr int GPRE = 0;                       // (an early request of the gate rows needs 32 registers nobody has)
     const chunk16 zero16 = {0u, 0u, 0u, 0u};
-    chunk16 gpre[GPRE > 0 ? GPRE : 1];
-#pragma unroll
-    for (int it = 0; it < GPRE; ++it) gpre[it] = zero16;
-    if (GPRE > 0 && gate) {
-#pragma unroll
-        for (int it = 0; it < GPRE; ++it) {
-            const int u = tid + it * 256;
-            const int pj = u / CH8, c8i = u % CH8;
-            const size_t p = (size_t)(n * H + Y0 + (pj >> 4)) * W + X0 + (pj & 15);
-            gpre[it] = *reinterpret_cast<const chunk16 *>(gate + p * Co + co0 + c8i * 8);
-        }
-        WAIT_VMCNT(GPRE + (WS - 1) * WLD);       // halo and filter tile 0 have landed (gate rows may still fly)
-    } else {
-        WAIT_VMCNT((WS - 1) * WLD);
-    }
+    WAIT_VMCNT((WS - 1) * WLD);                  // halo and filter tile 0 have landed
     WAIT_LGKMCNT(0);                             // no scalar load pending at loop entry (else every LDS wait is a full drain)
     __builtin_amdgcn_s_barrier();
     bf16x8_t fa0[TC], fb0[TP], fa1[TC], fb1[TP];
@@ -276,13 +260,12 @@ __global__ __launch_bounds__(256, halo_cfg<BC>::BLOCKS_PER_CU) void k_conv3x3_ha
             }
         }
     }
-    // BC = 128 had no registers for the early gate request above: its gate rows are requested here, where the
-    // accumulators are dead, so that they travel while the staging tile is completed
-    constexpr int GLATE = GPRE == 0 ? UNITS : 0;
-    chunk16 glate[GLATE > 0 ? GLATE : 1];
-    if (GLATE > 0 && is_grad && gate) {
+    // gradient epilogue: the ReLU-gate rows are requested here, where the accumulators are dead (the main loop has no
+    // registers to spare for an earlier request), so that they travel while the staging tile is completed
+    chunk16 glate[UNITS];
+    if (is_grad && gate) {
 #pragma unroll
-        for (int it = 0; it < GLATE; ++it) {
+        for (int it = 0; it < UNITS; ++it) {
             const int u = tid + it * 256;
             const int pj = u / CH8, c8i = u % CH8;
             const size_t p = (size_t)(n * H + Y0 + (pj >> 4)) * W + X0 + (pj & 15);
@@ -348,12 +331,7 @@ __global__ __launch_bounds__(256, halo_cfg<BC>::BLOCKS_PER_CU) void k_conv3x3_ha
         if (is_grad) {
             chunk16 old = zero16, gt = zero16, rr;
             if (accum) old = *reinterpret_cast<const chunk16 *>(dst);
-            if (it < GPRE)
-                gt = gpre[it];
-            else if (it < GLATE && gate)
-                gt = glate[it < GLATE ? it : 0];
-            else if (gate)
-                gt = *reinterpret_cast<const chunk16 *>(gate + p * Co + co);
+            if (gate) gt = glate[it];
 #pragma unroll
             for (int j = 0; j < 4; ++j) rr[j] = grad_epilogue_pair(v[j], old[j], gt[j], accum != 0, gate != nullptr);
             *reinterpret_cast<chunk16 *>(dst) = rr;
@@ -363,15 +341,15 @@ __global__ __launch_bounds__(256, halo_cfg<BC>::BLOCKS_PER_CU) void k_conv3x3_ha
     }
 }
 
-template <int BC>
 hipError_t launch_halo(const void *in, const void *wt, const float *bias, void *out, int relu, GradEpi epi,
                        const GatherConv &g, void *pool_out, uint8_t *pool_idx, hipStream_t s)
 {
-    constexpr size_t ring_bytes = (size_t)halo_cfg<BC>::ELEMS * 2 + halo_cfg<BC>::WS * (size_t)BC * halo_cfg<BC>::KS * 2;
+    constexpr int BC = halo_cfg::BC;
+    constexpr size_t ring_bytes = (size_t)halo_cfg::ELEMS * 2 + halo_cfg::WS * (size_t)BC * halo_cfg::KS * 2;
     constexpr size_t smem = ring_bytes + BC * sizeof(float);
     static_assert((size_t)256 * (BC + 4) * 2 <= ring_bytes, "epilogue staging fits");
-    static_assert((smem + 1279) / 1280 * halo_cfg<BC>::BLOCKS_PER_CU <= 128, "blocks per CU (LDS is handed out in 1280-byte granules)");
-    auto kfn = k_conv3x3_halo<BC>;
+    static_assert((smem + 1279) / 1280 * halo_cfg::BLOCKS_PER_CU <= 128, "blocks per CU (LDS is handed out in 1280-byte granules)");
+    auto kfn = k_conv3x3_halo;
     static bool attr_set = false;
     if (!attr_set && smem > 64 * 1024) {
         hipError_t e = hipFuncSetAttribute((const void *)kfn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
@@ -926,8 +904,7 @@ hipError_t conv3x3_halo_mfma(const void *in, const void *wt, const float *bias, 
                              GradEpi epi, const GatherConv &g, hipStream_t s)
 {
     if (!conv3x3_halo_supported(g)) return hipErrorInvalidValue;
-    if (g.Co % 128 == 0) return launch_halo<128>(in, wt, bias, out, relu, epi, g, nullptr, nullptr, s);
-    return launch_halo<64>(in, wt, bias, out, relu, epi, g, nullptr, nullptr, s);
+    return launch_halo(in, wt, bias, out, relu, epi, g, nullptr, nullptr, s);
 }
 
 bool conv3x3_c8_supported(const GatherConv &g)
@@ -955,8 +932,7 @@ hipError_t conv3x3_halo_pool_mfma(const void *in, const void *wt, const float *b
 {
     if (!conv3x3_halo_supported(g) || !pool_out || !pool_idx || ((uintptr_t)pool_idx & 7)) return hipErrorInvalidValue;
     GradEpi none{nullptr, 0};
-    if (g.Co % 128 == 0) return launch_halo<128>(in, wt, bias, nullptr, relu, none, g, pool_out, pool_idx, s);
-    return launch_halo<64>(in, wt, bias, nullptr, relu, none, g, pool_out, pool_idx, s);
+    return launch_halo(in, wt, bias, nullptr, relu, none, g, pool_out, pool_idx, s);
 }
 
 }  // namespace bapipe
