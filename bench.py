@@ -52,20 +52,27 @@ def one_f_one_b(M, depth):
 
 
 def cpu_baseline(stage, sample):
-    """Oracle fwd+bwd on `sample` samples of micro-batch 0 (same seeded inputs), timed."""
+    """Oracle fwd+bwd on `sample` samples (same seeded inputs), timed: the first `sample` samples of micro-batch 0,
+    or whole micro-batches 0, 1, ... when `sample` is a multiple of the micro-batch size."""
     from oracle import ops
     from oracle.stage import OracleStage
-    sub = dict(stage, micro_batch=sample, n_micro=1)
+    mb = stage["micro_batch"]
+    n_mb = max(1, sample // mb)
+    per = sample if n_mb == 1 else mb
+    sub = dict(stage, micro_batch=per, n_micro=n_mb)
     params = gen.all_params(stage)
-    x = gen.stage_input(stage, 0)[:sample]
-    g = gen.labels(stage, 0)[:sample] if gen.ends_in_loss(stage) else gen.upstream_grad(stage, 0)[:sample]
+    loss = gen.ends_in_loss(stage)
+    xs = [gen.stage_input(stage, m)[:per] for m in range(n_mb)]
+    gs = [(gen.labels(stage, m) if loss else gen.upstream_grad(stage, m))[:per] for m in range(n_mb)]
     orc = OracleStage(sub, params, depth=1)
     t0 = time.time()
-    orc.forward(0, x)
-    orc.backward(0, g)
+    for m in range(n_mb):
+        orc.forward(m, xs[m])
+        orc.backward(m, gs[m])
     dt = time.time() - t0
-    return dict(value=sample / dt, unit="samples/s", cores=int(ops.num_threads()), kind="oracle",
-                sample="%d samples of micro-batch 0, fwd+bwd, %.1f s" % (sample, dt))
+    what = "%d samples of micro-batch 0" % per if n_mb == 1 else "micro-batches 0..%d (%d samples)" % (n_mb - 1, per * n_mb)
+    return dict(value=per * n_mb / dt, unit="samples/s", cores=int(ops.num_threads()), kind="oracle",
+                sample="%s, fwd+bwd, %.1f s" % (what, dt))
 
 
 class Workload:
@@ -337,11 +344,12 @@ def main():
 
     if not a.no_cpu_baseline:
         # about 10-30 s of oracle work on the 16 host threads of the GPU machine
-        default_sample = {"tiny": 16, "vgg16_stage1": 32, "vgg16_deep": 32, "vgg16_classifier": 64,
+        default_sample = {"tiny": 16, "vgg16_stage1": 64, "vgg16_deep": 32, "vgg16_classifier": 64,
                           "resnet50_stage": 32, "vgg16_conv3": 32, "resnet50_stem": 32, "resnet50_tail": 32,
                           "vgg16_full": 16, "resnet50_full": 32, "gnmt_lstm_stage": 64}[a.workload]
-        sample = min(w.mb * w.M if a.workload == "tiny" else w.mb, a.cpu_sample or default_sample)
-        sample = min(sample, w.mb)
+        sample = min(w.mb * w.M, a.cpu_sample or default_sample)
+        if sample > w.mb:
+            sample -= sample % w.mb                       # whole micro-batches
         out["cpu_baseline"] = cpu_baseline(stage, sample)
     print(json.dumps(out), flush=True)
 
