@@ -860,12 +860,12 @@ const char *bapipe_last_error(const bapipe_stage_t *st) { return st ? st->err.c_
 void bapipe_stage_destroy(bapipe_stage_t *st)
 {
     if (!st) return;
-    (void)hipStreamSynchronize(st->stream);
-    if (st->stream_b) (void)hipStreamSynchronize(st->stream_b);          // the caller's stream: not destroyed here
+    (void)hipStreamSynchronize(st->stream);                              // the caller's streams: drained, not destroyed
+    if (st->stream_b) (void)hipStreamSynchronize(st->stream_b);
+    if (st->stream_w) (void)hipStreamSynchronize(st->stream_w);
     for (hipEvent_t e : st->ev_fwd) if (e) (void)hipEventDestroy(e);
     for (hipEvent_t e : st->ev_bwd) if (e) (void)hipEventDestroy(e);
     st->dev_free(st->work_b);
-    if (st->stream_w) (void)hipStreamSynchronize(st->stream_w);
     if (st->ev_g) (void)hipEventDestroy(st->ev_g);
     if (st->ev_w_end) (void)hipEventDestroy(st->ev_w_end);
     st->dev_free(st->work_w);
