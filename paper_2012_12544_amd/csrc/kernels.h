@@ -35,6 +35,10 @@ struct ConvShape {
 struct GradEpi {
     const void *gate;  // forward values deciding the producer's fused-ReLU mask, or NULL
     int accum;         // add to what is already stored
+    // With accum: the stored value is read from here (same layout as the destination) instead of from the
+    // destination itself - the other contribution to a gradient with two sources, taken where it already lies
+    // instead of being copied first.  Honoured by the MFMA gather convolution; NULL everywhere else.
+    const void *accum_from = nullptr;
 };
 
 // ---- direct (CUDA-core style) convolution: fp32 stages and shapes the MFMA path skips

@@ -47,7 +47,8 @@ __global__ __launch_bounds__(WP *WC * 64, WP *WC >= 8 ? 1 : 2) void k_gather_mfm
     const bf16_t *__restrict__ in, const bf16_t *__restrict__ wt, const float *__restrict__ bias,
     bf16_t *out, const bf16_t *__restrict__ gate, int accum, int relu, int is_grad, GatherConv g,
     int tiles_c, unsigned in_bytes, unsigned wt_bytes, float *__restrict__ part, int kt_per_split,
-    float *__restrict__ stat_part, const bf16_t *__restrict__ bn_x, const float *__restrict__ bn_stats)
+    float *__restrict__ stat_part, const bf16_t *__restrict__ bn_x, const float *__restrict__ bn_stats,
+    const bf16_t *old_from)
 {
     constexpr int NT = WP * WC * 64, NW = WP * WC;
     constexpr int CPR = BK / 8;              // 16-byte chunks per tile row
@@ -411,7 +412,7 @@ __global__ __launch_bounds__(WP *WC * 64, WP *WC >= 8 ? 1 : 2) void k_gather_mfm
             bf16_t *dst = out + (size_t)p * g.Co + co;
             if (is_grad) {
                 chunk16 old = zero16, gt = zero16, r;
-                if (accum) old = *reinterpret_cast<const chunk16 *>(dst);
+                if (accum) old = *reinterpret_cast<const chunk16 *>(old_from ? old_from + (size_t)p * g.Co + co : dst);
                 if (gate) gt = it < GPRE ? gpre[it < GPRE ? it : 0] : *reinterpret_cast<const chunk16 *>(gate + (size_t)p * g.Co + co);
 #pragma unroll
                 for (int j = 0; j < 4; ++j) r[j] = grad_epilogue_pair(v[j], old[j], gt[j], accum != 0, gate != nullptr);
@@ -463,7 +464,8 @@ __global__ __launch_bounds__(WP *WC * 64, WP *WC >= 8 ? 1 : 2) void k_gather_mfm
 // out[p][co] = epilogue( sum_split part[split][p][co] + bias[co] ), 8 channels per thread
 __global__ void k_gather_splitk_reduce(const float *__restrict__ part, int splits, size_t total, int Co,
                                        const float *__restrict__ bias, bf16_t *out,
-                                       const bf16_t *__restrict__ gate, int accum, int relu, int is_grad)
+                                       const bf16_t *__restrict__ gate, int accum, int relu, int is_grad,
+                                       const bf16_t *old_from)
 {
     size_t i = ((size_t)blockIdx.x * 256 + threadIdx.x) * 8;
     if (i >= total) return;
@@ -478,7 +480,7 @@ __global__ void k_gather_splitk_reduce(const float *__restrict__ part, int split
     }
     const int co = (int)(i % Co);
     vec_t<bf16_t, 8> old, gt, r;
-    if (is_grad && accum) old = *reinterpret_cast<const vec_t<bf16_t, 8> *>(out + i);
+    if (is_grad && accum) old = *reinterpret_cast<const vec_t<bf16_t, 8> *>((old_from ? old_from : out) + i);
     if (is_grad && gate) gt = *reinterpret_cast<const vec_t<bf16_t, 8> *>(gate + i);
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
@@ -558,7 +560,8 @@ hipError_t launch_gather(const void *in, const void *wt, const float *bias, void
         }                                                                                                         \
         hipLaunchKernelGGL(kfn, grid, dim3(NT), smem, s, (const bf16_t *)in, (const bf16_t *)wt, bias,          \
                            (bf16_t *)out, (const bf16_t *)epi.gate, epi.accum, relu, is_grad, g, tiles_c, in_bytes, \
-                           wt_bytes, part, plan.kt_per_split, stat_part, (const bf16_t *)bn_x, bn_stats);         \
+                           wt_bytes, part, plan.kt_per_split, stat_part, (const bf16_t *)bn_x, bn_stats,         \
+                           (const bf16_t *)epi.accum_from);                                                      \
     } while (0)
     const bool taps_inner = g.Ci % BK == 0 && g.R * g.S <= 32;      // the stride-1 variant keeps a 32-bit tap mask
     if (g.s_in == 1) {
@@ -573,7 +576,7 @@ hipError_t launch_gather(const void *in, const void *wt, const float *bias, void
         const size_t total = (size_t)npix * g.Co;
         hipLaunchKernelGGL(k_gather_splitk_reduce, dim3((unsigned)((total / 8 + 255) / 256)), dim3(256), 0, s, part,
                            plan.splits, total, g.Co, bias, (bf16_t *)out, (const bf16_t *)epi.gate, epi.accum, relu,
-                           is_grad);
+                           is_grad, (const bf16_t *)epi.accum_from);
     }
     return hipGetLastError();
 }
@@ -943,6 +946,7 @@ hipError_t conv_gather_mfma(const void *in, const void *wt, const float *bias, v
     if (stat_part && conv_gather_mfma_stat_chunks(g) == 0) return hipErrorInvalidValue;
     if (bn_x && (!stat_part || !bn_stats || !(epi.gate || epi.accum))) return hipErrorInvalidValue;   // gradient epilogue only
     if ((long long)g.N * g.Ho * g.Wo == 0) return hipSuccess;
+    if (epi.accum_from && (!epi.accum || conv3x3_halo_supported(g))) return hipErrorInvalidValue;   // gather kernel only
     if (conv3x3_halo_supported(g)) return conv3x3_halo_mfma(in, wt, bias, out, relu, epi, g, s);
     if (!epi.gate && !epi.accum && conv3x3_c8_supported(g)) return conv3x3_c8_mfma(in, wt, bias, out, relu, g, s);
     const GatherPlan p = gather_plan(g);

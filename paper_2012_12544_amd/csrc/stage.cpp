@@ -53,6 +53,10 @@ struct Tensor {
     // Input / output gradient of a linear layer whose weight gradient is deferred: the tensor (its gradient) lives
     // in that layer's per-mini-batch buffer, one copy per micro-batch, so that nothing has to be copied there.
     char *mb_store = nullptr, *gmb_store = nullptr;
+    // Gradient with two sources, a residual ADD (processed first in backward) and a conv: the ADD's share is not
+    // copied, the conv's input-gradient epilogue reads it where it lies (GradEpi::accum_from).  Layer index of
+    // that conv, or -1.
+    int fanout_conv = -1;
     size_t bytes() const { return elems * esize; }
 };
 
@@ -604,6 +608,7 @@ struct BwdCtx {
     void *dx_direct;               // caller's NHWC buffer used in place of grads[0]
     const int32_t *labels;
     std::vector<char> written;
+    std::vector<const void *> pending;   // per tensor: an ADD's share of its gradient that the tensor's conv will add (fanout_conv)
     bool profiling = false;        // profiler: run every kernel of the layer now (no deferral)
     int bn_sums_ready = -1;        // batch-norm layer whose backward sums the last conv left in the workspace
 };
@@ -683,6 +688,10 @@ int layer_backward(bapipe_stage *st, int li, BwdCtx &c)
             GatherConv dg = dgrad_geom(st, L);
             dg.beside = st->stream_b && !c.profiling && !L.bnb_chunks && !L.strided_1x1;
             GradEpi e = epi_for(st, L.a, c);
+            if (c.pending[A.root]) {                      // the residual ADD's share, added here instead of copied there
+                e.accum_from = c.pending[A.root];
+                c.pending[A.root] = nullptr;
+            }
             void *dx = grad_ptr(st, L.a, c);
             const bool mf = use_mfma_gather(st, dg);
             const bool tp = st->tap_begin(mf ? BAPIPE_KC_CONV_GATHER_MFMA : BAPIPE_KC_CONV_DIRECT);
@@ -754,6 +763,9 @@ int layer_backward(bapipe_stage *st, int li, BwdCtx &c)
         double bytes = 0.0;
         if (a_grad && st->tensors[A.root].galias == L.o) {
             c.written[A.root] = 1;
+        } else if (a_grad && st->tensors[A.root].fanout_conv >= 0 && !c.profiling && !c.written[A.root]) {
+            c.pending[A.root] = g;                        // taken by that conv's input-gradient epilogue
+            c.written[A.root] = 1;
         } else if (a_grad) {
             GradEpi e = epi_for(st, L.a, c);
             HIPCHK(grad_copy(dt, g, grad_ptr(st, L.a, c), e, O.elems, s));
@@ -761,6 +773,9 @@ int layer_backward(bapipe_stage *st, int li, BwdCtx &c)
         }
         const int rb = st->tensors[L.b].root;
         if (st->tensors[rb].need_grad && st->tensors[rb].galias == L.o) {
+            c.written[rb] = 1;
+        } else if (st->tensors[rb].need_grad && st->tensors[rb].fanout_conv >= 0 && !c.profiling && !c.written[rb]) {
+            c.pending[rb] = g;
             c.written[rb] = 1;
         } else if (st->tensors[rb].need_grad) {
             GradEpi e = epi_for(st, L.b, c);
@@ -1246,6 +1261,18 @@ int bapipe_stage_create(const bapipe_layer_desc_t *layers, int n_layers, int mic
             if (use_mfma_gather(st, dg)) { w = conv_gather_mfma_workspace(dg); work = w > work ? w : work; }
         }
     }
+    // residual fan-out: a tensor read by exactly one conv (MFMA gather input gradient, plain epilogue) and, later in
+    // the list, one ADD
+    for (int t = 0; t < nt; ++t) {
+        Tensor &T = st->tensors[t];
+        if (st->dt != DT_BF16 || T.root != t || !T.need_grad || T.galias >= 0 || T.consumers.size() != 2) continue;
+        const int ic = T.consumers[0], ia = T.consumers[1];
+        const Layer &Lc = st->layers[ic], &La = st->layers[ia];
+        if (ic >= ia || Lc.d.kind != BAPIPE_CONV2D || La.d.kind != BAPIPE_ADD || Lc.a != t || (La.a != t && La.b != t)) continue;
+        const GatherConv dg = dgrad_geom(st, Lc);
+        if (!use_mfma_gather(st, dg) || conv3x3_halo_supported(dg) || Lc.strided_1x1 || Lc.bnb_chunks) continue;
+        T.fanout_conv = ic;
+    }
     st->slot_bytes = align_up(slot);
     st->transient_bytes = trans;
     st->grads_bytes = gr;
@@ -1382,6 +1409,7 @@ int bapipe_stage_backward(bapipe_stage_t *st, int mb_id, const void *dy_dev_or_l
     c.dx_direct = nullptr;
     c.labels = nullptr;
     c.written.assign(st->tensors.size(), 0);
+    c.pending.assign(st->tensors.size(), nullptr);
     const Tensor &In = st->tensors[0];
     const bool want_dx = In.need_grad && dx_dev != nullptr;
     if (want_dx && (nhwc || In.H * In.W == 1) && In.Cp == In.C) c.dx_direct = dx_dev;
@@ -1407,6 +1435,8 @@ int bapipe_stage_backward(bapipe_stage_t *st, int mb_id, const void *dy_dev_or_l
         int rc = layer_backward(st, i, c);
         if (rc != BAPIPE_OK) return rc;
     }
+    for (const void *p : c.pending)
+        if (p) return st->fail(BAPIPE_E_DEVICE, "backward: a residual gradient was left for a conv that never took it");
     if (want_dx && !c.dx_direct) {
         if (nhwc)
             HIPCHK(nhwc_repad(dt, st->gptr(0), dx_dev, (size_t)st->mb * In.H * In.W, In.Cp, In.C, s));
@@ -1699,6 +1729,7 @@ int bapipe_profile_layers(bapipe_stage_t *st, int warmup, int iters, bapipe_laye
         for (int k = 0; k < warmup + iters && rc == BAPIPE_OK; ++k) {
             if (k == warmup) (void)hipEventRecord(e0, s);
             bc.written.assign(st->tensors.size(), 0);
+            bc.pending.assign(st->tensors.size(), nullptr);
             rc = layer_backward(st, i, bc);
         }
         (void)hipEventRecord(e1, s);
