@@ -139,8 +139,10 @@ size_t bn_workspace(int rows, int C);
 // stats: [2][C] floats (mean, invstd)
 // pre_chunks > 0: the workspace already holds [2][pre_chunks][C] partial sums of x and x^2 (left there by
 // the kernel that produced x) and the first pass over x is skipped
+// res: the other input of a residual ADD fed only by this layer - y = [relu_sum](round(bn(x)) + res) in one pass
 hipError_t bn_fwd(int dt, const void *x, const float *gamma, const float *beta, float eps, void *y,
-                  float *stats, int relu, int rows, int C, void *workspace, hipStream_t s, int pre_chunks = 0);
+                  float *stats, int relu, int rows, int C, void *workspace, hipStream_t s, int pre_chunks = 0,
+                  const void *res = nullptr, int relu_sum = 0);
 // pre_chunks > 0: the workspace already holds [2][pre_chunks][C] partial sums of dy and dy*xhat
 hipError_t bn_bwd(int dt, const void *x, const void *dy, const float *gamma, const float *stats,
                   void *dx, float *dgamma, float *dbeta, GradEpi epi, int rows, int C,

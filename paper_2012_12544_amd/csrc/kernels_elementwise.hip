@@ -519,8 +519,11 @@ constexpr int BN_ROWS_PER_THREAD = 2;
 template <class T, int V>
 __global__ void k_bn_apply(const T *__restrict__ x, const float *__restrict__ gamma,
                            const float *__restrict__ beta, const float *__restrict__ stats,
-                           T *__restrict__ y, int relu, int rows, int C, ColPlan p)
+                           T *__restrict__ y, int relu, int rows, int C, ColPlan p,
+                           const T *__restrict__ res, int relu_sum)
 {
+    // res: the other input of a residual ADD that only this layer's output feeds - y = [relu](q(bn(x)) + res),
+    // the normalised value rounded to storage first, as the stand-alone ADD would have read it
     const int cx = threadIdx.x % p.CGB, ry = threadIdx.x / p.CGB;
     const int cg = blockIdx.x * p.CGB + cx;
     if (ry >= p.RY || cg >= p.CV) return;
@@ -537,11 +540,12 @@ __global__ void k_bn_apply(const T *__restrict__ x, const float *__restrict__ ga
     const int r0 = blockIdx.y * (p.RY * BN_ROWS_PER_THREAD);
     int r1 = r0 + p.RY * BN_ROWS_PER_THREAD;
     if (r1 > rows) r1 = rows;
-    vec_t<T, V> a[BN_ROWS_PER_THREAD];
+    vec_t<T, V> a[BN_ROWS_PER_THREAD], b[BN_ROWS_PER_THREAD];
 #pragma unroll
     for (int u = 0; u < BN_ROWS_PER_THREAD; ++u) {            // all loads of the thread first
         const int r = r0 + ry + u * p.RY;
         a[u] = xv[(size_t)(r < r1 ? r : r1 - 1) * p.CV + cg];
+        if (res) b[u] = reinterpret_cast<const vec_t<T, V> *>(res)[(size_t)(r < r1 ? r : r1 - 1) * p.CV + cg];
     }
 #pragma unroll
     for (int u = 0; u < BN_ROWS_PER_THREAD; ++u) {
@@ -553,6 +557,10 @@ __global__ void k_bn_apply(const T *__restrict__ x, const float *__restrict__ ga
             float xh = (to_f32(a[u].e[j]) - mu[j]) * inv[j];
             float v = ga[j] * xh + be[j];
             if (relu) v = fmaxf(v, 0.0f);
+            if (res) {
+                v = round_to<T>(v) + to_f32(b[u].e[j]);
+                if (relu_sum) v = fmaxf(v, 0.0f);
+            }
             o.e[j] = from_f32<T>(v);
         }
         yv[(size_t)r * p.CV + cg] = o;
@@ -696,7 +704,7 @@ template <class T, int V, int R>
 __global__ __launch_bounds__(OP_NT) void k_bn_fwd_onepass(const T *__restrict__ x, const float *__restrict__ gamma,
                                                           const float *__restrict__ beta, float eps,
                                                           T *__restrict__ y, float *__restrict__ stats, int relu,
-                                                          int rows, int C)
+                                                          int rows, int C, const T *__restrict__ res, int relu_sum)
 {
     __shared__ float wpart[OP_WAVES][2 * V];
     __shared__ double tot[2 * V];
@@ -749,12 +757,17 @@ __global__ __launch_bounds__(OP_NT) void k_bn_fwd_onepass(const T *__restrict__ 
     for (int u = 0; u < R; ++u) {
         const int r = threadIdx.x + u * OP_NT;
         if (r >= rows) break;
-        vec_t<T, V> o;
+        vec_t<T, V> o, b;
+        if (res) b = reinterpret_cast<const vec_t<T, V> *>(res)[(size_t)r * CV + cg];
 #pragma unroll
         for (int j = 0; j < V; ++j) {
             float xh = (to_f32(a[u].e[j]) - mu[j]) * inv[j];
             float v = ga[j] * xh + be[j];
             if (relu) v = fmaxf(v, 0.0f);
+            if (res) {                                   // residual ADD behind this layer, see k_bn_apply
+                v = round_to<T>(v) + to_f32(b.e[j]);
+                if (relu_sum) v = fmaxf(v, 0.0f);
+            }
             o.e[j] = from_f32<T>(v);
         }
         yv[(size_t)r * CV + cg] = o;
@@ -1350,17 +1363,19 @@ static bool bn_onepass(int Vsel, int rows, int C) { return Vsel > 1 && rows <= O
 constexpr int OP_V = 4;
 #define BN_FWD_OP(T_, R_)                                                                                        \
     hipLaunchKernelGGL((k_bn_fwd_onepass<T_, OP_V, R_>), dim3(C / OP_V), dim3(OP_NT), 0, s, (const T_ *)x, gamma, \
-                       beta, eps, (T_ *)y, stats, relu, rows, C)
+                       beta, eps, (T_ *)y, stats, relu, rows, C, (const T_ *)res, relu_sum)
 #define BN_BWD_OP(T_, R_)                                                                                        \
     hipLaunchKernelGGL((k_bn_bwd_onepass<T_, OP_V, R_>), dim3(C / OP_V), dim3(OP_NT), 0, s, (const T_ *)x,        \
                        (const T_ *)dy, gamma, stats, (T_ *)dx, (const T_ *)epi.gate, epi.accum, dgamma, dbeta,    \
                        1.0f / (float)rows, rows, C)
 
 hipError_t bn_fwd(int dt, const void *x, const float *gamma, const float *beta, float eps, void *y,
-                  float *stats, int relu, int rows, int C, void *workspace, hipStream_t s, int pre_chunks)
+                  float *stats, int relu, int rows, int C, void *workspace, hipStream_t s, int pre_chunks,
+                  const void *res, int relu_sum)
 {
     if (rows <= 0 || C <= 0) return hipSuccess;
-    int Vsel = col_vec(dt, C, x, y);
+    if (res && relu) return hipErrorInvalidValue;          // the layer's own ReLU and a residual behind it exclude each other
+    int Vsel = col_vec(dt, C, x, y, res);
     float *part = (float *)workspace;
     if (pre_chunks > 0) {                 // statistics partials came with x: final pass and normalisation only
         hipLaunchKernelGGL(k_bn_stat_final, dim3(final_blocks(C)), dim3(TPB), 0, s, part, pre_chunks, C, rows, eps, stats);
@@ -1368,7 +1383,7 @@ hipError_t bn_fwd(int dt, const void *x, const float *gamma, const float *beta, 
             ColPlan p = col_plan(rows, C, V);
             const int rpb = p.RY * BN_ROWS_PER_THREAD;
             hipLaunchKernelGGL((k_bn_apply<T, V>), dim3(p.gx, (rows + rpb - 1) / rpb), dim3(TPB), 0, s, (const T *)x,
-                               gamma, beta, stats, (T *)y, relu, rows, C, p);
+                               gamma, beta, stats, (T *)y, relu, rows, C, p, (const T *)res, relu_sum);
         });
         return hipGetLastError();
     }
@@ -1385,7 +1400,7 @@ hipError_t bn_fwd(int dt, const void *x, const float *gamma, const float *beta, 
                            eps, stats);
         const int rpb = p.RY * BN_ROWS_PER_THREAD;
         hipLaunchKernelGGL((k_bn_apply<T, V>), dim3(p.gx, (rows + rpb - 1) / rpb), dim3(TPB), 0, s, (const T *)x,
-                           gamma, beta, stats, (T *)y, relu, rows, C, p);
+                           gamma, beta, stats, (T *)y, relu, rows, C, p, (const T *)res, relu_sum);
     });
     return hipGetLastError();
 }

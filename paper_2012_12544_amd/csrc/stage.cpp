@@ -90,6 +90,7 @@ struct Layer {
     // with the filter is taken at the output's resolution into the workspace (at up_off) and spread from there
     bool strided_1x1 = false;
     size_t up_off = 0;
+    int fuse_add = -1;     // batch-norm: the residual ADD (layer index) whose sum this layer's normalisation pass stores
     // LSTM: per in-flight micro-batch the slot keeps the gates and cell states (float), the delayed
     // copy of h that the recurrent products read, the buffer shared by the input projection
     // (forward) and the pre-activation gradients (backward) and the cell-gradient carry
@@ -573,12 +574,21 @@ int layer_forward(bapipe_stage *st, int li, const FwdCtx &c)
         // the partials of the producing conv are only there when that conv has just run (not when the
         // profiler times this layer alone)
         const int pre = (L.stats_given && !c.profiling) ? st->layers[li - 1].stat_chunks : 0;
+        if (L.fuse_add >= 0) {                       // y of the ADD behind this layer, in the same pass
+            const Layer &S = st->layers[L.fuse_add];
+            const void *other = in_ptr(st, S.a == L.o ? S.b : S.a, c);
+            HIPCHK(bn_fwd(dt, a, L.w, L.bias, L.d.eps, st->tptr(S.o, c.mbid), (float *)(st->slot(c.mbid) + L.aux_off), 0,
+                          st->mb * A.H * A.W, A.C, st->work, s, pre, other, S.d.fuse_relu));
+            st->tap_end(tp, 0.0, 4.0 * A.bytes());                               // x twice, the other summand, y
+            break;
+        }
         HIPCHK(bn_fwd(dt, a, L.w, L.bias, L.d.eps, o, (float *)(st->slot(c.mbid) + L.aux_off), L.d.fuse_relu,
                       st->mb * A.H * A.W, A.C, st->work, s, pre));
         st->tap_end(tp, 0.0, 3.0 * A.bytes());                                   // read x twice, write y
         break;
     }
     case BAPIPE_ADD: {
+        if (L.fused) break;                       // stored by the batch-norm that feeds it
         const bool tp = st->tap_begin(BAPIPE_KC_ELEMENTWISE);
         HIPCHK(add_fwd(dt, a, in_ptr(st, L.b, c), o, L.d.fuse_relu, O.elems, s));
         st->tap_end(tp, 0.0, 3.0 * O.bytes());
@@ -1150,6 +1160,19 @@ int bapipe_stage_create(const bapipe_layer_desc_t *layers, int n_layers, int mic
         if (!conv3x3_halo_supported(fwd_geom(st, L)) || (O.H & 1) || (O.W & 1)) continue;
         L.fuse_pool = O.consumers[0];
         P.fused = true;
+    }
+    // batch-norm -> residual ADD: where the later-produced summand is a batch-norm output (no ReLU of its own) that
+    // only the ADD reads, that layer's normalisation pass stores the sum and the ADD launches nothing
+    for (int i = 0; i < n_layers; ++i) {
+        Layer &S = st->layers[i];
+        if (S.d.kind != BAPIPE_ADD) continue;
+        const int t = S.a > S.b ? S.a : S.b;                  // the summand produced last
+        if (t == 0 || root_of(t) != t || root_of(S.a) != S.a || root_of(S.b) != S.b) continue;
+        Layer &Bn = st->layers[t - 1];
+        const Tensor &T = st->tensors[t];
+        if (Bn.d.kind != BAPIPE_BATCHNORM2D || Bn.d.fuse_relu || T.consumers.size() != 1 || T.stashed || t == last_t) continue;
+        Bn.fuse_add = i;
+        S.fused = true;
     }
     size_t work = 256;
     for (int i = 0; i < n_layers; ++i) {
