@@ -204,7 +204,12 @@ int bapipe_stage_step(bapipe_stage_t *st, float lr);
  * kernels in isolation on scratch data, `warmup` untimed then `iters` timed repetitions,
  * timed with HIP events on the stage's stream.  Does not change weights, gradients, stash
  * or schedule state; E_ORDER if micro-batches are in flight.  out: host array of `cap`
- * records; *n receives the number of layers; E_INVALID if cap < n_layers. */
+ * records; *n receives the number of layers; E_INVALID if cap < n_layers.
+ * Where the stage runs two layers as one kernel, the time is reported on the layer that launches
+ * it and the other reports 0: a max-pool done in the epilogue of the conv before it (forward),
+ * a residual ADD whose sum is stored by the batch-norm before it (forward).  Linear layers, whose
+ * weight gradient the stage defers to `step`, are timed with that GEMM run per micro-batch: an
+ * upper bound for what the schedule pays. */
 int bapipe_profile_layers(bapipe_stage_t *st, int warmup, int iters,
                           bapipe_layer_profile_t *out, int cap, int *n);
 
