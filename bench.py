@@ -18,7 +18,7 @@ step (mean of the K timed steps and the median of their per-step event times), T
                    on this very GPU (register-resident MFMA loop, streaming copy)
   per_config     - the other configurations of the benchmark suite, each timed the same way for a
                    few steps in the same process: ms per step, samples/s, TFLOP/s, dominant class
-  measured_peaks - what bapipe_measure_peaks returns on this GPU
+  measured_peaks - what bapipe_measure_peaks and bapipe_measure_lds return on this GPU
   cpu_baseline   - the CPU oracle timed on the host cores on a bounded sample of the workload
 """
 import argparse
@@ -263,9 +263,10 @@ def main():
     B.load()
     dev = "cuda:0"
     torch.cuda.init()
-    peaks = (None, None)
+    peaks, lds = (None, None), (None, None)
     if not a.no_peaks:
         peaks = B.bapipe_measure_peaks(torch.cuda.current_stream().cuda_stream)
+        lds = B.bapipe_measure_lds(torch.cuda.current_stream().cuda_stream)
 
     shape = {}
     if a.micro_batch:
@@ -309,7 +310,8 @@ def main():
     }
     if peaks[0]:
         out["measured_peaks"] = {"mfma_bf16_tflops": round(peaks[0], 1), "copy_gbs": round(peaks[1], 1),
-                                 "frac_of_measured_mfma_peak": round(head["tflops"] / peaks[0], 4)}
+                                 "frac_of_measured_mfma_peak": round(head["tflops"] / peaks[0], 4),
+                                 "lds_read_b128_tbs": round(lds[0], 1), "lds_read_b64_tr_tbs": round(lds[1], 1)}
     w.close()
 
     if not a.no_per_config:

@@ -276,6 +276,15 @@ int bapipe_stage_kernel_timing_read(bapipe_stage_t *st, double *total_ms, uint64
  * of the call, runs on hip_stream and synchronises it.  E_OOM / E_DEVICE on failure. */
 int bapipe_measure_peaks(void *hip_stream, double *mfma_bf16_tflops, double *copy_gbs);
 
+/* The third ceiling of the MFMA kernels, which feed the matrix cores from LDS: the rate at which all
+ * compute units together read LDS (TB/s, conflict-free addresses, nothing leaves the unit) with
+ * ds_read_b128, the fragment load of the forward / input-gradient kernels, and with the transposing
+ * ds_read_b64_tr_b16, the fragment load of the weight-gradient kernels (both operands of a weight
+ * gradient are contracted over pixels, the dimension that is not contiguous in memory).  A kernel that
+ * reads B bytes of fragments per MFMA cannot run the matrix cores above rate / B.  Runs on
+ * hip_stream and synchronises it; E_OOM / E_DEVICE on failure. */
+int bapipe_measure_lds(void *hip_stream, double *read_b128_tbs, double *read_b64_tr_tbs);
+
 /* Message of the last failed call on this handle (or of the last failed create when st is
  * NULL); valid until the next call on the same handle. */
 const char *bapipe_last_error(const bapipe_stage_t *st);

@@ -26,7 +26,7 @@ EXPORTS = [
     "bapipe_profile_layers", "bapipe_profile_sweep", "bapipe_stage_set_params", "bapipe_stage_get_params",
     "bapipe_stage_get_grads", "bapipe_stage_get_pool_indices", "bapipe_stage_get_loss",
     "bapipe_stage_stash_bytes", "bapipe_last_error", "bapipe_stage_destroy",
-    "bapipe_stage_kernel_timing", "bapipe_stage_kernel_timing_read", "bapipe_measure_peaks",
+    "bapipe_stage_kernel_timing", "bapipe_stage_kernel_timing_read", "bapipe_measure_peaks", "bapipe_measure_lds",
     "bapipe_schedule_cost", "bapipe_schedule_choose", "bapipe_partition",
 ]
 PLAN_1F1B_AS, PLAN_FBP_AS, PLAN_1F1B_SNO, PLAN_1F1B_SO = range(4)
@@ -97,6 +97,7 @@ def load():
     lib.bapipe_stage_kernel_timing_read.argtypes = [vp, ct.POINTER(ct.c_double), ct.POINTER(ct.c_uint64),
                                                     ct.POINTER(ct.c_double), ct.POINTER(ct.c_double)]
     lib.bapipe_measure_peaks.argtypes = [vp, ct.POINTER(ct.c_double), ct.POINTER(ct.c_double)]
+    lib.bapipe_measure_lds.argtypes = [vp, ct.POINTER(ct.c_double), ct.POINTER(ct.c_double)]
     lib.bapipe_last_error.argtypes = [vp]
     lib.bapipe_last_error.restype = ct.c_char_p
     lib.bapipe_stage_destroy.argtypes = [vp]
@@ -262,6 +263,13 @@ def bapipe_measure_peaks(stream=0):
     tf, gb = ct.c_double(0), ct.c_double(0)
     _check(load().bapipe_measure_peaks(stream, ct.byref(tf), ct.byref(gb)))
     return tf.value, gb.value
+
+
+def bapipe_measure_lds(stream=0):
+    """(TB/s all compute units read LDS with ds_read_b128, with ds_read_b64_tr_b16) on the current device."""
+    a, b = ct.c_double(0), ct.c_double(0)
+    _check(load().bapipe_measure_lds(stream, ct.byref(a), ct.byref(b)))
+    return a.value, b.value
 
 
 def bapipe_stage_destroy(h):

@@ -533,3 +533,9 @@ def test_measured_peaks_are_plausible_and_below_the_published_ones():
     one = ct.c_double(0)
     assert B.load().bapipe_measure_peaks(0, None, ct.byref(one)) == B.E_INVALID
     assert B.load().bapipe_measure_peaks(0, ct.byref(one), None) == B.E_INVALID
+    # LDS read rates: 256 units x 128 bytes per clock x 2.4 GHz = 78.6 TB/s is what the instruction set documents
+    # for a unit; the 64-bit transposing read moves half as much per instruction and cannot be faster than the
+    # 128-bit read
+    wide, tr = B.bapipe_measure_lds()
+    assert 20.0 < tr <= 1.05 * wide < 200.0, (wide, tr)
+    assert B.load().bapipe_measure_lds(0, None, ct.byref(one)) == B.E_INVALID
