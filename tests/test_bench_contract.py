@@ -37,3 +37,17 @@ def test_one_json_line_with_roofline_and_cpu_baseline():
     assert abs(roof["frac"] - roof["achieved"] / roof["peak"]) < 1e-3
     cb = d["cpu_baseline"]
     assert cb["kind"] == "oracle" and cb["value"] > 0 and cb["cores"] >= 1 and "sample" in cb
+
+
+def test_cpu_baseline_samples_whole_micro_batches():
+    """The oracle leg of the benchmark: a sample below one micro-batch takes the first samples of micro-batch 0, a
+    larger one whole micro-batches in schedule order; the rate counts exactly the samples that were run."""
+    sys.path.insert(0, ROOT)
+    import bench
+    from stage_inputs import configs as C
+    st = C.FULL["tiny"]()
+    mb = st["micro_batch"]
+    part = bench.cpu_baseline(st, mb - 1)
+    assert part["kind"] == "oracle" and part["value"] > 0 and ("%d samples of micro-batch 0" % (mb - 1)) in part["sample"]
+    two = bench.cpu_baseline(st, 2 * mb)
+    assert ("micro-batches 0..1 (%d samples)" % (2 * mb)) in two["sample"] and two["cores"] >= 1
