@@ -234,6 +234,19 @@ __global__ __launch_bounds__(256, halo_cfg::BLOCKS_PER_CU) void k_conv3x3_halo(c
     WAIT_VMCNT(0);
     __syncthreads();
 
+    // gradient epilogue: the ReLU-gate rows are requested here, after the last MFMA (the main loop has no registers to
+    // spare for an earlier request), so that they travel while the accumulators are parked in the staging tile
+    chunk16 glate[UNITS];
+    if (is_grad && gate) {
+#pragma unroll
+        for (int it = 0; it < UNITS; ++it) {
+            const int u = tid + it * 256;
+            const int pj = u / CH8, c8i = u % CH8;
+            const size_t p = (size_t)(n * H + Y0 + (pj >> 4)) * W + X0 + (pj & 15);
+            glate[it] = *reinterpret_cast<const chunk16 *>(gate + p * Co + co0 + c8i * 8);
+        }
+    }
+
     // ---- epilogue: every wave parks its 64 pixels x BC channels in LDS (bf16, bias / ReLU applied),
     // one barrier, then the block streams the patch out as 16-byte coalesced rows
 #pragma unroll
@@ -258,18 +271,6 @@ __global__ __launch_bounds__(256, halo_cfg::BLOCKS_PER_CU) void k_conv3x3_halo(c
                 c8[1] = (uint32_t)f32_to_bf16_bits(v2) | ((uint32_t)f32_to_bf16_bits(v3) << 16);
                 *reinterpret_cast<chunk8 *>(sO + prow * SROW + col) = c8;
             }
-        }
-    }
-    // gradient epilogue: the ReLU-gate rows are requested here, where the accumulators are dead (the main loop has no
-    // registers to spare for an earlier request), so that they travel while the staging tile is completed
-    chunk16 glate[UNITS];
-    if (is_grad && gate) {
-#pragma unroll
-        for (int it = 0; it < UNITS; ++it) {
-            const int u = tid + it * 256;
-            const int pj = u / CH8, c8i = u % CH8;
-            const size_t p = (size_t)(n * H + Y0 + (pj >> 4)) * W + X0 + (pj & 15);
-            glate[it] = *reinterpret_cast<const chunk16 *>(gate + p * Co + co0 + c8i * 8);
         }
     }
     __syncthreads();
