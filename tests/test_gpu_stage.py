@@ -233,6 +233,25 @@ def test_residual_block(dtype):
 
 
 @pytest.mark.parametrize("dtype", DT)
+@pytest.mark.parametrize("layout", [B.NCHW, B.NHWC])
+@pytest.mark.parametrize("hw,mb", [((6, 5), 3), ((30, 28), 3)])       # one-launch batch-norm; above its 2048 rows
+def test_residual_unit_on_the_stage_input(dtype, layout, hw, mb):
+    """conv 1x1 -> batch-norm -> (+ stage input) -> ReLU, then a second unit on that sum.  In bf16 the sum of each
+    unit is stored by its batch-norm's normalisation pass, and the ADD's share of the gradient of the unit's input is
+    added by the 1x1 conv's input-gradient epilogue instead of being copied first - for the first unit that input is
+    the STAGE input, whose buffers (NHWC) are the caller's own."""
+    def build(b):
+        c1 = b.conv(16, 16, 1, bias=0, src=-1)
+        n1 = b.bn(16)
+        s1 = b.addl(n1, -1)
+        b.conv(16, 16, 1, bias=0, src=s1)
+        n2 = b.bn(16)
+        b.addl(n2, s1)
+    st = single(build, 16, hw, dtype, micro_batch=mb, n_micro=3, name="residual-on-input")
+    compare_minibatch(st, layout=layout, verbose="residual units on the stage input, layout %d, rows %d" % (layout, mb * hw[0] * hw[1]))
+
+
+@pytest.mark.parametrize("dtype", DT)
 def test_classifier(dtype):
     st = C.vgg16_classifier(c=8, hw=3, hidden=40, classes=13, micro_batch=5, n_micro=3, dtype=dtype)
     for layout in (B.NCHW, B.NHWC):
