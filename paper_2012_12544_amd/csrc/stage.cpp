@@ -1739,7 +1739,7 @@ int bapipe_profile_layers(bapipe_stage_t *st, int warmup, int iters, bapipe_laye
         (void)hipEventRecord(e1, s);
         if (hipEventSynchronize(e1) != hipSuccess) { rc = st->fail(BAPIPE_E_DEVICE, "profile: event sync failed"); break; }
         (void)hipEventElapsedTime(&ms, e0, e1);
-        out[i].fwd_ms = ms / iters;
+        out[i].fwd_ms = L.fused ? 0.0 : ms / iters;          // done by the layer before it: only the empty event pair was timed
 
         BwdCtx bc;
         bc.mbid = 0; bc.x_direct = bc.dy_direct = nullptr; bc.dx_direct = nullptr; bc.labels = nullptr;

@@ -287,6 +287,23 @@ def test_profile_feeds_the_partition_explorer():
     assert total / 2 * (1 - 1e-9) <= rep["bottleneck_ms"] <= total and math.isclose(rep["ideal_stage_ms"], total / 2, rel_tol=1e-9)
 
 
+def test_profile_reports_layers_that_share_a_kernel_on_the_launching_layer():
+    """Layers the stage runs as one kernel: the time is on the layer that launches it, the other reports 0 forward
+    time - the max-pool behind a halo conv (bf16), the residual ADD behind a batch-norm."""
+    st = C.vgg16_stage1(c1=64, c2=64, hw=32, micro_batch=2, n_micro=2)
+    g = GpuStage(st, gen.all_params(st))
+    prof = B.bapipe_profile_layers(g.h, 1, 2, len(st["layers"]))
+    g.close()
+    pools = [i for i, L in enumerate(st["layers"]) if L["kind"] == C.MAXPOOL2D]
+    assert pools and all(prof[i]["fwd_ms"] == 0.0 and prof[i]["bwd_ms"] > 0.0 and prof[i - 1]["fwd_ms"] > 0.0 for i in pools)
+    st = C.resnet50_stage(cin=16, mid3=8, mid4=8, hw=8, n3=2, n4=1, micro_batch=3, n_micro=2)
+    g = GpuStage(st, gen.all_params(st))
+    prof = B.bapipe_profile_layers(g.h, 1, 2, len(st["layers"]))
+    g.close()
+    adds = [i for i, L in enumerate(st["layers"]) if L["kind"] == C.ADD]
+    assert adds and all(prof[i]["fwd_ms"] == 0.0 and prof[i - 1]["fwd_ms"] > 0.0 for i in adds)
+
+
 @pytest.mark.parametrize("net", ["vgg16_full", "resnet50_full"])
 def test_whole_network_profile_is_partitioned_into_four_stages(net):
     """The loop the profiler exists for (Sec. III-A / III-C): profile every layer of a whole network
